@@ -1,0 +1,191 @@
+"""Pins of the oracle's attention, positional encoding and EMA scores.
+
+The checks below are dense numpy formulas (matrix softmax, RoPE written as a complex
+multiplication) applied to special cases where the method has a textbook definition:
+full causal attention, sink + sliding window, and brute force over the cache membership.
+"""
+import numpy as np
+import pytest
+
+from oracle import OracleConfig, OracleSeq
+
+
+def rope_complex(x, pos, base):
+    """RoPE on the last axis of x at integer positions pos (broadcast over leading axes):
+    the pair (x_i, x_{i+d/2}) is the complex number x_i + 1j*x_{i+d/2}, multiplied by
+    exp(1j * pos * base**(-2i/d))."""
+    d = x.shape[-1]
+    half = d // 2
+    z = x[..., :half] + 1j * x[..., half:]
+    theta = base ** (-2.0 * np.arange(half) / d)
+    z = z * np.exp(1j * np.asarray(pos, dtype=np.float64)[..., None] * theta)
+    return np.concatenate([z.real, z.imag], axis=-1)
+
+
+def dense_attention(q, qpos, keys, kpos, vals, visible, base, scale):
+    """q [m,d] at qpos [m]; keys/vals [n,d] at kpos [n]; visible [m,n] bool -> (out [m,d], P [m,n])."""
+    s = rope_complex(q, qpos, base) @ rope_complex(keys, kpos, base).T * scale
+    s = np.where(visible, s, -np.inf)
+    s = s - s.max(axis=1, keepdims=True)
+    p = np.exp(s)
+    p /= p.sum(axis=1, keepdims=True)
+    return p @ vals, p
+
+
+def _rand(rng, *shape):
+    return rng.standard_normal(shape).astype(np.float32)
+
+
+def test_full_causal_attention_before_any_discard(oracle_mod):
+    """While nothing has been discarded the cache order is the original order and the PE index
+    is the original index (Section 3.1), so the outputs are ordinary causal attention (Eq. 1)."""
+    rng = np.random.default_rng(10)
+    Hq, Hkv, d, S, Q = 4, 2, 16, 48, 8
+    cfg = OracleConfig(n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, n_sink=4, cascade_sizes=[24, 24],
+                       ema_beta=0.9, rope_base=10000.0)
+    o = OracleSeq(cfg)
+    q, k, v = _rand(rng, S, Hq, d), _rand(rng, S, Hkv, d), _rand(rng, S, Hkv, d)
+    outs = np.concatenate([o.chunk(q[s:s + Q], k[s:s + Q], v[s:s + Q]) for s in range(0, S, Q)])
+    assert len(o.discard_log(0)) == 0
+    pos = np.arange(S)
+    causal = pos[:, None] >= pos[None, :]
+    for h in range(Hq):
+        g = h // (Hq // Hkv)
+        ref, _ = dense_attention(q[:, h].astype(np.float64), pos, k[:, g].astype(np.float64), pos,
+                                 v[:, g].astype(np.float64), causal, 10000.0, d ** -0.5)
+        np.testing.assert_allclose(outs[:, h], ref, rtol=1e-10, atol=1e-12)
+
+
+@pytest.mark.parametrize("Q", [1, 5])
+def test_one_cascade_equals_streaming_llm(oracle_mod, Q):
+    """One cascade that accepts everything = sink cache (Section 3.1): each chunk attends to the
+    first alpha tokens plus the last |C| tokens before the chunk (Eq. 3), with PE = cache index,
+    plus its own causal part (Fig. 4)."""
+    rng = np.random.default_rng(11)
+    H, d, S, alpha, C = 2, 8, 60, 3, 9
+    cfg = OracleConfig(n_q_heads=H, n_kv_heads=H, head_dim=d, n_sink=alpha, cascade_sizes=[C],
+                       ema_beta=0.5, rope_base=100.0)
+    o = OracleSeq(cfg)
+    q, k, v = _rand(rng, S, H, d), _rand(rng, S, H, d), _rand(rng, S, H, d)
+    for s in range(0, S, Q):
+        out = o.chunk(q[s:s + Q], k[s:s + Q], v[s:s + Q])
+        cached = list(range(min(s, alpha))) + list(range(max(alpha, s - C), s))
+        members = np.array(cached + list(range(s, s + Q)))
+        n = len(cached)
+        kpos = np.arange(len(members))
+        vis = np.concatenate([np.ones((Q, n), bool), np.tril(np.ones((Q, Q), bool))], axis=1)
+        for h in range(H):
+            ref, _ = dense_attention(q[s:s + Q, h].astype(np.float64), n + np.arange(Q),
+                                     k[members, h].astype(np.float64), kpos,
+                                     v[members, h].astype(np.float64), vis, 100.0, d ** -0.5)
+            np.testing.assert_allclose(out[:, h], ref, rtol=1e-10, atol=1e-12)
+
+
+def test_brute_force_over_membership_and_ema(oracle_mod):
+    """Brute force: for every chunk take the membership the policy produced, build the dense
+    masked attention over those tokens at PE = cache index (Eq. 2, Section 3.1), and check
+    outputs, the EMA increments (Section 3.1 "Token Selection": one step per query row, so
+    row i of a chunk of Q weighs beta^(Q-1-i)(1-beta), the coefficients of Alg. 3), the max
+    reduction over the query heads of a group (Appendix "Head Policy"), and the updated scores."""
+    rng = np.random.default_rng(12)
+    Hq, Hkv, d, S, Q, beta, base = 4, 2, 8, 96, 6, 0.8, 50.0
+    G = Hq // Hkv
+    cfg = OracleConfig(n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, n_sink=2, cascade_sizes=[4, 4, 4],
+                       ema_beta=beta, rope_base=base)
+    o = OracleSeq(cfg)
+    q, k, v = _rand(rng, S, Hq, d), _rand(rng, S, Hkv, d), _rand(rng, S, Hkv, d)
+    w = beta ** (Q - 1 - np.arange(Q)) * (1 - beta)
+    for s in range(0, S, Q):
+        before = [o.state(g) for g in range(Hkv)]
+        out = o.chunk(q[s:s + Q], k[s:s + Q], v[s:s + Q])
+        for g in range(Hkv):
+            cached = before[g].ids
+            n = len(cached)
+            members = np.concatenate([cached, np.arange(s, s + Q)])
+            vis = np.concatenate([np.ones((Q, n), bool), np.tril(np.ones((Q, Q), bool))], axis=1)
+            deltas = []
+            for hh in range(G):
+                h = g * G + hh
+                ref, P = dense_attention(q[s:s + Q, h].astype(np.float64), n + np.arange(Q),
+                                         k[members, g].astype(np.float64), np.arange(n + Q),
+                                         v[members, g].astype(np.float64), vis, base, d ** -0.5)
+                np.testing.assert_allclose(out[:, h], ref, rtol=1e-10, atol=1e-12)
+                dh = w @ P
+                # every row of P sums to one, so the increments of one head sum to 1 - beta^Q
+                assert abs(dh.sum() - (1 - beta ** Q)) < 1e-12
+                deltas.append(dh)
+            delta = np.max(deltas, axis=0)
+            np.testing.assert_allclose(o.last_delta(g), delta, rtol=1e-10, atol=1e-15)
+            # scores after the chunk, for every token that is still cached
+            after = o.state(g)
+            mu_expect = {int(i): beta ** Q * m + dl for i, m, dl in zip(cached, before[g].mu, delta[:n])}
+            mu_expect.update({s + i: delta[n + i] for i in range(Q)})
+            for i, m in zip(after.ids, after.mu):
+                assert abs(m - mu_expect[int(i)]) <= 1e-12 * max(1.0, abs(m)), (s, g, i)
+    assert sum(len(o.discard_log(g)) for g in range(Hkv)) > 50
+
+
+def test_mean_head_reduction(oracle_mod):
+    """The mean reduction over the query heads of a group (Appendix "Head Policy")."""
+    rng = np.random.default_rng(13)
+    Hq, Hkv, d, Q, beta = 3, 1, 4, 5, 0.7
+    cfg = OracleConfig(n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, n_sink=1, cascade_sizes=[8],
+                       ema_beta=beta, rope_base=10.0, head_reduce=1)
+    o = OracleSeq(cfg)
+    q, k, v = _rand(rng, Q, Hq, d), _rand(rng, Q, Hkv, d), _rand(rng, Q, Hkv, d)
+    o.chunk(q, k, v)
+    w = beta ** (Q - 1 - np.arange(Q)) * (1 - beta)
+    vis = np.tril(np.ones((Q, Q), bool))
+    deltas = [w @ dense_attention(q[:, h].astype(np.float64), np.arange(Q), k[:, 0].astype(np.float64),
+                                  np.arange(Q), v[:, 0].astype(np.float64), vis, 10.0, 0.5)[1] for h in range(Hq)]
+    np.testing.assert_allclose(o.last_delta(0), np.mean(deltas, axis=0), rtol=1e-10)
+
+
+def test_decode_step_is_single_row_ema(oracle_mod):
+    """A decode step (Eq. 2) is a chunk of one: mu <- gamma*mu + (1-gamma)*s (Section 3.1)."""
+    rng = np.random.default_rng(14)
+    H, d, beta = 1, 4, 0.6
+    cfg = OracleConfig(n_q_heads=H, n_kv_heads=H, head_dim=d, n_sink=1, cascade_sizes=[16],
+                       ema_beta=beta, rope_base=10.0)
+    o = OracleSeq(cfg)
+    mu = {}
+    ks, vs = [], []
+    for t in range(10):
+        q, k, v = _rand(rng, H, d), _rand(rng, H, d), _rand(rng, H, d)
+        ks.append(k[0]); vs.append(v[0])
+        out = o.decode(q, k, v)
+        K, V = np.array(ks, dtype=np.float64), np.array(vs, dtype=np.float64)
+        ref, P = dense_attention(q.astype(np.float64), np.array([t]), K, np.arange(t + 1), V,
+                                 np.ones((1, t + 1), bool), 10.0, 0.5)
+        np.testing.assert_allclose(out, ref, rtol=1e-10, atol=1e-12)
+        for j in range(t + 1):
+            mu[j] = beta * mu.get(j, 0.0) + (1 - beta) * P[0, j]
+        st = o.state(0)
+        np.testing.assert_allclose(st.mu, [mu[int(i)] for i in st.ids], rtol=1e-12)
+
+
+def test_rope_relative_shift(oracle_mod):
+    """RoPE scores depend on position differences only: adding sink tokens in front that get
+    (numerically) no attention shifts every index and must leave the outputs unchanged."""
+    rng = np.random.default_rng(15)
+    H, d, S = 1, 8, 12
+    q, k, v = _rand(rng, S, H, d), _rand(rng, S, H, d), _rand(rng, S, H, d)
+    base = OracleConfig(n_q_heads=H, n_kv_heads=H, head_dim=d, n_sink=0, cascade_sizes=[64],
+                        ema_beta=0.9, rope_base=1000.0)
+    o1 = OracleSeq(base)
+    ref = o1.chunk(q, k, v)
+    # the same stream behind 5 leading tokens with zero keys (logit 0) and zero values: the
+    # real tokens keep their mutual logits, and the mass the zero keys take is known densely.
+    o2 = OracleSeq(base)
+    lead = 5
+    zk = np.zeros((lead, H, d), np.float32)
+    o2.chunk(_rand(rng, lead, H, d), zk, zk)
+    out = o2.chunk(q, k, v)
+    pos = np.arange(S)
+    _, P = dense_attention(q[:, 0].astype(np.float64), lead + pos,
+                           np.concatenate([zk[:, 0], k[:, 0]]).astype(np.float64), np.arange(lead + S),
+                           np.concatenate([zk[:, 0], v[:, 0]]).astype(np.float64),
+                           np.concatenate([np.ones((S, lead), bool), np.tril(np.ones((S, S), bool))], axis=1),
+                           1000.0, d ** -0.5)
+    keep = P[:, lead:].sum(axis=1, keepdims=True)     # mass left on the real tokens
+    np.testing.assert_allclose(out[:, 0], ref[:, 0] * keep, rtol=1e-9, atol=1e-12)
