@@ -1,0 +1,495 @@
+// Host side of the C ABI declared in include/cascade_kv.h: validation, workspace layout, the
+// score-independent mirror of the cache structure, and the kernel sequence of every call.
+#include <math.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "launch.h"
+#include "plan_core.h"
+#include "structure.h"
+
+using namespace ckv;
+
+struct cascade_ctx {
+    cascade_config cfg;
+    Geom g;
+    HostState st;
+    HostState st_prev;   // structure before the last call (for the diagnostic score snapshot)
+    int last_tokens = 0;
+    DevBuffers buf;
+    int dtype;
+    size_t elem;
+    int max_chunk;
+    int tail_k;          // rows of a chunk (counted from its end) that enter the score sums
+    bool mfma;
+    std::string err;
+};
+
+static thread_local std::string g_init_error;
+
+static int fail(cascade_ctx* ctx, int code, const std::string& msg)
+{
+    if (ctx) ctx->err = msg;
+    else g_init_error = msg;
+    return code;
+}
+
+static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// ------------------------------------------------------------------ configuration
+
+static int check_config(const cascade_config* c, std::string& why)
+{
+    if (c->batch < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1) { why = "batch and head counts must be positive"; return CASCADE_E_INVALID_CONFIG; }
+    if (c->n_q_heads % c->n_kv_heads) { why = "n_q_heads must be a multiple of n_kv_heads"; return CASCADE_E_INVALID_CONFIG; }
+    if (c->dtype != CASCADE_F32 && c->dtype != CASCADE_BF16) { why = "dtype must be CASCADE_F32 or CASCADE_BF16"; return CASCADE_E_INVALID_CONFIG; }
+    if (c->head_dim < 2 || c->head_dim % 2) { why = "head_dim must be even"; return CASCADE_E_INVALID_CONFIG; }
+    if (c->n_sink < 0) { why = "n_sink must not be negative"; return CASCADE_E_INVALID_CONFIG; }
+    if (c->n_cascades < 1 || c->n_cascades > CASCADE_MAX_CASCADES) { why = "n_cascades out of range"; return CASCADE_E_INVALID_CONFIG; }
+    bool all_zero = true;
+    for (int i = 0; i < c->n_cascades; ++i) {
+        if (c->cascade_sizes[i] < 1) { why = "every cascade needs at least one slot"; return CASCADE_E_INVALID_CONFIG; }
+        if (c->accept_period[i] < 0) { why = "accept_period must not be negative"; return CASCADE_E_INVALID_CONFIG; }
+        if (c->accept_period[i] != 0) all_zero = false;
+    }
+    if (!all_zero) {
+        if (c->accept_period[0] != 1) { why = "the first cascade must accept every token (accept_period[0] == 1)"; return CASCADE_E_INVALID_CONFIG; }
+        for (int i = 0; i < c->n_cascades; ++i)
+            if (c->accept_period[i] < 1) { why = "accept_period entries must be >= 1"; return CASCADE_E_INVALID_CONFIG; }
+    }
+    if (!(c->ema_beta >= 0.f && c->ema_beta < 1.f)) { why = "ema_beta must be in [0, 1)"; return CASCADE_E_INVALID_CONFIG; }
+    if (!(c->rope_base > 0.f)) { why = "rope_base must be positive"; return CASCADE_E_INVALID_CONFIG; }
+    if (c->softmax_scale < 0.f) { why = "softmax_scale must not be negative"; return CASCADE_E_INVALID_CONFIG; }
+    if (c->max_chunk < 1) { why = "max_chunk must be >= 1"; return CASCADE_E_INVALID_CONFIG; }
+    if (c->head_reduce != CASCADE_REDUCE_MAX && c->head_reduce != CASCADE_REDUCE_MEAN) { why = "unknown head_reduce"; return CASCADE_E_INVALID_CONFIG; }
+    if (c->token_selection != 0 && c->token_selection != 1) { why = "token_selection must be 0 or 1"; return CASCADE_E_INVALID_CONFIG; }
+    long slots = c->n_sink;
+    for (int i = 0; i < c->n_cascades; ++i) slots += c->cascade_sizes[i];
+    if (slots > (1L << 28)) { why = "cache too large"; return CASCADE_E_INVALID_CONFIG; }
+    if (c->dtype == CASCADE_BF16 && c->head_dim != 64 && c->head_dim != 128) { why = "bf16 kernels cover head_dim 64 and 128"; return CASCADE_E_UNSUPPORTED; }
+    if (c->dtype == CASCADE_F32 && c->head_dim > 256) { why = "fp32 kernels cover head_dim up to 256"; return CASCADE_E_UNSUPPORTED; }
+    return CASCADE_OK;
+}
+
+static void make_geom(const cascade_config* c, Geom& g)
+{
+    memset(&g, 0, sizeof(g));
+    g.B = c->batch; g.Hq = c->n_q_heads; g.Hkv = c->n_kv_heads; g.G = g.Hq / g.Hkv; g.d = c->head_dim;
+    g.n_sink = c->n_sink; g.N = c->n_cascades;
+    bool all_zero = true;
+    for (int i = 0; i < g.N; ++i) if (c->accept_period[i] != 0) all_zero = false;
+    int slots = g.n_sink;
+    for (int i = 0; i < g.N; ++i) {
+        g.cap[i] = c->cascade_sizes[i];
+        g.period[i] = all_zero ? (1 << i) : c->accept_period[i];
+        slots += g.cap[i];
+    }
+    g.slots = slots;
+    int base = g.n_sink;                       // physical order: sinks, last cascade, ..., first cascade
+    for (int i = g.N - 1; i >= 0; --i) { g.base[i] = base; base += g.cap[i]; }
+    g.token_selection = c->token_selection;
+    g.head_reduce = c->head_reduce;
+    g.beta = c->ema_beta;
+    g.scale = c->softmax_scale > 0.f ? c->softmax_scale : (float)(1.0 / sqrt((double)g.d));
+}
+
+static int decode_splits(const Geom& g)
+{
+    // enough workgroups to fill 256 compute units several times over, at least 256 rows each
+    int s = (2048 + g.B * g.Hkv - 1) / (g.B * g.Hkv);
+    const int max_s = (g.slots + 255) / 256;
+    if (s > max_s) s = max_s;
+    if (s < 1) s = 1;
+    return s;
+}
+
+// Workspace layout; with base == nullptr only the total size is computed.
+static size_t carve(const cascade_config* c, const Geom& g, char* base, DevBuffers* out)
+{
+    const size_t elem = c->dtype == CASCADE_BF16 ? 2 : 4;
+    const size_t BH = (size_t)g.B * g.Hkv, BHq = (size_t)g.B * g.Hq;
+    const size_t mc = (size_t)c->max_chunk;
+    const int n_qvar_max = 2 * g.N + 2;
+    const int splits = decode_splits(g);
+    const int rope_rows = 2 * g.slots + c->max_chunk + 1;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return base ? (void*)(base + o) : (void*)nullptr; };
+    DevBuffers b;
+    memset(&b, 0, sizeof(b));
+    b.Kc = take(BH * g.slots * g.d * elem);
+    b.Kr = take(BH * g.slots * g.d * elem);
+    b.Vc = take(BH * g.slots * g.d * elem);
+    b.mu = (float*)take(BH * g.slots * 4);
+    b.ids = (int32_t*)take(BH * g.slots * 4);
+    b.swaps = (int32_t*)take(BH * g.N * 4);
+    b.mu_snap = (float*)take(c->keep_update_scores ? BH * g.slots * 4 : 0);
+    b.rope = (float2*)take((size_t)rope_rows * (g.d / 2) * 8);
+    b.wrow = (float*)take(mc * 4);
+    b.Qr = take((size_t)n_qvar_max * BHq * mc * g.d * elem);
+    b.Krc = take(BH * mc * g.d * elem);
+    b.Vch = take(BH * mc * g.d * elem);
+    b.lse = (float*)take(BHq * mc * 4);
+    b.mu_chunk = (float*)take(BH * mc * 4);
+    b.offers = (int32_t*)take(BH * 2 * mc * 4);
+    b.winners = (int32_t*)take(BH * g.N * (mc + 1) * 4);
+    b.logits = (float*)take(BHq * ((size_t)g.slots + 1) * 4);
+    b.part = (float*)take(BHq * splits * 2 * 4);
+    b.opart = (float*)take(BHq * splits * g.d * 4);
+    b.rope_rows = rope_rows;
+    b.dec_splits = splits;
+    if (out) *out = b;
+    return off;
+}
+
+extern "C" size_t cascade_workspace_bytes(const cascade_config* cfg)
+{
+    if (!cfg) return 0;
+    std::string why;
+    if (check_config(cfg, why) != CASCADE_OK) return 0;
+    Geom g;
+    make_geom(cfg, g);
+    return carve(cfg, g, nullptr, nullptr);
+}
+
+static int hip_check(cascade_ctx* ctx, hipError_t e, const char* what)
+{
+    if (e == hipSuccess) return CASCADE_OK;
+    return fail(ctx, CASCADE_E_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+// ------------------------------------------------------------------ init / destroy
+
+extern "C" int cascade_init(const cascade_config* cfg, void* dev_workspace, size_t workspace_bytes,
+                            const cascade_init_state* init_state, void* stream, cascade_ctx** out_ctx)
+{
+    if (!cfg || !dev_workspace || !out_ctx) return fail(nullptr, CASCADE_E_NULL_ARG, "cascade_init: NULL argument");
+    *out_ctx = nullptr;
+    std::string why;
+    int rc = check_config(cfg, why);
+    if (rc != CASCADE_OK) return fail(nullptr, rc, "cascade_init: " + why);
+    if (((uintptr_t)dev_workspace & 255) != 0) return fail(nullptr, CASCADE_E_BAD_ARG, "cascade_init: workspace must be 256-byte aligned");
+    Geom g;
+    make_geom(cfg, g);
+    const size_t need = carve(cfg, g, nullptr, nullptr);
+    if (workspace_bytes < need) return fail(nullptr, CASCADE_E_WORKSPACE_TOO_SMALL, "cascade_init: workspace too small");
+
+    HostState st;
+    int total = 0;
+    if (init_state) {
+        if (init_state->counts[0] < 0 || init_state->counts[0] > g.n_sink)
+            return fail(nullptr, CASCADE_E_BAD_ARG, "cascade_init: sink count exceeds n_sink");
+        st.sink_fill = init_state->counts[0];
+        total = st.sink_fill;
+        for (int c = 0; c < g.N; ++c) {
+            const int cnt = init_state->counts[1 + c];
+            if (cnt < 0 || cnt > g.cap[c]) return fail(nullptr, CASCADE_E_BAD_ARG, "cascade_init: a cascade count exceeds its capacity");
+            st.count[c] = cnt;
+            total += cnt;
+        }
+        if (init_state->t < 0 || init_state->n_seen < 0 || init_state->n_seen > 0x7FFFFFFF)
+            return fail(nullptr, CASCADE_E_BAD_ARG, "cascade_init: t / n_seen out of range");
+        st.t = init_state->t;
+        st.n_seen = init_state->n_seen;
+        if (total > 0 && (!init_state->dev_k || !init_state->dev_v || !init_state->dev_mu || !init_state->dev_ids))
+            return fail(nullptr, CASCADE_E_NULL_ARG, "cascade_init: init_state with items needs k, v, mu and ids");
+    }
+
+    cascade_ctx* ctx = new cascade_ctx();
+    ctx->cfg = *cfg;
+    ctx->g = g;
+    ctx->st = st;
+    ctx->dtype = cfg->dtype;
+    ctx->elem = cfg->dtype == CASCADE_BF16 ? 2 : 4;
+    ctx->max_chunk = cfg->max_chunk;
+    carve(cfg, g, (char*)dev_workspace, &ctx->buf);
+    ctx->mfma = cfg->dtype == CASCADE_BF16;
+    if (const char* e = getenv("CASCADE_KV_SCALAR_ATTENTION")) if (e[0] == '1') ctx->mfma = false;
+
+    // rows of a chunk whose EMA weight beta^k has not dropped below the cut
+    {
+        const double beta = cfg->ema_beta;
+        double eps = cfg->score_tail_eps == 0.f ? ldexp(1.0, -40) : (double)cfg->score_tail_eps;
+        int k = cfg->max_chunk;
+        if (eps > 0.0) {
+            if (beta <= 0.0) k = 1;
+            else {
+                double kk = ceil(log(eps) / log(beta));
+                if (kk < 1.0) kk = 1.0;
+                if (kk < (double)k) k = (int)kk;
+            }
+        }
+        ctx->tail_k = k;
+    }
+
+    hipStream_t s = (hipStream_t)stream;
+    const DevBuffers& b = ctx->buf;
+    const size_t BH = (size_t)g.B * g.Hkv;
+    // zero the cache (rows of empty slots are read, masked, by the attention tiles) and scratch
+    hipError_t e = hipMemsetAsync(dev_workspace, 0, need, s);
+    if (e != hipSuccess) { rc = hip_check(nullptr, e, "cascade_init: memset"); delete ctx; return rc; }
+    launch_fill_i32(b.ids, BH * g.slots, -1, s);
+    launch_rope_table(g, cfg->rope_base, b.rope, b.rope_rows, s);
+    launch_wrow_table(cfg->ema_beta, b.wrow, cfg->max_chunk, s);
+    if (init_state && total > 0)
+        launch_load_state(g, ctx->dtype, b, init_state->dev_k, init_state->dev_v, init_state->dev_mu,
+                          init_state->dev_ids, init_state->counts, total, s);
+    e = hipGetLastError();
+    if (e != hipSuccess) { rc = hip_check(nullptr, e, "cascade_init: launch"); delete ctx; return rc; }
+    *out_ctx = ctx;
+    return CASCADE_OK;
+}
+
+extern "C" void cascade_destroy(cascade_ctx* ctx) { delete ctx; }
+
+extern "C" const char* cascade_last_error(const cascade_ctx* ctx) { return ctx ? ctx->err.c_str() : g_init_error.c_str(); }
+
+// Diagnostics: keep the scores the coming insertion decisions are taken with.
+static int snapshot_scores(cascade_ctx* ctx, int n_tokens, hipStream_t s)
+{
+    ctx->st_prev = ctx->st;
+    ctx->last_tokens = n_tokens;
+    if (!ctx->cfg.keep_update_scores) return CASCADE_OK;
+    const size_t bytes = (size_t)ctx->g.B * ctx->g.Hkv * ctx->g.slots * 4;
+    return hip_check(ctx, hipMemcpyAsync(ctx->buf.mu_snap, ctx->buf.mu, bytes, hipMemcpyDeviceToDevice, s),
+                     "score snapshot");
+}
+
+// ------------------------------------------------------------------ prefill chunk
+
+extern "C" int cascade_prefill_chunk(cascade_ctx* ctx, const void* dev_q, const void* dev_k, const void* dev_v,
+                                     int32_t n_tokens, void* dev_out, void* stream)
+{
+    if (!ctx) return CASCADE_E_NULL_ARG;
+    if (!dev_q || !dev_k || !dev_v || !dev_out) return fail(ctx, CASCADE_E_NULL_ARG, "cascade_prefill_chunk: NULL argument");
+    if (n_tokens < 1 || n_tokens > ctx->max_chunk) return fail(ctx, CASCADE_E_BAD_ARG, "cascade_prefill_chunk: n_tokens out of range");
+    if (ctx->st.n_seen + n_tokens > 0x7FFFFFFF) return fail(ctx, CASCADE_E_BAD_ARG, "cascade_prefill_chunk: token index overflow");
+    const Geom& g = ctx->g;
+    hipStream_t s = (hipStream_t)stream;
+    const int Q = n_tokens;
+
+    SegList sl;
+    build_segments(g, ctx->st, true, Q, sl);
+    launch_prep(g, ctx->dtype, ctx->buf, sl, Q, dev_q, dev_k, dev_v, s);
+    if (ctx->mfma) launch_attn_mfma(g, ctx->buf, sl, Q, ctx->max_chunk, dev_out, s);
+    else launch_attn_simple(g, ctx->dtype, ctx->buf, sl, Q, ctx->max_chunk, dev_out, s);
+
+    const int tail = Q < ctx->tail_k ? Q : ctx->tail_k;
+    const float decay = (float)pow((double)g.beta, (double)Q);
+    if (ctx->mfma) launch_score_mfma(g, ctx->buf, sl, Q, ctx->max_chunk, tail, decay, s);
+    else launch_score_simple(g, ctx->dtype, ctx->buf, sl, Q, ctx->max_chunk, tail, decay, s);
+
+    int rc = snapshot_scores(ctx, Q, s);
+    if (rc) return rc;
+    UpdatePlan pl;
+    plan_update(g, ctx->st, Q, pl);
+    launch_plan(g, ctx->buf, pl, ctx->max_chunk, s);
+    launch_moves(g, ctx->dtype, ctx->buf, pl, ctx->max_chunk, dev_k, dev_v, g.Hkv * g.d, Q * g.Hkv * g.d, s);
+    return hip_check(ctx, hipGetLastError(), "cascade_prefill_chunk");
+}
+
+// ------------------------------------------------------------------ decode step
+
+extern "C" int cascade_decode_step(cascade_ctx* ctx, const void* dev_q, const void* dev_k, const void* dev_v,
+                                   void* dev_out, void* stream)
+{
+    if (!ctx) return CASCADE_E_NULL_ARG;
+    if (!dev_q || !dev_k || !dev_v || !dev_out) return fail(ctx, CASCADE_E_NULL_ARG, "cascade_decode_step: NULL argument");
+    const Geom& g = ctx->g;
+    if (!decode_supported(g)) return fail(ctx, CASCADE_E_UNSUPPORTED, "cascade_decode_step: needs head_dim 64 or 128 and at most 8 query heads per KV head");
+    if (ctx->st.n_seen + 1 > 0x7FFFFFFF) return fail(ctx, CASCADE_E_BAD_ARG, "cascade_decode_step: token index overflow");
+    hipStream_t s = (hipStream_t)stream;
+
+    SegList sl;
+    build_segments(g, ctx->st, false, 1, sl);
+    launch_decode(g, ctx->dtype, ctx->buf, sl, ctx->max_chunk, dev_q, dev_k, dev_v, dev_out, s);
+
+    int rc = snapshot_scores(ctx, 1, s);
+    if (rc) return rc;
+    UpdatePlan pl;
+    plan_update(g, ctx->st, 1, pl);
+    launch_plan(g, ctx->buf, pl, ctx->max_chunk, s);
+    launch_moves(g, ctx->dtype, ctx->buf, pl, ctx->max_chunk, dev_k, dev_v, g.Hkv * g.d, g.Hkv * g.d, s);
+    return hip_check(ctx, hipGetLastError(), "cascade_decode_step");
+}
+
+// ------------------------------------------------------------------ read state
+
+extern "C" int cascade_read_state(cascade_ctx* ctx, cascade_state_view* view, void* stream)
+{
+    if (!ctx) return CASCADE_E_NULL_ARG;
+    if (!view) return fail(ctx, CASCADE_E_NULL_ARG, "cascade_read_state: NULL view");
+    const Geom& g = ctx->g;
+    const HostState& st = ctx->st;
+    hipStream_t s = (hipStream_t)stream;
+    int rc = hip_check(ctx, hipStreamSynchronize(s), "cascade_read_state: synchronize");
+    if (rc) return rc;
+
+    const size_t BH = (size_t)g.B * g.Hkv;
+    const int n = st.n_cached(g);
+    std::vector<int> slot(n);
+    for (int r = 0; r < n; ++r) slot[r] = slot_of_rank(g, st, r);
+
+    memset(view->counts, 0, sizeof(view->counts));
+    memset(view->xi, 0, sizeof(view->xi));
+    memset(view->accepted, 0, sizeof(view->accepted));
+    memset(view->discards, 0, sizeof(view->discards));
+    view->counts[0] = st.sink_fill;
+    for (int c = 0; c < g.N; ++c) {
+        view->counts[1 + c] = st.count[c];
+        view->xi[c] = st.xi[c];
+        view->accepted[c] = st.accepted[c];
+        view->discards[c] = st.discards[c];
+    }
+    view->t = st.t;
+    view->n_seen = st.n_seen;
+    view->pre_count = ctx->st_prev.n_cached(g);
+    view->last_tokens = ctx->last_tokens;
+
+    if (ctx->cfg.keep_update_scores && view->host_pre_mu && ctx->last_tokens > 0) {
+        std::vector<float> snap(BH * g.slots);
+        rc = hip_check(ctx, hipMemcpy(snap.data(), ctx->buf.mu_snap, snap.size() * 4, hipMemcpyDeviceToHost), "cascade_read_state: copy score snapshot");
+        if (rc) return rc;
+        const int np = view->pre_count;
+        for (int r = 0; r < np; ++r) {
+            const int sl = slot_of_rank(g, ctx->st_prev, r);
+            for (size_t bh = 0; bh < BH; ++bh) view->host_pre_mu[bh * g.slots + r] = snap[bh * g.slots + sl];
+        }
+    }
+    if (ctx->cfg.keep_update_scores && view->host_chunk_mu && ctx->last_tokens > 0) {
+        rc = hip_check(ctx, hipMemcpy(view->host_chunk_mu, ctx->buf.mu_chunk, BH * (size_t)ctx->max_chunk * 4, hipMemcpyDeviceToHost),
+                       "cascade_read_state: copy chunk scores");
+        if (rc) return rc;
+    }
+
+    if (view->host_ids || view->host_mu || view->host_slot) {
+        std::vector<int32_t> ids(BH * g.slots);
+        std::vector<float> mu(BH * g.slots);
+        rc = hip_check(ctx, hipMemcpy(ids.data(), ctx->buf.ids, ids.size() * 4, hipMemcpyDeviceToHost), "cascade_read_state: copy ids");
+        if (rc) return rc;
+        rc = hip_check(ctx, hipMemcpy(mu.data(), ctx->buf.mu, mu.size() * 4, hipMemcpyDeviceToHost), "cascade_read_state: copy mu");
+        if (rc) return rc;
+        for (size_t bh = 0; bh < BH; ++bh)
+            for (int r = 0; r < g.slots; ++r) {
+                const size_t o = bh * g.slots + r;
+                if (view->host_ids) view->host_ids[o] = r < n ? ids[bh * g.slots + slot[r]] : -1;
+                if (view->host_mu) view->host_mu[o] = r < n ? mu[bh * g.slots + slot[r]] : 0.f;
+                if (view->host_slot) view->host_slot[o] = r < n ? slot[r] : -1;
+            }
+    }
+    if (view->host_swaps) {
+        std::vector<int32_t> sw(BH * g.N);
+        rc = hip_check(ctx, hipMemcpy(sw.data(), ctx->buf.swaps, sw.size() * 4, hipMemcpyDeviceToHost), "cascade_read_state: copy swaps");
+        if (rc) return rc;
+        for (size_t i = 0; i < sw.size(); ++i) view->host_swaps[i] = sw[i];
+    }
+    for (int which = 0; which < 2; ++which) {
+        float* dst = which == 0 ? view->host_k : view->host_v;
+        if (!dst) continue;
+        const void* src = which == 0 ? ctx->buf.Kc : ctx->buf.Vc;
+        std::vector<char> raw((size_t)g.slots * g.d * ctx->elem);
+        for (size_t bh = 0; bh < BH; ++bh) {
+            rc = hip_check(ctx, hipMemcpy(raw.data(), (const char*)src + bh * raw.size(), raw.size(), hipMemcpyDeviceToHost),
+                           "cascade_read_state: copy rows");
+            if (rc) return rc;
+            for (int r = 0; r < g.slots; ++r) {
+                float* o = dst + (bh * g.slots + r) * g.d;
+                if (r >= n) { memset(o, 0, sizeof(float) * g.d); continue; }
+                if (ctx->dtype == CASCADE_BF16) {
+                    const bf16_t* p = (const bf16_t*)raw.data() + (size_t)slot[r] * g.d;
+                    for (int e = 0; e < g.d; ++e) o[e] = bf16_to_f32(p[e]);
+                } else {
+                    memcpy(o, (const float*)raw.data() + (size_t)slot[r] * g.d, sizeof(float) * g.d);
+                }
+            }
+        }
+    }
+    return CASCADE_OK;
+}
+
+// ------------------------------------------------------------------ host-only utility
+
+// Fill, ring heads and counters after feeding chunks of the given sizes to an empty cache; with
+// scores also the membership.  Pure host arithmetic (no device is touched).  The membership is
+// computed by the same segment / eviction routines the device kernels run (plan_core.h), one
+// "thread" at a time.
+extern "C" int cascade_simulate_structure(const cascade_config* cfg, const int32_t* chunk_sizes, int32_t n_chunks,
+                                          const float* host_scores, cascade_state_view* view)
+{
+    if (!cfg || !view || (!chunk_sizes && n_chunks > 0)) return fail(nullptr, CASCADE_E_NULL_ARG, "cascade_simulate_structure: NULL argument");
+    std::string why;
+    int rc = check_config(cfg, why);
+    if (rc != CASCADE_OK) return fail(nullptr, rc, "cascade_simulate_structure: " + why);
+    Geom g;
+    make_geom(cfg, g);
+    HostState st;
+    std::vector<float> mu;
+    std::vector<int32_t> ids;
+    std::vector<int64_t> swaps(g.N, 0);
+    if (host_scores) { mu.assign(g.slots, 0.f); ids.assign(g.slots, -1); }
+    size_t consumed = 0;
+    for (int ci = 0; ci < n_chunks; ++ci) {
+        const int Q = chunk_sizes[ci];
+        if (Q < 1) return fail(nullptr, CASCADE_E_BAD_ARG, "cascade_simulate_structure: chunk sizes must be >= 1");
+        UpdatePlan pl;
+        plan_update(g, st, Q, pl);
+        if (!host_scores) continue;
+        const float* muc = host_scores + consumed;
+        consumed += Q;
+        std::vector<int32_t> off_a(Q + 1), off_b(Q + 1);
+        std::vector<std::vector<int32_t>> W(g.N, std::vector<int32_t>(Q + 2, -1));
+        int32_t *off_in = off_a.data(), *off_out = off_b.data();
+        for (int c = 0; c < g.N; ++c) {
+            const CascStep& cs = pl.c[c];
+            if (cs.M == 0) break;
+            for (int sidx = 0; sidx < cs.J + cs.pre; ++sidx) {
+                const int j = sidx - cs.pre;
+                int sw;
+                W[c][1 + j] = segment_winner(cs, c, j, g.slots, pl.n_to_sink, g.token_selection, off_in,
+                                             mu.data(), muc, &sw);
+                swaps[c] += sw;
+            }
+            for (int i = 0; i < cs.P; ++i) off_out[i] = evicted_ref(cs, i, W[c].data());
+            std::swap(off_in, off_out);
+        }
+        for (int c = g.N - 1; c >= -1; --c) {      // the last cascade first: sources are still intact
+            int E, extra = 0;
+            if (c < 0) E = pl.n_to_sink;
+            else { if (pl.c[c].M == 0) continue; E = final_entries(pl.c[c], &extra); }
+            for (int e = 0; e < E + extra; ++e) {
+                int dst, ref;
+                if (c < 0) { dst = pl.sink_fill0 + e; ref = g.slots + e; }
+                else if (!final_entry(pl.c[c], e, E, W[c].data(), &dst, &ref)) continue;
+                if (ref < g.slots) { mu[dst] = mu[ref]; ids[dst] = ids[ref]; }
+                else { mu[dst] = muc[ref - g.slots]; ids[dst] = pl.id0 + (ref - g.slots); }
+            }
+        }
+    }
+    memset(view->counts, 0, sizeof(view->counts));
+    memset(view->xi, 0, sizeof(view->xi));
+    memset(view->accepted, 0, sizeof(view->accepted));
+    memset(view->discards, 0, sizeof(view->discards));
+    view->counts[0] = st.sink_fill;
+    for (int c = 0; c < g.N; ++c) {
+        view->counts[1 + c] = st.count[c];
+        view->xi[c] = st.xi[c];
+        view->accepted[c] = st.accepted[c];
+        view->discards[c] = st.discards[c];
+    }
+    view->t = st.t;
+    view->n_seen = st.n_seen;
+    view->pre_count = 0;
+    view->last_tokens = 0;
+    const int n = st.n_cached(g);
+    for (int r = 0; r < g.slots; ++r) {
+        const int sl = r < n ? slot_of_rank(g, st, r) : -1;
+        if (view->host_slot) view->host_slot[r] = sl;
+        if (host_scores && view->host_ids) view->host_ids[r] = sl >= 0 ? ids[sl] : -1;
+        if (host_scores && view->host_mu) view->host_mu[r] = sl >= 0 ? mu[sl] : 0.f;
+    }
+    if (host_scores && view->host_swaps) for (int c = 0; c < g.N; ++c) view->host_swaps[c] = swaps[c];
+    return CASCADE_OK;
+}

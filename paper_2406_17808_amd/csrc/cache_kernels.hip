@@ -1,0 +1,314 @@
+// Cache maintenance kernels: tables, query/key rotation, the score-dependent part of the
+// cascade update (Alg. 2) and the row moves that carry it out.
+#include "launch.h"
+#include "plan_core.h"
+#include "structure.h"
+
+namespace ckv {
+
+// ------------------------------------------------------------------ tables
+
+// (cos, sin)(p * theta_i), theta_i = base^(-2i/d), evaluated in double so that large
+// indices keep full float accuracy.
+__global__ void rope_table_kernel(float2* __restrict__ rope, int rows, int half, int d, double base)
+{
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long)rows * half) return;
+    const int p = (int)(idx / half), i = (int)(idx % half);
+    const double theta = pow(base, -2.0 * (double)i / (double)d);
+    double s, c;
+    sincos((double)p * theta, &s, &c);
+    rope[idx] = make_float2((float)c, (float)s);
+}
+
+void launch_rope_table(const Geom& g, float base, float2* rope, int rows, hipStream_t s)
+{
+    const int half = g.d / 2;
+    const long n = (long)rows * half;
+    hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                       rope, rows, half, g.d, (double)base);
+}
+
+// wrow[k] = beta^k (1 - beta): weight of the query row that has k rows after it in its chunk
+// (Alg. 3's coefficient; the EMA of Section 3.1 unrolled over the rows of a chunk).
+__global__ void wrow_table_kernel(float* __restrict__ wrow, int n, double beta)
+{
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < n) wrow[k] = (float)(pow(beta, (double)k) * (1.0 - beta));
+}
+
+void launch_wrow_table(float beta, float* wrow, int n, hipStream_t s)
+{
+    hipLaunchKernelGGL(wrow_table_kernel, dim3((n + 255) / 256), dim3(256), 0, s, wrow, n, (double)beta);
+}
+
+__global__ void fill_i32_kernel(int32_t* __restrict__ p, size_t n, int32_t v)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = v;
+}
+
+void launch_fill_i32(int32_t* p, size_t n, int32_t value, hipStream_t s)
+{
+    if (n == 0) return;
+    const unsigned blocks = (unsigned)std::min<size_t>((n + 255) / 256, 65535);
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks), dim3(256), 0, s, p, n, value);
+}
+
+// ------------------------------------------------------------------ initial state
+
+// Scatter a state given in cache order into the physical layout (ring heads at 0) and build
+// the rotated key copy.  One thread per (row, rotary pair).
+struct FillCounts { int sink; int c[kMaxCascades]; };
+
+template <typename T>
+__global__ void load_state_kernel(Geom g, FillCounts fc, int total, T* __restrict__ Kc, T* __restrict__ Kr,
+                                  T* __restrict__ Vc, float* __restrict__ mu, int32_t* __restrict__ ids,
+                                  const float2* __restrict__ rope,
+                                  const T* __restrict__ k_in, const T* __restrict__ v_in,
+                                  const float* __restrict__ mu_in, const int32_t* __restrict__ ids_in)
+{
+    const int half = g.d / 2;
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long per_bh = (long)total * half;
+    if (idx >= per_bh * g.B * g.Hkv) return;
+    const int bh = (int)(idx / per_bh);
+    const int r = (int)((idx % per_bh) / half), e = (int)(idx % half);
+    // rank r in cache order -> physical slot
+    int slot = -1, rr = r;
+    if (rr < fc.sink) slot = rr;
+    else {
+        rr -= fc.sink;
+        for (int c = g.N - 1; c >= 0; --c) {
+            if (rr < fc.c[c]) { slot = g.base[c] + rr; break; }
+            rr -= fc.c[c];
+        }
+    }
+    const size_t src = ((size_t)bh * total + r) * g.d;
+    const size_t dst = ((size_t)bh * g.slots + slot) * g.d;
+    const float x0 = Elem<T>::load(k_in + src + e), x1 = Elem<T>::load(k_in + src + e + half);
+    const float2 cs = rope[(size_t)slot * half + e];
+    Elem<T>::store(Kc + dst + e, x0);
+    Elem<T>::store(Kc + dst + e + half, x1);
+    Elem<T>::store(Kr + dst + e, x0 * cs.x - x1 * cs.y);
+    Elem<T>::store(Kr + dst + e + half, x1 * cs.x + x0 * cs.y);
+    Vc[dst + e] = v_in[src + e];
+    Vc[dst + e + half] = v_in[src + e + half];
+    if (e == 0) {
+        mu[(size_t)bh * g.slots + slot] = mu_in[(size_t)bh * total + r];
+        ids[(size_t)bh * g.slots + slot] = ids_in[(size_t)bh * total + r];
+    }
+}
+
+void launch_load_state(const Geom& g, int dtype, const DevBuffers& b, const void* k, const void* v,
+                       const float* mu, const int32_t* ids, const int* counts, int total, hipStream_t s)
+{
+    if (total == 0) return;
+    const long n = (long)g.B * g.Hkv * total * (g.d / 2);
+    FillCounts fc;
+    fc.sink = counts[0];
+    for (int i = 0; i < kMaxCascades; ++i) fc.c[i] = i < g.N ? counts[1 + i] : 0;
+    const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+    if (dtype == CASCADE_F32)
+        hipLaunchKernelGGL(load_state_kernel<float>, grid, block, 0, s, g, fc, total, (float*)b.Kc, (float*)b.Kr,
+                           (float*)b.Vc, b.mu, b.ids, b.rope, (const float*)k, (const float*)v, mu, ids);
+    else
+        hipLaunchKernelGGL(load_state_kernel<bf16_t>, grid, block, 0, s, g, fc, total, (bf16_t*)b.Kc, (bf16_t*)b.Kr,
+                           (bf16_t*)b.Vc, b.mu, b.ids, b.rope, (const bf16_t*)k, (const bf16_t*)v, mu, ids);
+}
+
+// ------------------------------------------------------------------ per-chunk rotation
+
+// For every rotated query copy v: Qr[v][b][h][i] = R(qrot0[v] + i) q[b][i][h]; chunk keys are
+// rotated to their chunk index, chunk values are copied head-major.  One thread per rotary pair.
+template <typename T>
+__global__ void prep_kernel(Geom g, SegList sl, int Q, const float2* __restrict__ rope,
+                            const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
+                            T* __restrict__ Qr, T* __restrict__ Krc, T* __restrict__ Vch)
+{
+    const int half = g.d / 2;
+    const int rows_per_tok = sl.n_qvar * g.Hq + 2 * g.Hkv;   // per (b, i): query copies, K, V
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long total = (long)g.B * Q * rows_per_tok * half;
+    if (idx >= total) return;
+    const int e = (int)(idx % half);
+    long r = idx / half;
+    const int row = (int)(r % rows_per_tok);
+    r /= rows_per_tok;
+    const int i = (int)(r % Q), b = (int)(r / Q);
+    if (row < sl.n_qvar * g.Hq) {
+        const int vq = row / g.Hq, h = row % g.Hq;
+        const size_t src = (((size_t)b * Q + i) * g.Hq + h) * g.d;
+        const size_t dst = ((((size_t)vq * g.B + b) * g.Hq + h) * Q + i) * g.d;
+        const float x0 = Elem<T>::load(q + src + e), x1 = Elem<T>::load(q + src + e + half);
+        const float2 cs = rope[(size_t)(sl.qrot0[vq] + i) * half + e];
+        Elem<T>::store(Qr + dst + e, x0 * cs.x - x1 * cs.y);
+        Elem<T>::store(Qr + dst + e + half, x1 * cs.x + x0 * cs.y);
+    } else {
+        const int rr = row - sl.n_qvar * g.Hq;
+        const int h = rr % g.Hkv;
+        const size_t src = (((size_t)b * Q + i) * g.Hkv + h) * g.d;
+        const size_t dst = (((size_t)b * g.Hkv + h) * Q + i) * g.d;
+        if (rr < g.Hkv) {
+            const float x0 = Elem<T>::load(k + src + e), x1 = Elem<T>::load(k + src + e + half);
+            const float2 cs = rope[(size_t)i * half + e];
+            Elem<T>::store(Krc + dst + e, x0 * cs.x - x1 * cs.y);
+            Elem<T>::store(Krc + dst + e + half, x1 * cs.x + x0 * cs.y);
+        } else {
+            Vch[dst + e] = v[src + e];
+            Vch[dst + e + half] = v[src + e + half];
+        }
+    }
+}
+
+void launch_prep(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int Q,
+                 const void* q, const void* k, const void* v, hipStream_t s)
+{
+    const long n = (long)g.B * Q * (sl.n_qvar * g.Hq + 2 * g.Hkv) * (g.d / 2);
+    const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+    if (dtype == CASCADE_F32)
+        hipLaunchKernelGGL(prep_kernel<float>, grid, block, 0, s, g, sl, Q, b.rope, (const float*)q, (const float*)k,
+                           (const float*)v, (float*)b.Qr, (float*)b.Krc, (float*)b.Vch);
+    else
+        hipLaunchKernelGGL(prep_kernel<bf16_t>, grid, block, 0, s, g, sl, Q, b.rope, (const bf16_t*)q, (const bf16_t*)k,
+                           (const bf16_t*)v, (bf16_t*)b.Qr, (bf16_t*)b.Krc, (bf16_t*)b.Vch);
+}
+
+// ------------------------------------------------------------------ cascade update: who ends up where
+
+// One workgroup per (sequence, KV head).  For every cascade in turn:
+//   phase 1  the winner of every segment (see plan_core.h);
+//   phase 2  every push passes the item it evicts on to the next cascade.
+// winners[c][0] is the segment of the item that was newest before the update, winners[c][1+j]
+// that of the j-th slot opened.
+__global__ void plan_kernel(Geom g, UpdatePlan pl, int qstride, const float* __restrict__ mu,
+                            const float* __restrict__ mu_chunk, int32_t* __restrict__ offers,
+                            int32_t* __restrict__ winners, int32_t* __restrict__ swaps)
+{
+    const int bh = blockIdx.x;
+    const float* mub = mu + (size_t)bh * g.slots;
+    const float* muc = mu_chunk + (size_t)bh * qstride;
+    int32_t* off_in = offers + (size_t)bh * 2 * qstride;
+    int32_t* off_out = off_in + qstride;
+    for (int c = 0; c < pl.N; ++c) {
+        const CascStep cs = pl.c[c];
+        if (cs.M == 0) break;
+        int32_t* W = winners + ((size_t)bh * pl.N + c) * (qstride + 1);
+        const int nseg = cs.J + cs.pre;
+        int my_swaps = 0;
+        for (int sidx = threadIdx.x; sidx < nseg; sidx += blockDim.x) {
+            const int j = sidx - cs.pre;
+            int sw;
+            W[1 + j] = segment_winner(cs, c, j, g.slots, pl.n_to_sink, g.token_selection, off_in, mub, muc, &sw);
+            my_swaps += sw;
+        }
+        if (my_swaps) atomicAdd(&swaps[bh * pl.N + c], my_swaps);
+        __syncthreads();
+        for (int i = threadIdx.x; i < cs.P; i += blockDim.x) off_out[i] = evicted_ref(cs, i, W);
+        __syncthreads();
+        int32_t* tmp = off_in; off_in = off_out; off_out = tmp;
+    }
+}
+
+void launch_plan(const Geom& g, const DevBuffers& b, const UpdatePlan& pl, int max_chunk, hipStream_t s)
+{
+    const int threads = pl.Q >= 1024 ? 1024 : (pl.Q >= 256 ? 256 : 64);
+    hipLaunchKernelGGL(plan_kernel, dim3(g.B * g.Hkv), dim3(threads), 0, s, g, pl, max_chunk, b.mu, b.mu_chunk,
+                       b.offers, b.winners, b.swaps);
+}
+
+// ------------------------------------------------------------------ cascade update: row moves
+
+// Final content of cascade c (c = -1: sinks).  Entry e < E names a ring position that was
+// written during the update and the ref that ends up in it; one extra entry covers the item
+// that was newest before the update if a competing offer replaced it.  A destination row is
+// rebuilt from the un-rotated source key, re-rotated to the destination slot index.
+// `lanes` threads cooperate on a row; each handles rotary pairs e, e + lanes, ...
+template <typename T>
+__global__ void move_kernel(Geom g, UpdatePlan pl, int c, int E, int extra, int qstride,
+                            const float2* __restrict__ rope, const int32_t* __restrict__ winners,
+                            T* __restrict__ Kc, T* __restrict__ Kr, T* __restrict__ Vc,
+                            float* __restrict__ mu, int32_t* __restrict__ ids,
+                            const float* __restrict__ mu_chunk,
+                            const T* __restrict__ k_in, const T* __restrict__ v_in,
+                            long tok_stride, long batch_stride, int lanes)
+{
+    const int bh = blockIdx.y;
+    const int b = bh / g.Hkv, h = bh % g.Hkv;
+    const int rows_per_block = blockDim.x / lanes;
+    const int e = blockIdx.x * rows_per_block + threadIdx.x / lanes;
+    const int lane = threadIdx.x % lanes;
+    if (e >= E + extra) return;
+    int dst, ref;
+    if (c < 0) {
+        dst = pl.sink_fill0 + e;
+        ref = g.slots + e;
+    } else {
+        const int32_t* W = winners + ((size_t)bh * pl.N + c) * (qstride + 1);
+        if (!final_entry(pl.c[c], e, E, W, &dst, &ref)) return;
+    }
+    const int half = g.d / 2;
+    const size_t drow = ((size_t)bh * g.slots + dst) * g.d;
+    const T *ks, *vs;
+    float score;
+    int id;
+    if (ref < g.slots) {
+        const size_t srow = ((size_t)bh * g.slots + ref) * g.d;
+        ks = Kc + srow;
+        vs = Vc + srow;
+        score = mu[(size_t)bh * g.slots + ref];
+        id = ids[(size_t)bh * g.slots + ref];
+    } else {
+        const int i = ref - g.slots;
+        const size_t srow = (size_t)b * batch_stride + (size_t)i * tok_stride + (size_t)h * g.d;
+        ks = k_in + srow;
+        vs = v_in + srow;
+        score = mu_chunk[(size_t)bh * qstride + i];
+        id = pl.id0 + i;
+    }
+    for (int p = lane; p < half; p += lanes) {
+        const float x0 = Elem<T>::load(ks + p), x1 = Elem<T>::load(ks + p + half);
+        const float2 cs2 = rope[(size_t)dst * half + p];
+        Elem<T>::store(Kc + drow + p, x0);
+        Elem<T>::store(Kc + drow + p + half, x1);
+        Elem<T>::store(Kr + drow + p, x0 * cs2.x - x1 * cs2.y);
+        Elem<T>::store(Kr + drow + p + half, x1 * cs2.x + x0 * cs2.y);
+        Vc[drow + p] = vs[p];
+        Vc[drow + p + half] = vs[p + half];
+    }
+    if (lane == 0) {
+        mu[(size_t)bh * g.slots + dst] = score;
+        ids[(size_t)bh * g.slots + dst] = id;
+    }
+}
+
+// Destinations of cascade c take sources from earlier cascades or from the chunk only (items
+// never move backwards), so writing the last cascade first keeps every source intact until it
+// has been read.
+void launch_moves(const Geom& g, int dtype, const DevBuffers& b, const UpdatePlan& pl, int max_chunk,
+                  const void* k, const void* v, int k_token_stride, int k_batch_stride, hipStream_t s)
+{
+    const int lanes = 32, threads = 256, rows = threads / lanes;
+    for (int c = pl.N - 1; c >= -1; --c) {
+        int E, extra = 0;
+        if (c < 0) {
+            E = pl.n_to_sink;
+        } else {
+            if (pl.c[c].M == 0) continue;
+            E = final_entries(pl.c[c], &extra);
+        }
+        if (E + extra == 0) continue;
+        const dim3 grid((E + extra + rows - 1) / rows, g.B * g.Hkv), block(threads);
+        if (dtype == CASCADE_F32)
+            hipLaunchKernelGGL(move_kernel<float>, grid, block, 0, s, g, pl, c, E, extra, max_chunk, b.rope, b.winners,
+                               (float*)b.Kc, (float*)b.Kr, (float*)b.Vc, b.mu, b.ids, b.mu_chunk,
+                               (const float*)k, (const float*)v, (long)k_token_stride, (long)k_batch_stride, lanes);
+        else
+            hipLaunchKernelGGL(move_kernel<bf16_t>, grid, block, 0, s, g, pl, c, E, extra, max_chunk, b.rope, b.winners,
+                               (bf16_t*)b.Kc, (bf16_t*)b.Kr, (bf16_t*)b.Vc, b.mu, b.ids, b.mu_chunk,
+                               (const bf16_t*)k, (const bf16_t*)v, (long)k_token_stride, (long)k_batch_stride, lanes);
+    }
+}
+
+}  // namespace ckv

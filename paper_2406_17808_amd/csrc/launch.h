@@ -1,0 +1,68 @@
+// Launchers of the HIP kernels (one per kernel family), called by the host API.
+#pragma once
+
+#include "internal.h"
+
+namespace ckv {
+
+// Device memory of one context, carved out of the caller's workspace.
+struct DevBuffers {
+    // cache
+    void* Kc;        // [B,Hkv,slots,d] un-rotated keys
+    void* Kr;        // [B,Hkv,slots,d] keys rotated to their physical slot index
+    void* Vc;        // [B,Hkv,slots,d]
+    float* mu;       // [B,Hkv,slots] EMA scores
+    int32_t* ids;    // [B,Hkv,slots] original token index, -1 = empty
+    int32_t* swaps;  // [B,Hkv,N]
+    float* mu_snap;  // [B,Hkv,slots] diagnostics: scores when the last insertion decisions were taken
+    // tables
+    float2* rope;    // [rope_rows, d/2] (cos, sin) of index * theta_i
+    float* wrow;     // [max_chunk] beta^k (1 - beta): EMA weight of the row that has k rows after it
+    // per-call scratch
+    void* Qr;        // [n_qvar_max, B, Hq, max_chunk, d] rotated query copies
+    void* Krc;       // [B,Hkv,max_chunk,d] chunk keys rotated to their chunk index
+    void* Vch;       // [B,Hkv,max_chunk,d] chunk values, head-major
+    float* lse;      // [B,Hq,max_chunk] log-sum-exp of every query row (natural log, scaled logits)
+    float* mu_chunk; // [B,Hkv,max_chunk] scores of the chunk's tokens
+    int32_t* offers; // [B,Hkv,2,max_chunk]
+    int32_t* winners;// [B,Hkv,N,max_chunk+1]
+    // decode scratch
+    float* logits;   // [B,Hq,slots+1]
+    float* part;     // [B,Hq,dec_splits,2] (max, sum) of every split
+    float* opart;    // [B,Hq,dec_splits,d]
+    int rope_rows;
+    int dec_splits;
+};
+
+// tables
+void launch_rope_table(const Geom& g, float base, float2* rope, int rows, hipStream_t s);
+void launch_wrow_table(float beta, float* wrow, int n, hipStream_t s);
+
+// cache maintenance
+void launch_fill_i32(int32_t* p, size_t n, int32_t value, hipStream_t s);
+void launch_load_state(const Geom& g, int dtype, const DevBuffers& b, const void* k, const void* v,
+                       const float* mu, const int32_t* ids, const int* counts, int total, hipStream_t s);
+void launch_prep(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int Q,
+                 const void* q, const void* k, const void* v, hipStream_t s);
+void launch_plan(const Geom& g, const DevBuffers& b, const UpdatePlan& pl, int max_chunk, hipStream_t s);
+void launch_moves(const Geom& g, int dtype, const DevBuffers& b, const UpdatePlan& pl, int max_chunk,
+                  const void* k, const void* v, int k_token_stride, int k_batch_stride, hipStream_t s);
+
+// attention, generic (any dtype / head_dim): scalar arithmetic
+void launch_attn_simple(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int Q,
+                        int max_chunk, void* out, hipStream_t s);
+void launch_score_simple(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int Q,
+                         int max_chunk, int tail_rows, float decay, hipStream_t s);
+
+// attention, bf16 MFMA (head_dim 64 or 128)
+void launch_attn_mfma(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, int max_chunk,
+                      void* out, hipStream_t s);
+void launch_score_mfma(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, int max_chunk,
+                       int tail_rows, float decay, hipStream_t s);
+
+// decode
+void launch_decode(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int qstride,
+                   const void* q, const void* k, const void* v, void* out, hipStream_t s);
+bool decode_supported(const Geom& g);
+
+}  // namespace ckv

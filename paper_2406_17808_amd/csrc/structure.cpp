@@ -1,0 +1,117 @@
+// Host-side structure of the cascade update and of the attention segments.
+#include "structure.h"
+
+#include <algorithm>
+
+namespace ckv {
+
+static int64_t gcd64(int64_t a, int64_t b)
+{
+    while (b) { int64_t r = a % b; a = b; b = r; }
+    return a;
+}
+
+// Alg. 2 applied to Q tokens in order, scores aside.  The items offered to cascade c arrive
+// at times tau_k = first + k*step (an arithmetic progression: cascade c-1 only evicts at its
+// own accepting times once it is full).  Offer k is
+//   APPEND  while the cascade is not full (accepting or eager add),
+//   PUSH    when full and tau_k mod period == 0 (the oldest item moves on to cascade c+1),
+//   SELECT  when full otherwise (competes with the newest item, one of the two is lost).
+void plan_update(const Geom& g, HostState& st, int Q, UpdatePlan& plan)
+{
+    plan.Q = Q;
+    plan.N = g.N;
+    plan.sink_fill0 = st.sink_fill;
+    plan.n_to_sink = std::min(Q, g.n_sink - st.sink_fill);
+    plan.id0 = (int)st.n_seen;
+    const int Qc = Q - plan.n_to_sink;
+
+    int64_t first = st.t, step = 1;
+    int M = Qc;
+    for (int c = 0; c < g.N; ++c) {
+        CascStep& cs = plan.c[c];
+        const int cap = g.cap[c];
+        const int64_t f = g.period[c];
+        const bool full0 = st.count[c] == cap;
+        cs.cap = cap;
+        cs.base = g.base[c];
+        cs.M = M;
+        cs.A = std::min(M, cap - st.count[c]);
+        cs.pstride = (int)(f / gcd64(step, f));
+        // offers at accepting times are k = ka + i*pstride for the smallest such ka >= 0
+        int ka = -1;
+        for (int k = 0; k < cs.pstride && k < M; ++k)
+            if ((first + (int64_t)k * step) % f == 0) { ka = k; break; }
+        cs.kp0 = M;
+        cs.P = 0;
+        if (ka >= 0) {
+            st.accepted[c] += (M - 1 - ka) / cs.pstride + 1;
+            int k = ka;
+            if (k < cs.A) k += ((cs.A - k + cs.pstride - 1) / cs.pstride) * cs.pstride;
+            if (k < M) { cs.kp0 = k; cs.P = (M - 1 - k) / cs.pstride + 1; }
+        }
+        cs.J = cs.A + cs.P;
+        cs.wpos0 = full0 ? st.xi[c] : st.count[c];
+        cs.newest0 = full0 ? (st.xi[c] + cap - 1) % cap : 0;
+        cs.pre = (full0 && M > 0 && cs.kp0 > 0) ? 1 : 0;
+
+        st.discards[c] += M - cs.A - cs.P;              // every SELECT loses one item
+        if (c == g.N - 1) st.discards[c] += cs.P;       // evicted from the last cascade
+        st.count[c] += cs.A;
+        if (st.count[c] == cap) st.xi[c] = (int)(((int64_t)(full0 ? st.xi[c] : 0) + cs.P) % cap);
+
+        if (cs.P > 0) { first += (int64_t)cs.kp0 * step; step *= cs.pstride; }
+        M = cs.P;
+    }
+    st.t += Qc;
+    st.n_seen += Q;
+    st.sink_fill += plan.n_to_sink;
+}
+
+// Cache order is sinks, last cascade oldest..newest, ..., first cascade (Section 3.1
+// "Positional Encoding": the index inside the cache).  Stored keys are rotated to their
+// physical slot index, so within a run where (cache index - slot index) is constant the
+// queries need one rotation: by (own index) - (that constant).
+void build_segments(const Geom& g, const HostState& st, bool with_chunk, int Q, SegList& out)
+{
+    out.n = 0;
+    out.n_qvar = 0;
+    const int n = st.n_cached(g);
+    out.n_cached = n;
+    auto add = [&](int start, int len, int delta, int chunk) {
+        if (len <= 0) return;
+        const int rot0 = n - delta;
+        int v = -1;
+        for (int i = 0; i < out.n_qvar; ++i) if (out.qrot0[i] == rot0) v = i;
+        if (v < 0) { v = out.n_qvar++; out.qrot0[v] = rot0; }
+        Seg& s = out.s[out.n++];
+        s.start = start; s.len = len; s.qvar = v; s.chunk = chunk;
+    };
+    add(0, st.sink_fill, 0, 0);
+    int rank = st.sink_fill;                         // cache index of the oldest item of the cascade
+    for (int c = g.N - 1; c >= 0; --c) {
+        const int cnt = st.count[c], cap = g.cap[c], xi = st.xi[c], base = g.base[c];
+        if (cnt < cap) {
+            add(base, cnt, rank - base, 0);
+        } else {
+            add(base + xi, cap - xi, rank - (base + xi), 0);          // oldest part: ring [xi, cap)
+            add(base, xi, rank + (cap - xi) - base, 0);               // wrapped part: ring [0, xi)
+        }
+        rank += cnt;
+    }
+    if (with_chunk) add(0, Q, n, 1);                 // chunk key i is rotated to i and sits at n + i
+}
+
+int slot_of_rank(const Geom& g, const HostState& st, int r)
+{
+    if (r < st.sink_fill) return r;
+    r -= st.sink_fill;
+    for (int c = g.N - 1; c >= 0; --c) {
+        const int cnt = st.count[c];
+        if (r < cnt) return g.base[c] + (cnt < g.cap[c] ? r : (st.xi[c] + r) % g.cap[c]);
+        r -= cnt;
+    }
+    return -1;
+}
+
+}  // namespace ckv

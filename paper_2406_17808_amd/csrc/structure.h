@@ -1,0 +1,43 @@
+// Host-side mirror of the score-independent part of the cache state.
+//
+// In Alg. 2 only the CONTENT of a slot depends on the attention scores (token selection
+// replaces the newest item in place).  How full every sub-cache is, where its ring head
+// sits (Section 3.1 "Circular Buffers") and when it accepts are functions of the number of
+// tokens seen alone, identical for every sequence and KV head.  The host therefore tracks
+// them itself and never has to read anything back from the device to size a launch.
+#pragma once
+
+#include <stdint.h>
+
+#include "internal.h"
+
+namespace ckv {
+
+struct HostState {
+    int sink_fill = 0;
+    int count[kMaxCascades] = {0};
+    int xi[kMaxCascades] = {0};        // ring index of the oldest item; 0 while the cascade is filling
+    int64_t t = 0;                     // tokens offered to the first cascade so far
+    int64_t n_seen = 0;                // tokens consumed so far
+    int64_t accepted[kMaxCascades] = {0};
+    int64_t discards[kMaxCascades] = {0};
+
+    int n_cached(const Geom& g) const
+    {
+        int n = sink_fill;
+        for (int c = 0; c < g.N; ++c) n += count[c];
+        return n;
+    }
+};
+
+// Structure of inserting Q tokens in order (Alg. 2 applied Q times); advances `st`.
+void plan_update(const Geom& g, HostState& st, int Q, UpdatePlan& plan);
+
+// Runs of physical rows that share one query rotation, for the state BEFORE a chunk of Q tokens.
+// with_chunk: append the segment of the chunk's own keys.
+void build_segments(const Geom& g, const HostState& st, bool with_chunk, int Q, SegList& out);
+
+// physical slot of the r-th entry in cache order (r < n_cached)
+int slot_of_rank(const Geom& g, const HostState& st, int r);
+
+}  // namespace ckv

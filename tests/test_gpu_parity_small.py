@@ -1,0 +1,134 @@
+"""GPU parity on small configurations: every output row, every decision score and every cache
+membership is compared with the CPU oracle (see gpu_harness.py for how parity is decomposed)."""
+import numpy as np
+import pytest
+
+from paper_2406_17808_amd import binding as B
+from paper_2406_17808_amd.workloads import WORKLOADS, chunk_inputs, round_to_bf16
+
+pytestmark = pytest.mark.gpu
+
+
+def _inputs(rng, cfg, n, scale=1.0):
+    shape_q = (cfg.batch, n, cfg.n_q_heads, cfg.head_dim)
+    shape_k = (cfg.batch, n, cfg.n_kv_heads, cfg.head_dim)
+    q, k, v = (rng.standard_normal(s).astype(np.float32) * np.float32(scale) for s in (shape_q, shape_k, shape_k))
+    if cfg.dtype == B.CASCADE_BF16:
+        q, k, v = round_to_bf16(q), round_to_bf16(k), round_to_bf16(v)
+    return q, k, v
+
+
+def _tolerances(cfg):
+    # outputs: the bar of the benchmark spec; scores: same arithmetic, same bar with headroom for
+    # sums of few terms (bf16: operand rounding of rotated q and k, 2^-9 each, over d terms)
+    return (2e-2, 6e-2) if cfg.dtype == B.CASCADE_BF16 else (1e-5, 5e-5)
+
+
+def test_tiny_f32_free_running(oracle_mod):
+    """The fp32 configuration: 2048 tokens, 4 sinks + 4 x 64 slots, chunks of 32, free running.
+    Membership must equal the oracle's after every chunk (bit-exact), outputs within 1e-5."""
+    from gpu_harness import ParityRun
+    from paper_2406_17808_amd.cache import config_of
+    wl = WORKLOADS["tiny_f32"]
+    cfg = config_of(wl, keep_update_scores=1)
+    run = ParityRun(cfg, one_step_ahead=False)
+    worst_out = worst_score = 0.0
+    for c in range(wl.n_chunks):
+        q, k, v = chunk_inputs(wl, 0, c)
+        rep = run.step(q, k, v)
+        assert rep.replay_exact, c
+        assert rep.drift == 0, (c, rep)
+        worst_out, worst_score = max(worst_out, rep.out_err), max(worst_score, rep.score_err)
+    print(f"tiny_f32: max out err {worst_out:.3e}, max score err {worst_score:.3e}")
+    assert worst_out <= 1e-5
+    assert worst_score <= 5e-5
+    st = run.gpu.read_state()
+    assert st.counts.tolist() == [4, 64, 64, 64, 64] and st.n_seen == 2048
+    run.close()
+
+
+@pytest.mark.parametrize("case", [
+    dict(name="bf16_d128_ragged", dtype=B.CASCADE_BF16, d=128, Hq=8, Hkv=2, batch=1, n_sink=5,
+         sizes=[48, 40, 36], chunks=[1, 7, 64, 100, 33, 128, 128, 2, 90, 128, 128, 77, 128, 128, 128], max_chunk=128),
+    dict(name="bf16_d64_batch2", dtype=B.CASCADE_BF16, d=64, Hq=4, Hkv=4, batch=2, n_sink=3,
+         sizes=[70, 70], chunks=[50, 50, 50, 50, 50, 13, 96, 96, 96, 96], max_chunk=96),
+    dict(name="bf16_chunk_larger_than_cache", dtype=B.CASCADE_BF16, d=128, Hq=4, Hkv=1, batch=1, n_sink=4,
+         sizes=[8, 8, 8], chunks=[300, 300, 17, 300], max_chunk=300),
+    dict(name="bf16_big_tiles", dtype=B.CASCADE_BF16, d=128, Hq=8, Hkv=2, batch=1, n_sink=64,
+         sizes=[256, 256, 256, 256], chunks=[512] * 8, max_chunk=512),
+    dict(name="f32_periods_mean", dtype=B.CASCADE_F32, d=32, Hq=4, Hkv=2, batch=2, n_sink=2,
+         sizes=[9, 5, 7], chunks=[20, 3, 20, 20, 1, 20, 20, 20], max_chunk=20, periods=[1, 3, 2],
+         head_reduce=B.CASCADE_REDUCE_MEAN),
+    dict(name="f32_no_selection_one_cascade", dtype=B.CASCADE_F32, d=64, Hq=2, Hkv=2, batch=1, n_sink=4,
+         sizes=[24], chunks=[10] * 8, max_chunk=10, token_selection=0),
+    dict(name="f32_all_rows_in_scores", dtype=B.CASCADE_F32, d=64, Hq=2, Hkv=1, batch=1, n_sink=2,
+         sizes=[16, 16], chunks=[40] * 5, max_chunk=40, beta=0.999, score_tail_eps=-1.0),
+], ids=lambda c: c["name"])
+def test_prefill_one_step_ahead(oracle_mod, case):
+    from gpu_harness import ParityRun
+    cfg = B.make_config(batch=case["batch"], n_q_heads=case["Hq"], n_kv_heads=case["Hkv"], head_dim=case["d"],
+                        dtype=case["dtype"], n_sink=case["n_sink"], cascade_sizes=case["sizes"],
+                        ema_beta=case.get("beta", 0.9), rope_base=10000.0, max_chunk=case["max_chunk"],
+                        accept_period=case.get("periods"), head_reduce=case.get("head_reduce", 0),
+                        token_selection=case.get("token_selection", 1),
+                        score_tail_eps=case.get("score_tail_eps", 0.0), keep_update_scores=1)
+    tol_out, tol_score = _tolerances(cfg)
+    rng = np.random.default_rng(7)
+    run = ParityRun(cfg, one_step_ahead=True)
+    drift = compared = 0
+    worst_out = worst_score = 0.0
+    for i, n in enumerate(case["chunks"]):
+        q, k, v = _inputs(rng, cfg, n)
+        rep = run.step(q, k, v)
+        assert rep.replay_exact, (case["name"], i)
+        worst_out, worst_score = max(worst_out, rep.out_err), max(worst_score, rep.score_err)
+        drift += rep.drift
+        compared += rep.compared
+    print(f"{case['name']}: out {worst_out:.3e} score {worst_score:.3e} drift {drift}/{compared}")
+    assert worst_out <= tol_out
+    assert worst_score <= tol_score
+    # membership may only differ from the free oracle where score gaps are inside float noise
+    assert drift <= (0.02 * compared if cfg.dtype == B.CASCADE_BF16 else 0), (drift, compared)
+    run.close()
+
+
+@pytest.mark.parametrize("dtype,d", [(B.CASCADE_F32, 64), (B.CASCADE_BF16, 128)])
+def test_prefill_then_decode(oracle_mod, dtype, d):
+    """A decode step has the semantics of a chunk of one token (Eq. 2)."""
+    from gpu_harness import ParityRun
+    cfg = B.make_config(batch=2, n_q_heads=8, n_kv_heads=2, head_dim=d, dtype=dtype, n_sink=4,
+                        cascade_sizes=[20, 12, 12], ema_beta=0.9, rope_base=10000.0, max_chunk=64,
+                        keep_update_scores=1)
+    tol_out, tol_score = _tolerances(cfg)
+    rng = np.random.default_rng(8)
+    run = ParityRun(cfg, one_step_ahead=True)
+    # decode from an empty cache, prefill, decode again
+    plan = [("d", 1)] * 6 + [("p", 64), ("p", 37)] + [("d", 1)] * 40
+    worst_out = worst_score = 0.0
+    for i, (kind, n) in enumerate(plan):
+        q, k, v = _inputs(rng, cfg, n)
+        rep = run.step(q, k, v, decode=(kind == "d"))
+        assert rep.replay_exact, i
+        worst_out, worst_score = max(worst_out, rep.out_err), max(worst_score, rep.score_err)
+    print(f"prefill_then_decode {dtype}: out {worst_out:.3e} score {worst_score:.3e}")
+    assert worst_out <= tol_out and worst_score <= tol_score
+    run.close()
+
+
+def test_error_paths_on_device(oracle_mod):
+    import torch
+    from paper_2406_17808_amd.cache import CascadeKVCache
+    cfg = B.make_config(batch=1, n_q_heads=2, n_kv_heads=1, head_dim=64, dtype=B.CASCADE_F32, n_sink=1,
+                        cascade_sizes=[4], ema_beta=0.9, rope_base=10000.0, max_chunk=8)
+    c = CascadeKVCache(cfg)
+    q = torch.zeros(1, 9, 2, 64, device="cuda:0")
+    kv = torch.zeros(1, 9, 1, 64, device="cuda:0")
+    with pytest.raises(B.CascadeError) as e:
+        c.prefill_chunk(q, kv, kv)
+    assert e.value.code == B.CASCADE_E_BAD_ARG
+    with pytest.raises(B.CascadeError) as e:
+        B.cascade_prefill_chunk(c.ctx, 0, kv.data_ptr(), kv.data_ptr(), 4, q.data_ptr())
+    assert e.value.code == B.CASCADE_E_NULL_ARG
+    st = c.read_state()
+    assert st.count == 0 and st.n_seen == 0
+    c.close()
