@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the cascading KV cache hot path on one MI355X.
+
+A step is one pass of the whole prefill hot path over one chunk of the workload: query/key
+rotation, chunk attention, exact EMA score sums and the cascade update (one call of
+cascade_prefill_chunk).  The default workload is the 1M-token / 65K-slot prefill; warm-up
+chunks are the first chunks of the stream (32 of them fill the cache), the timed chunks follow.
+The single JSON line also carries the decode-step latency of the batch-32 decode workload, the
+roofline figures of the dominant kernel of each, and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK = 2.5e15     # dense bf16 MFMA FLOP/s of one MI355X
+HBM_PEAK = 8.0e12           # bytes/s
+
+
+def prefill_bench(args, torch, B, wl):
+    from paper_2406_17808_amd.cache import CascadeKVCache, config_of
+    from paper_2406_17808_amd.workloads import chunk_inputs_torch
+    dev = "cuda:0"
+    W, K = args.warmup, args.steps
+    assert W + K <= wl.n_chunks, f"{wl.name} has only {wl.n_chunks} chunks"
+    cfg = config_of(wl)
+    cache = CascadeKVCache(cfg, dev)
+    chunks = [chunk_inputs_torch(wl, args.seed, c, dev) for c in range(W + K)]
+    out = torch.empty_like(chunks[0][0])
+    # cached rows before every chunk (host arithmetic; the fill does not depend on the scores)
+    n_before = [B.cascade_simulate_structure(cfg, [wl.chunk] * c).count if c else 0 for c in range(W + K)]
+    for c in range(W):
+        cache.prefill_chunk(*chunks[c], out=out)
+    torch.cuda.synchronize()
+    B.cascade_profile_begin(cache.ctx)
+    t0 = time.perf_counter()
+    for c in range(W, W + K):
+        cache.prefill_chunk(*chunks[c], out=out)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = B.cascade_profile_end(cache.ctx)
+    seconds = t1 - t0
+    tokens = K * wl.chunk * wl.batch
+    Q, d = wl.chunk, wl.head_dim
+    # algorithmic work of the attention kernel: one QK^T and one PV over the visible pairs
+    flops = [4.0 * d * wl.n_q_heads * wl.batch * (Q * n_before[c] + Q * (Q + 1) / 2) for c in range(W, W + K)]
+    attn_ms, attn_n = prof["attention"]
+    avg_s = attn_ms / 1e3 / max(attn_n, 1)
+    achieved = (sum(flops) / K) / avg_s
+    res = {
+        "tokens_per_s": tokens / seconds, "ms_per_step": seconds * 1e3 / K,
+        "kernel_ms_per_step": {k: v[0] / max(v[1], 1) for k, v in prof.items() if v[1]},
+        "roofline": {"bound": "mfma", "kernel": "attn_mfma_kernel", "achieved": achieved / 1e12,
+                     "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK,
+                     "traffic": None, "flop_per_launch": sum(flops) / K, "avg_launch_ms": avg_s * 1e3},
+        "end_to_end_mfma_frac": (sum(flops) / seconds) / MFMA_BF16_PEAK,
+    }
+    return res, cache, chunks, cfg
+
+
+def cpu_baseline(args, torch, B, wl, cache, cfg, chunks):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the same workload:
+    `sample_tokens` tokens against the cache the GPU run ended with, all KV heads."""
+    import numpy as np
+    from oracle import OracleConfig, OracleSeq
+    st = cache.read_state(with_kv=True)
+    o = OracleSeq(OracleConfig(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.n_sink, list(wl.cascade_sizes),
+                               float(np.float32(wl.ema_beta)), wl.rope_base))
+    n = st.count
+    for g in range(wl.n_kv_heads):
+        o.set_state(g, st.ids[0, g, :n].astype(np.int64), st.mu[0, g, :n].astype(np.float64), st.counts,
+                    st.k[0, g, :n], st.v[0, g, :n], st.t, st.n_seen)
+    m = args.cpu_sample_tokens
+    q, k, v = (x[0, :m].float().cpu().numpy() for x in chunks[-1])
+    t0 = time.perf_counter()
+    o.chunk(q, k, v)
+    dt = time.perf_counter() - t0
+    threads = min(int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)), wl.n_kv_heads)
+    o.close()
+    return {"value": m / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"{m} tokens of {wl.name} against the {n}-row cache the GPU run ended with, "
+                      f"all {wl.n_kv_heads} KV heads ({dt:.1f} s)"}
+
+
+def decode_bench(args, torch, B):
+    from paper_2406_17808_amd.cache import CascadeKVCache, config_of
+    from paper_2406_17808_amd.workloads import WORKLOADS
+    wl = WORKLOADS["decode_b32"]
+    dev = "cuda:0"
+    cfg = config_of(wl, max_chunk=1)
+    slots, d = wl.n_slots, wl.head_dim
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(args.seed + 12345)
+    shape = (wl.batch, wl.n_kv_heads, slots, d)
+    k0 = torch.randn(shape, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    v0 = torch.randn(shape, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    mu0 = torch.rand(shape[:3], generator=gen, device=dev, dtype=torch.float32)
+    total = 4 * slots
+    ids0 = torch.cat([torch.arange(wl.n_sink), torch.arange(total - (slots - wl.n_sink), total)]).to(torch.int32)
+    ids0 = ids0.to(dev).expand(wl.batch, wl.n_kv_heads, slots).contiguous()
+    st = B.cascade_init_state()
+    st.dev_k, st.dev_v, st.dev_mu, st.dev_ids = k0.data_ptr(), v0.data_ptr(), mu0.data_ptr(), ids0.data_ptr()
+    st.counts[0] = wl.n_sink
+    for i, c in enumerate(wl.cascade_sizes):
+        st.counts[1 + i] = c
+    st.t, st.n_seen = total - wl.n_sink, total
+    cache = CascadeKVCache(cfg, dev, st)
+    torch.cuda.synchronize()
+    del k0, v0
+    steps, warm = args.decode_steps, args.decode_warmup
+    n_in = 64   # distinct step inputs, cycled
+    qs = torch.randn((n_in, wl.batch, wl.n_q_heads, d), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    ks = torch.randn((n_in, wl.batch, wl.n_kv_heads, d), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    vs = torch.randn((n_in, wl.batch, wl.n_kv_heads, d), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    out = torch.empty_like(qs[0])
+    for i in range(warm):
+        cache.decode_step(qs[i % n_in], ks[i % n_in], vs[i % n_in], out=out)
+    torch.cuda.synchronize()
+    B.cascade_profile_begin(cache.ctx)
+    t0 = time.perf_counter()
+    for i in range(warm, warm + steps):
+        cache.decode_step(qs[i % n_in], ks[i % n_in], vs[i % n_in], out=out)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = B.cascade_profile_end(cache.ctx)
+    BH = wl.batch * wl.n_kv_heads
+    # algorithmic bytes of a step: every cached K and V row once, scores read and written once
+    bytes_step = BH * slots * (2 * d * 2 + 8)
+    qk_ms, qk_n = prof["decode_qk"]
+    k_bytes = BH * slots * d * 2
+    res = {
+        "decode_step_us": dt / steps * 1e6, "decode_steps": steps, "decode_tokens_per_s": wl.batch * steps / dt,
+        "decode_hbm_frac": bytes_step / (dt / steps) / HBM_PEAK,
+        "decode_kernel_us": {k: v[0] / max(v[1], 1) * 1e3 for k, v in prof.items() if v[1]},
+        "roofline_decode": {"bound": "hbm", "kernel": "decode_qk_kernel", "achieved": k_bytes / (qk_ms / 1e3 / max(qk_n, 1)) / 1e9,
+                            "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                            "frac": k_bytes / (qk_ms / 1e3 / max(qk_n, 1)) / HBM_PEAK, "traffic": None},
+    }
+    cache.close()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=224)
+    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--workload", default="prefill_1m")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=128)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--decode-steps", type=int, default=256)
+    ap.add_argument("--decode-warmup", type=int, default=16)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this path runs on ONE GPU (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2406_17808_amd import binding as B
+    from paper_2406_17808_amd.workloads import WORKLOADS
+    B.load_library()   # fails loudly if the HIP library has not been built
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    wl = WORKLOADS[args.workload]
+    res, cache, chunks, cfg = prefill_bench(args, torch, B, wl)
+    line = {
+        "metric": "prefill_tokens_per_s_per_layer", "value": res["tokens_per_s"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "seq_len": wl.seq_len, "chunk": wl.chunk, "n_sink": wl.n_sink,
+                   "cascades": list(wl.cascade_sizes), "n_q_heads": wl.n_q_heads, "n_kv_heads": wl.n_kv_heads,
+                   "head_dim": wl.head_dim, "ema_beta": wl.ema_beta, "timed_chunks": [args.warmup, args.warmup + args.steps]},
+        "roofline": res["roofline"], "kernel_ms_per_step": res["kernel_ms_per_step"],
+        "end_to_end_mfma_frac": res["end_to_end_mfma_frac"],
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(args, torch, B, wl, cache, cfg, chunks)
+    cache.close()
+    del cache, chunks
+    torch.cuda.empty_cache()
+    if not args.no_decode:
+        line.update(decode_bench(args, torch, B))
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

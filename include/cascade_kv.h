@@ -189,6 +189,30 @@ int cascade_read_state(cascade_ctx* ctx, cascade_state_view* view, void* stream)
 int cascade_simulate_structure(const cascade_config* cfg, const int32_t* chunk_sizes, int32_t n_chunks,
                                const float* host_scores, cascade_state_view* view);
 
+/*
+ * Diagnostics: per-kernel-family GPU time measured with HIP events recorded on the stream of
+ * each call, around the launches of that family.  cascade_profile_begin starts (and resets) the
+ * collection; cascade_profile_end waits for all recorded events and returns, per family, the
+ * summed milliseconds and the number of timed intervals.  While collecting, every call creates
+ * events (host allocations), so leave it off in production loops.
+ */
+enum {
+    CASCADE_K_PREP = 0,        /* query / chunk-key rotation */
+    CASCADE_K_ATTENTION = 1,   /* chunk attention (QK^T, softmax, PV) */
+    CASCADE_K_SCORES = 2,      /* exact EMA score sums */
+    CASCADE_K_UPDATE = 3,      /* cascade plan + row moves */
+    CASCADE_K_DECODE_QK = 4,
+    CASCADE_K_DECODE_PV = 5,
+    CASCADE_K_DECODE_FINISH = 6,
+    CASCADE_K_FAMILIES = 7
+};
+typedef struct cascade_profile {
+    double ms[CASCADE_K_FAMILIES];
+    int64_t intervals[CASCADE_K_FAMILIES];
+} cascade_profile;
+int cascade_profile_begin(cascade_ctx* ctx);
+int cascade_profile_end(cascade_ctx* ctx, cascade_profile* out);
+
 /* Text of the last error of this context (or of the last failed cascade_init if ctx is NULL). */
 const char* cascade_last_error(const cascade_ctx* ctx);
 

@@ -30,7 +30,11 @@ CASCADE_REDUCE_MEAN = 1
 EXPORTED_SYMBOLS = [
     "cascade_workspace_bytes", "cascade_init", "cascade_destroy", "cascade_prefill_chunk",
     "cascade_decode_step", "cascade_read_state", "cascade_simulate_structure", "cascade_last_error",
+    "cascade_profile_begin", "cascade_profile_end",
 ]
+
+CASCADE_K_FAMILIES = 7
+KERNEL_FAMILIES = ["prep", "attention", "scores", "update", "decode_qk", "decode_pv", "decode_finish"]
 
 
 class CascadeError(RuntimeError):
@@ -75,6 +79,10 @@ class cascade_state_view(ctypes.Structure):
     ]
 
 
+class cascade_profile(ctypes.Structure):
+    _fields_ = [("ms", ctypes.c_double * CASCADE_K_FAMILIES), ("intervals", ctypes.c_int64 * CASCADE_K_FAMILIES)]
+
+
 _LIB = None
 
 
@@ -103,6 +111,10 @@ def load_library():
         L.cascade_simulate_structure.restype = ctypes.c_int
         L.cascade_simulate_structure.argtypes = [ctypes.POINTER(cascade_config), P, ctypes.c_int32, P,
                                                  ctypes.POINTER(cascade_state_view)]
+        L.cascade_profile_begin.restype = ctypes.c_int
+        L.cascade_profile_begin.argtypes = [P]
+        L.cascade_profile_end.restype = ctypes.c_int
+        L.cascade_profile_end.argtypes = [P, ctypes.POINTER(cascade_profile)]
         L.cascade_last_error.restype = ctypes.c_char_p
         L.cascade_last_error.argtypes = [P]
         _LIB = L
@@ -159,6 +171,17 @@ def cascade_prefill_chunk(ctx, dev_q: int, dev_k: int, dev_v: int, n_tokens: int
 
 def cascade_decode_step(ctx, dev_q: int, dev_k: int, dev_v: int, dev_out: int, stream: int = 0) -> None:
     _check(load_library().cascade_decode_step(ctx, dev_q, dev_k, dev_v, dev_out, stream), ctx)
+
+
+def cascade_profile_begin(ctx) -> None:
+    _check(load_library().cascade_profile_begin(ctx), ctx)
+
+
+def cascade_profile_end(ctx) -> dict:
+    """{family: (milliseconds, intervals)} of the kernels launched since cascade_profile_begin."""
+    p = cascade_profile()
+    _check(load_library().cascade_profile_end(ctx, ctypes.byref(p)), ctx)
+    return {name: (float(p.ms[i]), int(p.intervals[i])) for i, name in enumerate(KERNEL_FAMILIES)}
 
 
 class StateArrays:

@@ -26,7 +26,26 @@ struct cascade_ctx {
     int max_chunk;
     int tail_k;          // rows of a chunk (counted from its end) that enter the score sums
     bool mfma;
+    bool profiling = false;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> prof[CASCADE_K_FAMILIES];
     std::string err;
+};
+
+// Brackets the launches of one kernel family with two events when profiling is on.
+struct Timed {
+    cascade_ctx* ctx;
+    int fam;
+    hipStream_t s;
+    hipEvent_t stop = nullptr;
+    Timed(cascade_ctx* c, int f, hipStream_t st) : ctx(c), fam(f), s(st)
+    {
+        if (!ctx->profiling) return;
+        hipEvent_t start;
+        if (hipEventCreate(&start) != hipSuccess || hipEventCreate(&stop) != hipSuccess) { stop = nullptr; return; }
+        (void)hipEventRecord(start, s);
+        ctx->prof[fam].push_back({start, stop});
+    }
+    ~Timed() { if (stop) (void)hipEventRecord(stop, s); }
 };
 
 static thread_local std::string g_init_error;
@@ -243,7 +262,48 @@ extern "C" int cascade_init(const cascade_config* cfg, void* dev_workspace, size
     return CASCADE_OK;
 }
 
-extern "C" void cascade_destroy(cascade_ctx* ctx) { delete ctx; }
+static void drop_events(cascade_ctx* ctx)
+{
+    for (auto& fam : ctx->prof) {
+        for (auto& ev : fam) { (void)hipEventDestroy(ev.first); (void)hipEventDestroy(ev.second); }
+        fam.clear();
+    }
+}
+
+extern "C" void cascade_destroy(cascade_ctx* ctx)
+{
+    if (!ctx) return;
+    drop_events(ctx);
+    delete ctx;
+}
+
+extern "C" int cascade_profile_begin(cascade_ctx* ctx)
+{
+    if (!ctx) return CASCADE_E_NULL_ARG;
+    drop_events(ctx);
+    ctx->profiling = true;
+    return CASCADE_OK;
+}
+
+extern "C" int cascade_profile_end(cascade_ctx* ctx, cascade_profile* out)
+{
+    if (!ctx) return CASCADE_E_NULL_ARG;
+    if (!out) return fail(ctx, CASCADE_E_NULL_ARG, "cascade_profile_end: NULL output");
+    ctx->profiling = false;
+    memset(out, 0, sizeof(*out));
+    for (int f = 0; f < CASCADE_K_FAMILIES; ++f)
+        for (auto& ev : ctx->prof[f]) {
+            int rc = hip_check(ctx, hipEventSynchronize(ev.second), "cascade_profile_end: event");
+            if (rc) { drop_events(ctx); return rc; }
+            float ms = 0.f;
+            rc = hip_check(ctx, hipEventElapsedTime(&ms, ev.first, ev.second), "cascade_profile_end: elapsed");
+            if (rc) { drop_events(ctx); return rc; }
+            out->ms[f] += ms;
+            out->intervals[f] += 1;
+        }
+    drop_events(ctx);
+    return CASCADE_OK;
+}
 
 extern "C" const char* cascade_last_error(const cascade_ctx* ctx) { return ctx ? ctx->err.c_str() : g_init_error.c_str(); }
 
@@ -273,21 +333,31 @@ extern "C" int cascade_prefill_chunk(cascade_ctx* ctx, const void* dev_q, const 
 
     SegList sl;
     build_segments(g, ctx->st, true, Q, sl);
-    launch_prep(g, ctx->dtype, ctx->buf, sl, Q, dev_q, dev_k, dev_v, s);
-    if (ctx->mfma) launch_attn_mfma(g, ctx->buf, sl, Q, ctx->max_chunk, dev_out, s);
-    else launch_attn_simple(g, ctx->dtype, ctx->buf, sl, Q, ctx->max_chunk, dev_out, s);
-
+    {
+        Timed t(ctx, CASCADE_K_PREP, s);
+        launch_prep(g, ctx->dtype, ctx->buf, sl, Q, dev_q, dev_k, dev_v, s);
+    }
+    {
+        Timed t(ctx, CASCADE_K_ATTENTION, s);
+        if (ctx->mfma) launch_attn_mfma(g, ctx->buf, sl, Q, ctx->max_chunk, dev_out, s);
+        else launch_attn_simple(g, ctx->dtype, ctx->buf, sl, Q, ctx->max_chunk, dev_out, s);
+    }
     const int tail = Q < ctx->tail_k ? Q : ctx->tail_k;
     const float decay = (float)pow((double)g.beta, (double)Q);
-    if (ctx->mfma) launch_score_mfma(g, ctx->buf, sl, Q, ctx->max_chunk, tail, decay, s);
-    else launch_score_simple(g, ctx->dtype, ctx->buf, sl, Q, ctx->max_chunk, tail, decay, s);
-
+    {
+        Timed t(ctx, CASCADE_K_SCORES, s);
+        if (ctx->mfma) launch_score_mfma(g, ctx->buf, sl, Q, ctx->max_chunk, tail, decay, s);
+        else launch_score_simple(g, ctx->dtype, ctx->buf, sl, Q, ctx->max_chunk, tail, decay, s);
+    }
     int rc = snapshot_scores(ctx, Q, s);
     if (rc) return rc;
     UpdatePlan pl;
     plan_update(g, ctx->st, Q, pl);
-    launch_plan(g, ctx->buf, pl, ctx->max_chunk, s);
-    launch_moves(g, ctx->dtype, ctx->buf, pl, ctx->max_chunk, dev_k, dev_v, g.Hkv * g.d, Q * g.Hkv * g.d, s);
+    {
+        Timed t(ctx, CASCADE_K_UPDATE, s);
+        launch_plan(g, ctx->buf, pl, ctx->max_chunk, s);
+        launch_moves(g, ctx->dtype, ctx->buf, pl, ctx->max_chunk, dev_k, dev_v, g.Hkv * g.d, Q * g.Hkv * g.d, s);
+    }
     return hip_check(ctx, hipGetLastError(), "cascade_prefill_chunk");
 }
 
@@ -305,14 +375,27 @@ extern "C" int cascade_decode_step(cascade_ctx* ctx, const void* dev_q, const vo
 
     SegList sl;
     build_segments(g, ctx->st, false, 1, sl);
-    launch_decode(g, ctx->dtype, ctx->buf, sl, ctx->max_chunk, dev_q, dev_k, dev_v, dev_out, s);
-
+    {
+        Timed t0(ctx, CASCADE_K_DECODE_QK, s);
+        launch_decode_qk(g, ctx->dtype, ctx->buf, sl, dev_q, dev_k, s);
+    }
+    {
+        Timed t1(ctx, CASCADE_K_DECODE_PV, s);
+        launch_decode_pv(g, ctx->dtype, ctx->buf, sl, s);
+    }
+    {
+        Timed t2(ctx, CASCADE_K_DECODE_FINISH, s);
+        launch_decode_finish(g, ctx->dtype, ctx->buf, sl, ctx->max_chunk, dev_v, dev_out, s);
+    }
     int rc = snapshot_scores(ctx, 1, s);
     if (rc) return rc;
     UpdatePlan pl;
     plan_update(g, ctx->st, 1, pl);
-    launch_plan(g, ctx->buf, pl, ctx->max_chunk, s);
-    launch_moves(g, ctx->dtype, ctx->buf, pl, ctx->max_chunk, dev_k, dev_v, g.Hkv * g.d, g.Hkv * g.d, s);
+    {
+        Timed t3(ctx, CASCADE_K_UPDATE, s);
+        launch_plan(g, ctx->buf, pl, ctx->max_chunk, s);
+        launch_moves(g, ctx->dtype, ctx->buf, pl, ctx->max_chunk, dev_k, dev_v, g.Hkv * g.d, g.Hkv * g.d, s);
+    }
     return hip_check(ctx, hipGetLastError(), "cascade_decode_step");
 }
 

@@ -32,9 +32,131 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi)
     return (a >> 16) | (b & 0xFFFF0000u);
 }
 
-constexpr int kAttnThreads = 256;
-constexpr int kBM = 256;   // query rows per workgroup: 4 waves x 2 blocks of 32
-constexpr int kBN = 64;    // keys per tile
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+
+// two floats -> packed bf16 pair (v_cvt_pk_bf16_f32, round to nearest even)
+__device__ inline uint32_t cvt_pk_bf16(float lo, float hi)
+{
+    const f32x2_t x = {lo, hi};
+    const bf16x2_t y = __builtin_convertvector(x, bf16x2_t);
+    return __builtin_bit_cast(uint32_t, y);
+}
+
+// max over the two lanes l and l^32 (they hold the two halves of one query's keys)
+__device__ inline float max_xor32(float x)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+constexpr int kAttnThreads = 512;  // 8 waves: two per SIMD, so one wave's softmax overlaps the other's MFMAs
+constexpr int kBM = 256;           // query rows per workgroup: one 32-row block per wave
+constexpr int kBN = 64;            // keys per tile
+constexpr float kRescaleLog2 = 8.f;   // the running maximum is only raised when it grew by 2^8
+
+// Iterates over the 64-key tiles of all segments.  All fields are workgroup-uniform.
+struct TileIter {
+    int si, t0, len;
+    Seg sg;
+    __device__ void load(const SegList& sl, int wg_imax)
+    {
+        sg = sl.s[si];
+        len = sg.chunk ? min(sg.len, wg_imax + 1) : sg.len;   // chunk keys after the last row are never visible
+    }
+    __device__ bool valid(const SegList& sl) const { return si < sl.n; }
+    __device__ void first(const SegList& sl, int wg_imax)
+    {
+        si = 0; t0 = 0;
+        if (valid(sl)) load(sl, wg_imax);
+    }
+    __device__ void next(const SegList& sl, int wg_imax)
+    {
+        t0 += kBN;
+        if (t0 >= len) {
+            ++si; t0 = 0;
+            if (valid(sl)) load(sl, wg_imax);
+        }
+    }
+};
+
+template <int D>
+struct TileRegs {   // one thread's share of a K/V tile on its way from global memory to LDS
+    static constexpr int KP = (kBN * D / 8 + kAttnThreads - 1) / kAttnThreads;
+    static constexpr int VP = ((kBN / 4) * (D / 4) + kAttnThreads - 1) / kAttnThreads;
+    u32x4_t k[KP];
+    uint2 v[VP][4];
+};
+
+template <int D>
+__device__ inline void tile_fetch(TileRegs<D>& r, const TileIter& it, size_t bh, int slots, int Q,
+                                  const bf16_t* __restrict__ Kr, const bf16_t* __restrict__ Vc,
+                                  const bf16_t* __restrict__ Krc, const bf16_t* __restrict__ Vch, int tid)
+{
+    const bf16_t* kbase = it.sg.chunk ? Krc + bh * Q * D : Kr + (bh * slots + it.sg.start) * D;
+    const bf16_t* vbase = it.sg.chunk ? Vch + bh * Q * D : Vc + (bh * slots + it.sg.start) * D;
+#pragma unroll
+    for (int x = 0; x < TileRegs<D>::KP; ++x) {
+        const int p = tid + x * kAttnThreads;
+        if (p < kBN * D / 8) {
+            const int row = p / (D / 8), c8 = p % (D / 8);
+            const int grow = min(it.t0 + row, it.sg.len - 1);      // rows past the end repeat the last one (masked later)
+            r.k[x] = *reinterpret_cast<const u32x4_t*>(kbase + (size_t)grow * D + c8 * 8);
+        }
+    }
+#pragma unroll
+    for (int x = 0; x < TileRegs<D>::VP; ++x) {
+        const int p = tid + x * kAttnThreads;
+        if (p < (kBN / 4) * (D / 4)) {
+            const int kq = p / (D / 4), dq = p % (D / 4);
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const int grow = min(it.t0 + kq * 4 + rr, it.sg.len - 1);
+                r.v[x][rr] = *reinterpret_cast<const uint2*>(vbase + (size_t)grow * D + dq * 4);
+            }
+        }
+    }
+}
+
+// K goes to LDS row-major with a padded stride.  V is transposed in registers: a thread holds
+// 4 keys x 4 columns and writes, for each column, its 4 keys as one 8-byte piece; inside every
+// group of 16 keys the 4-key pieces are stored in the order 0,2,1,3 (the accumulator order).
+template <int D>
+__device__ inline void tile_store(const TileRegs<D>& r, bf16_t* __restrict__ Ks, bf16_t* __restrict__ Vt, int tid)
+{
+    constexpr int KSTR = D + 8, VSTR = kBN + 8;
+#pragma unroll
+    for (int x = 0; x < TileRegs<D>::KP; ++x) {
+        const int p = tid + x * kAttnThreads;
+        if (p < kBN * D / 8) {
+            const int row = p / (D / 8), c8 = p % (D / 8);
+            *reinterpret_cast<u32x4_t*>(&Ks[row * KSTR + c8 * 8]) = r.k[x];
+        }
+    }
+#pragma unroll
+    for (int x = 0; x < TileRegs<D>::VP; ++x) {
+        const int p = tid + x * kAttnThreads;
+        if (p < (kBN / 4) * (D / 4)) {
+            const int kq = p / (D / 4), dq = p % (D / 4);
+            const int sub = kq & 3, pos = ((sub & 1) << 1) | (sub >> 1);
+            const int kcol = (kq >> 2) * 16 + pos * 4;
+            const uint2* u = r.v[x];
+            uint2 w;
+            w.x = (u[0].x & 0xFFFFu) | (u[1].x << 16);
+            w.y = (u[2].x & 0xFFFFu) | (u[3].x << 16);
+            *reinterpret_cast<uint2*>(&Vt[(dq * 4 + 0) * VSTR + kcol]) = w;
+            w.x = (u[0].x >> 16) | (u[1].x & 0xFFFF0000u);
+            w.y = (u[2].x >> 16) | (u[3].x & 0xFFFF0000u);
+            *reinterpret_cast<uint2*>(&Vt[(dq * 4 + 1) * VSTR + kcol]) = w;
+            w.x = (u[0].y & 0xFFFFu) | (u[1].y << 16);
+            w.y = (u[2].y & 0xFFFFu) | (u[3].y << 16);
+            *reinterpret_cast<uint2*>(&Vt[(dq * 4 + 2) * VSTR + kcol]) = w;
+            w.x = (u[0].y >> 16) | (u[1].y & 0xFFFF0000u);
+            w.y = (u[2].y >> 16) | (u[3].y & 0xFFFF0000u);
+            *reinterpret_cast<uint2*>(&Vt[(dq * 4 + 3) * VSTR + kcol]) = w;
+        }
+    }
+}
 
 template <int D>
 __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(
@@ -46,8 +168,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(
     constexpr int DB = D / 32;        // 32-wide blocks of the head dimension in O^T
     constexpr int KSTR = D + 8;       // LDS row stride of the K tile (elements)
     constexpr int VSTR = kBN + 8;     // LDS row stride of the V^T tile (elements)
-    __shared__ __attribute__((aligned(16))) bf16_t Ks[kBN * KSTR];
-    __shared__ __attribute__((aligned(16))) bf16_t Vt[D * VSTR];
+    __shared__ __attribute__((aligned(16))) bf16_t Ks[2][kBN * KSTR];
+    __shared__ __attribute__((aligned(16))) bf16_t Vt[2][D * VSTR];
 
     const int BH = g.B * g.Hkv;
     const int bh = blockIdx.x % BH, tile = blockIdx.x / BH;   // consecutive workgroups: different KV heads
@@ -55,162 +177,113 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(
     const int tid = threadIdx.x, wave = tid >> 6, l = tid & 63, l32 = l & 31, half = l >> 5;
     const int GQ = g.G * Q;
 
-    // the two queries of this lane (one per 32-row block of the wave); rows are (head, token) pairs
-    int qi[2], qh[2];
-    bool qvalid[2];
-    int wave_imax = 0, wave_imin = Q;
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        const int r = tile * kBM + wave * 64 + qb * 32 + l32;
-        qvalid[qb] = r < GQ;
-        const int rc = min(r, GQ - 1);
-        qh[qb] = hk * g.G + rc / Q;
-        qi[qb] = rc % Q;
-    }
+    // the query of this lane; rows are (head, token) pairs
+    const int r_row = tile * kBM + wave * 32 + l32;
+    const bool qvalid = r_row < GQ;
+    const int rc = min(r_row, GQ - 1);
+    const int qh = hk * g.G + rc / Q, qi = rc % Q;
+    int wave_imax, wave_imin, wg_imax;
     {
-        const int r_lo = min(tile * kBM + wave * 64, GQ - 1), r_hi = min(tile * kBM + wave * 64 + 63, GQ - 1);
+        const int r_lo = min(tile * kBM + wave * 32, GQ - 1), r_hi = min(tile * kBM + wave * 32 + 31, GQ - 1);
         if (r_lo / Q == r_hi / Q) { wave_imin = r_lo % Q; wave_imax = r_hi % Q; }
         else { wave_imin = 0; wave_imax = Q - 1; }
-    }
-    int wg_imax;
-    {
-        const int r_lo = min(tile * kBM, GQ - 1), r_hi = min(tile * kBM + kBM - 1, GQ - 1);
-        wg_imax = (r_lo / Q == r_hi / Q) ? r_hi % Q : Q - 1;
+        const int w_lo = min(tile * kBM, GQ - 1), w_hi = min(tile * kBM + kBM - 1, GQ - 1);
+        wg_imax = (w_lo / Q == w_hi / Q) ? w_hi % Q : Q - 1;
     }
 
-    f32x16_t o[DB][2];
+    f32x16_t o[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) o[db][qb][j] = 0.f;
-    float m[2] = {-INFINITY, -INFINITY}, lsum[2] = {0.f, 0.f};
-    const float c2 = g.scale * 1.4426950408889634f;   // logits to the base-2 exponent
+        for (int j = 0; j < 16; ++j) o[db][j] = 0.f;
+    const float c2 = g.scale * 1.4426950408889634f;   // logits to base-2 exponents
+    float m_run = -INFINITY;                           // maximum the exponents are taken against
+    float lsum = 0.f;                                  // this lane's part of the row sum
 
-    Frag qf[2][KS];
-    for (int si = 0; si < sl.n; ++si) {
-        const Seg sg = sl.s[si];
-        // this segment's rotated copy of the queries
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            const bf16_t* qrow = Qr + ((((size_t)sg.qvar * g.B + b) * g.Hq + qh[qb]) * Q + qi[qb]) * D + half * 8;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) qf[qb][ks].u = *reinterpret_cast<const u32x4_t*>(qrow + ks * 16);
-        }
-        const bf16_t* kbase = sg.chunk ? Krc + (size_t)bh * Q * D : Kr + ((size_t)bh * g.slots + sg.start) * D;
-        const bf16_t* vbase = sg.chunk ? Vch + (size_t)bh * Q * D : Vc + ((size_t)bh * g.slots + sg.start) * D;
-        const int len = sg.chunk ? min(sg.len, wg_imax + 1) : sg.len;
+    TileIter cur, nxt;
+    cur.first(sl, wg_imax);
+    TileRegs<D> regs;
+    if (cur.valid(sl)) {
+        tile_fetch<D>(regs, cur, (size_t)bh, g.slots, Q, Kr, Vc, Krc, Vch, tid);
+        tile_store<D>(regs, Ks[0], Vt[0], tid);
+    }
+    __syncthreads();
 
-        for (int t0 = 0; t0 < len; t0 += kBN) {
-            __syncthreads();   // the previous tile has been consumed
-            // K tile: 64 rows of D elements, 16-byte pieces, row-major with padded stride
+    Frag qf[KS];
+    int q_seg = -1;
+    int buf = 0;
+    while (cur.valid(sl)) {
+        nxt = cur;
+        nxt.next(sl, wg_imax);
+        const bool has_next = nxt.valid(sl);
+        if (has_next) tile_fetch<D>(regs, nxt, (size_t)bh, g.slots, Q, Kr, Vc, Krc, Vch, tid);
+
+        if (!(cur.sg.chunk && cur.t0 > wave_imax)) {   // else: every key of the tile lies after this wave's rows
+            if (q_seg != cur.si) {                     // this segment's rotated copy of the queries
+                const bf16_t* qrow = Qr + ((((size_t)cur.sg.qvar * g.B + b) * g.Hq + qh) * Q + qi) * D + half * 8;
 #pragma unroll
-            for (int x = 0; x < (kBN * D / 8) / kAttnThreads; ++x) {
-                const int p = tid + x * kAttnThreads;
-                const int row = p / (D / 8), c8 = p % (D / 8);
-                const int grow = min(t0 + row, sg.len - 1);
-                const u32x4_t val = *reinterpret_cast<const u32x4_t*>(kbase + (size_t)grow * D + c8 * 8);
-                *reinterpret_cast<u32x4_t*>(&Ks[row * KSTR + c8 * 8]) = val;
+                for (int ks = 0; ks < KS; ++ks) qf[ks].u = *reinterpret_cast<const u32x4_t*>(qrow + ks * 16);
+                q_seg = cur.si;
             }
-            // V tile, transposed in registers: a thread takes 4 keys x 4 columns and writes, for
-            // each column, its 4 keys as one 8-byte piece.  Inside every group of 16 keys the
-            // 4-key pieces are stored in the order 0,2,1,3 (the accumulator order, see above).
-#pragma unroll
-            for (int x = 0; x < (kBN / 4) * (D / 4) / kAttnThreads; ++x) {
-                const int p = tid + x * kAttnThreads;
-                const int kq = p / (D / 4), dq = p % (D / 4);
-                uint32_t lo[4], hi[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int grow = min(t0 + kq * 4 + r, sg.len - 1);
-                    const uint2 u = *reinterpret_cast<const uint2*>(vbase + (size_t)grow * D + dq * 4);
-                    lo[r] = u.x;
-                    hi[r] = u.y;
-                }
-                const int sub = kq & 3, pos = ((sub & 1) << 1) | (sub >> 1);
-                const int kcol = (kq >> 2) * 16 + pos * 4;
-                uint2 w;
-                w.x = (lo[0] & 0xFFFFu) | (lo[1] << 16);
-                w.y = (lo[2] & 0xFFFFu) | (lo[3] << 16);
-                *reinterpret_cast<uint2*>(&Vt[(dq * 4 + 0) * VSTR + kcol]) = w;
-                w.x = (lo[0] >> 16) | (lo[1] & 0xFFFF0000u);
-                w.y = (lo[2] >> 16) | (lo[3] & 0xFFFF0000u);
-                *reinterpret_cast<uint2*>(&Vt[(dq * 4 + 1) * VSTR + kcol]) = w;
-                w.x = (hi[0] & 0xFFFFu) | (hi[1] << 16);
-                w.y = (hi[2] & 0xFFFFu) | (hi[3] << 16);
-                *reinterpret_cast<uint2*>(&Vt[(dq * 4 + 2) * VSTR + kcol]) = w;
-                w.x = (hi[0] >> 16) | (hi[1] & 0xFFFF0000u);
-                w.y = (hi[2] >> 16) | (hi[3] & 0xFFFF0000u);
-                *reinterpret_cast<uint2*>(&Vt[(dq * 4 + 3) * VSTR + kcol]) = w;
-            }
-            __syncthreads();
-            if (sg.chunk && t0 > wave_imax) continue;   // every key of the tile lies after this wave's rows
-
-            // S^T tile: [2 key blocks][2 query blocks]
-            f32x16_t s[2][2];
+            const bf16_t* Kb = Ks[buf];
+            const bf16_t* Vb = Vt[buf];
+            // S^T tile: 2 key blocks x this wave's query block
+            f32x16_t s[2];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int qb = 0; qb < 2; ++qb)
+                for (int j = 0; j < 16; ++j) s[kb][j] = 0.f;
 #pragma unroll
-                    for (int j = 0; j < 16; ++j) s[kb][qb][j] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
+            for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb) {
                     Frag kf;
-                    kf.u = *reinterpret_cast<const u32x4_t*>(&Ks[(kb * 32 + l32) * KSTR + ks * 16 + half * 8]);
-#pragma unroll
-                    for (int qb = 0; qb < 2; ++qb)
-                        s[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[qb][ks].v, s[kb][qb], 0, 0, 0);
+                    kf.u = *reinterpret_cast<const u32x4_t*>(&Kb[(kb * 32 + l32) * KSTR + ks * 16 + half * 8]);
+                    s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[ks].v, s[kb], 0, 0, 0);
                 }
-            }
-            const bool need_mask = (t0 + kBN > sg.len) || (sg.chunk && t0 + kBN - 1 > wave_imin);
-            Frag pf[2][2][2];   // [qb][kb][16-key half]
-#pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
-                if (need_mask) {
-                    const int lim = sg.chunk ? min(sg.len - 1, qi[qb]) : sg.len - 1;   // last visible key
-#pragma unroll
-                    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                        for (int j = 0; j < 16; ++j) {
-                            const int kk = t0 + kb * 32 + (j >> 2) * 8 + half * 4 + (j & 3);
-                            if (kk > lim) s[kb][qb][j] = -INFINITY;
-                        }
-                }
-                float mt = -INFINITY;
+            const int t0 = cur.t0;
+            if ((t0 + kBN > cur.sg.len) || (cur.sg.chunk && t0 + kBN - 1 > wave_imin)) {
+                const int lim = cur.sg.chunk ? min(cur.sg.len - 1, qi) : cur.sg.len - 1;   // last visible key
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                    for (int j = 0; j < 16; ++j) mt = fmaxf(mt, s[kb][qb][j]);
-                mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
-                const float mn = fmaxf(m[qb], mt);
-                const float alpha = exp2f((m[qb] - mn) * c2);
-                const float mc = mn * c2;
-                float ps = 0.f;
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb) {
-                    float p[16];
-#pragma unroll
                     for (int j = 0; j < 16; ++j) {
-                        p[j] = exp2f(s[kb][qb][j] * c2 - mc);
-                        ps += p[j];
+                        const int kk = t0 + kb * 32 + (j >> 2) * 8 + half * 4 + (j & 3);
+                        if (kk > lim) s[kb][j] = -INFINITY;
                     }
+            }
+            float mt = -INFINITY;
 #pragma unroll
-                    for (int hf = 0; hf < 2; ++hf)
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                        for (int x = 0; x < 4; ++x)
-                            pf[qb][kb][hf].u[x] = pack_bf16x2(p[hf * 8 + 2 * x], p[hf * 8 + 2 * x + 1]);
-                }
-                lsum[qb] = lsum[qb] * alpha + ps;
-                m[qb] = mn;
+                for (int j = 0; j < 16; ++j) mt = fmaxf(mt, s[kb][j]);
+            mt = max_xor32(mt);
+            // raise the running maximum only when it grew by more than 2^kRescaleLog2: the
+            // probabilities then stay below that factor, and most tiles skip the rescaling of O
+            const bool grow = (mt - m_run) * c2 > kRescaleLog2;
+            if (__any(grow)) {
+                const float mn = grow ? mt : m_run;
+                const float alpha = __builtin_amdgcn_exp2f((m_run - mn) * c2);   // 0 on the first tile
+                m_run = mn;
+                lsum *= alpha;
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
 #pragma unroll
-                    for (int j = 0; j < 16; ++j) o[db][qb][j] *= alpha;
+                    for (int j = 0; j < 16; ++j) o[db][j] *= alpha;
             }
+            const float mc = m_run * c2;
+            Frag pf[2][2];   // [key block][16-key half]
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        const float p0 = __builtin_amdgcn_exp2f(s[kb][hf * 8 + 2 * x] * c2 - mc);
+                        const float p1 = __builtin_amdgcn_exp2f(s[kb][hf * 8 + 2 * x + 1] * c2 - mc);
+                        lsum += p0 + p1;
+                        pf[kb][hf].u[x] = cvt_pk_bf16(p0, p1);
+                    }
             // O^T += V^T P^T
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
@@ -219,31 +292,31 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(
 #pragma unroll
                     for (int db = 0; db < DB; ++db) {
                         Frag vf;
-                        vf.u = *reinterpret_cast<const u32x4_t*>(&Vt[(db * 32 + l32) * VSTR + (kb * 2 + hf) * 16 + half * 8]);
-#pragma unroll
-                        for (int qb = 0; qb < 2; ++qb)
-                            o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[qb][kb][hf].v, o[db][qb], 0, 0, 0);
+                        vf.u = *reinterpret_cast<const u32x4_t*>(&Vb[(db * 32 + l32) * VSTR + (kb * 2 + hf) * 16 + half * 8]);
+                        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[kb][hf].v, o[db], 0, 0, 0);
                     }
         }
+        if (has_next) tile_store<D>(regs, Ks[buf ^ 1], Vt[buf ^ 1], tid);
+        __syncthreads();   // tile `cur` is consumed everywhere, tile `nxt` is visible
+        buf ^= 1;
+        cur = nxt;
     }
 
-    // normalise and store: this lane owns query qb, columns 32*db + 8*(j/4) + 4*half + j%4
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        const float lt = lsum[qb] + __shfl_xor(lsum[qb], 32, 64);
-        if (!qvalid[qb]) continue;
+    // normalise and store: this lane owns one query, columns 32*db + 8*(j/4) + 4*half + j%4
+    const float lt = lsum + __shfl_xor(lsum, 32, 64);
+    if (qvalid) {
         const float inv = 1.f / lt;
-        bf16_t* orow = out + (((size_t)b * Q + qi[qb]) * g.Hq + qh[qb]) * D;
+        bf16_t* orow = out + (((size_t)b * Q + qi) * g.Hq + qh) * D;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int jq = 0; jq < 4; ++jq) {
                 uint2 w;
-                w.x = pack_bf16x2(o[db][qb][jq * 4 + 0] * inv, o[db][qb][jq * 4 + 1] * inv);
-                w.y = pack_bf16x2(o[db][qb][jq * 4 + 2] * inv, o[db][qb][jq * 4 + 3] * inv);
+                w.x = cvt_pk_bf16(o[db][jq * 4 + 0] * inv, o[db][jq * 4 + 1] * inv);
+                w.y = cvt_pk_bf16(o[db][jq * 4 + 2] * inv, o[db][jq * 4 + 3] * inv);
                 *reinterpret_cast<uint2*>(orow + db * 32 + jq * 8 + half * 4) = w;
             }
-        if (half == 0) lse[((size_t)b * g.Hq + qh[qb]) * Q + qi[qb]] = m[qb] * g.scale + logf(lt);
+        if (half == 0) lse[((size_t)b * g.Hq + qh) * Q + qi] = m_run * g.scale + logf(lt);
     }
 }
 

@@ -265,36 +265,58 @@ __global__ void decode_finish_kernel(Geom g, int n_cached, int n_splits, int qst
     }
 }
 
-template <typename T, int EPL>
-static void decode_typed(const Geom& g, const DevBuffers& bf, const SegList& sl, const void* q, const void* k,
-                         const void* v, void* out, int qstride, hipStream_t s)
+static int per_split_of(const DevBuffers& bf, int n)
 {
-    const int n = sl.n_cached;
-    const int splits = bf.dec_splits;
-    int per_split = (n + splits - 1) / splits;
+    int per_split = (n + bf.dec_splits - 1) / bf.dec_splits;
     per_split = ((per_split + kRowsPerIter - 1) / kRowsPerIter) * kRowsPerIter;
-    if (per_split == 0) per_split = kRowsPerIter;
-    const dim3 grid(splits, g.Hkv, g.B), block(kDecThreads);
-    float* lse = bf.lse;   // [B,Hq] prefix of the chunk scratch
-    hipLaunchKernelGGL((decode_qk_kernel<T, EPL>), grid, block, 0, s, g, sl, per_split, (const T*)q, (const T*)k,
-                       (const T*)bf.Kr, bf.rope, bf.logits, bf.part, splits);
-    hipLaunchKernelGGL((decode_pv_kernel<T, EPL>), grid, block, 0, s, g, sl, per_split, (const T*)bf.Vc, bf.logits,
-                       bf.part, splits, bf.opart, bf.mu, lse);
-    hipLaunchKernelGGL(decode_finish_kernel<T>, dim3(g.Hkv, g.B), dim3(256), 0, s, g, n, splits, qstride, bf.opart,
-                       bf.logits, lse, (const T*)v, (T*)out, bf.mu_chunk);
+    return per_split == 0 ? kRowsPerIter : per_split;
 }
 
-void launch_decode(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int qstride,
-                   const void* q, const void* k, const void* v, void* out, hipStream_t s)
+template <typename T, int EPL>
+static void qk_typed(const Geom& g, const DevBuffers& bf, const SegList& sl, const void* q, const void* k, hipStream_t s)
 {
-    const int epl = g.d / kLanesPerRow;
-    if (dtype == CASCADE_F32) {
-        if (epl == 8) decode_typed<float, 8>(g, b, sl, q, k, v, out, qstride, s);
-        else decode_typed<float, 4>(g, b, sl, q, k, v, out, qstride, s);
-    } else {
-        if (epl == 8) decode_typed<bf16_t, 8>(g, b, sl, q, k, v, out, qstride, s);
-        else decode_typed<bf16_t, 4>(g, b, sl, q, k, v, out, qstride, s);
-    }
+    const dim3 grid(bf.dec_splits, g.Hkv, g.B), block(kDecThreads);
+    hipLaunchKernelGGL((decode_qk_kernel<T, EPL>), grid, block, 0, s, g, sl, per_split_of(bf, sl.n_cached), (const T*)q,
+                       (const T*)k, (const T*)bf.Kr, bf.rope, bf.logits, bf.part, bf.dec_splits);
+}
+
+template <typename T, int EPL>
+static void pv_typed(const Geom& g, const DevBuffers& bf, const SegList& sl, hipStream_t s)
+{
+    const dim3 grid(bf.dec_splits, g.Hkv, g.B), block(kDecThreads);
+    // the log-sum-exp of the step lives in the first B*Hq entries of the chunk scratch
+    hipLaunchKernelGGL((decode_pv_kernel<T, EPL>), grid, block, 0, s, g, sl, per_split_of(bf, sl.n_cached), (const T*)bf.Vc,
+                       bf.logits, bf.part, bf.dec_splits, bf.opart, bf.mu, bf.lse);
+}
+
+#define CKV_DISPATCH(fn, ...)                                                     \
+    do {                                                                          \
+        const int epl = g.d / kLanesPerRow;                                       \
+        if (dtype == CASCADE_F32) { if (epl == 8) fn<float, 8>(__VA_ARGS__); else fn<float, 4>(__VA_ARGS__); } \
+        else { if (epl == 8) fn<bf16_t, 8>(__VA_ARGS__); else fn<bf16_t, 4>(__VA_ARGS__); }                    \
+    } while (0)
+
+void launch_decode_qk(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, const void* q, const void* k,
+                      hipStream_t s)
+{
+    CKV_DISPATCH(qk_typed, g, b, sl, q, k, s);
+}
+
+void launch_decode_pv(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, hipStream_t s)
+{
+    CKV_DISPATCH(pv_typed, g, b, sl, s);
+}
+
+void launch_decode_finish(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int qstride, const void* v,
+                          void* out, hipStream_t s)
+{
+    const dim3 grid(g.Hkv, g.B), block(256);
+    if (dtype == CASCADE_F32)
+        hipLaunchKernelGGL(decode_finish_kernel<float>, grid, block, 0, s, g, sl.n_cached, b.dec_splits, qstride, b.opart,
+                           b.logits, b.lse, (const float*)v, (float*)out, b.mu_chunk);
+    else
+        hipLaunchKernelGGL(decode_finish_kernel<bf16_t>, grid, block, 0, s, g, sl.n_cached, b.dec_splits, qstride, b.opart,
+                           b.logits, b.lse, (const bf16_t*)v, (bf16_t*)out, b.mu_chunk);
 }
 
 bool decode_supported(const Geom& g) { return (g.d == 64 || g.d == 128) && g.G <= kMaxG; }

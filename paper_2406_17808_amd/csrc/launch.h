@@ -61,8 +61,11 @@ void launch_score_mfma(const Geom& g, const DevBuffers& b, const SegList& sl, in
                        int tail_rows, float decay, hipStream_t s);
 
 // decode
-void launch_decode(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int qstride,
-                   const void* q, const void* k, const void* v, void* out, hipStream_t s);
+void launch_decode_qk(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl,
+                      const void* q, const void* k, hipStream_t s);
+void launch_decode_pv(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, hipStream_t s);
+void launch_decode_finish(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int qstride,
+                          const void* v, void* out, hipStream_t s);
 bool decode_supported(const Geom& g);
 
 }  // namespace ckv

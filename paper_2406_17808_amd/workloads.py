@@ -194,3 +194,39 @@ def prefilled_state(wl: Workload, seed: int, seq: int, kv_head: int, n_prior_tok
     total = 4 * slots if n_prior_tokens is None else n_prior_tokens
     ids = np.concatenate([np.arange(wl.n_sink), np.arange(total - (slots - wl.n_sink), total)]).astype(np.int64)
     return k, v, mu, ids
+
+
+def chunk_inputs_torch(wl: Workload, seed: int, chunk_index: int, device, n_tokens: Optional[int] = None):
+    """The same recipe as chunk_inputs, drawn on the device by torch's seeded generator (for the
+    long workloads, where drawing on the host would dominate a run).  Returns q, k, v tensors
+    in the workload's dtype.  The bits differ from chunk_inputs; whoever needs both sides to see
+    the same values copies these tensors to the host."""
+    import torch
+    start = chunk_index * wl.chunk
+    n = min(wl.chunk, wl.seq_len - start) if n_tokens is None else n_tokens
+    gen = torch.Generator(device=device)
+    stable = 0
+    for ch in wl.name.encode():
+        stable = (stable * 131 + ch) % (1 << 31)
+    gen.manual_seed((seed << 40) ^ (stable << 8) ^ (chunk_index * 2654435761 % (1 << 40)))
+    dt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+
+    def draw(heads):
+        x = torch.randn((wl.batch, wl.chunk, heads, wl.head_dim), generator=gen, device=device, dtype=torch.float32)
+        return (x * wl.input_scale)[:, :n].to(dt).contiguous()
+
+    q, k, v = draw(wl.n_q_heads), draw(wl.n_kv_heads), draw(wl.n_kv_heads)
+    spec = planted_key_spec(wl, seed)
+    if spec is not None:
+        d = wl.head_dim
+        p = spec["position"]
+        if start <= p < start + n:
+            c = spec["cosine"]
+            kk = spec["norm_factor"] * math.sqrt(d) * (c * spec["u"] + math.sqrt(1.0 - c * c) * spec["w"])
+            k[:, p - start, :, :] = torch.from_numpy(kk.astype(np.float32)).to(device).to(dt)
+        first_q = wl.seq_len - spec["last_queries"]
+        lo, hi = max(first_q, start), min(wl.seq_len, start + n)
+        if lo < hi:
+            add = torch.from_numpy((spec["query_gain"] * math.sqrt(d) * spec["u"]).astype(np.float32)).to(device)
+            q[:, lo - start:hi - start] = (q[:, lo - start:hi - start].float() + add).to(dt)
+    return q, k, v
