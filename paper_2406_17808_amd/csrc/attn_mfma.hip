@@ -10,6 +10,9 @@
 // probabilities sit in the accumulators exactly as the B operand of O^T = V^T P^T needs them
 // (the contraction index runs over keys in the accumulator's own order; the V^T tile in LDS is
 // stored in that same order).
+#include <stdio.h>
+#include <stdlib.h>
+
 #include "launch.h"
 
 namespace ckv {
@@ -43,6 +46,13 @@ __device__ inline uint32_t cvt_pk_bf16(float lo, float hi)
     return __builtin_bit_cast(uint32_t, y);
 }
 
+// acc + lo + hi of a packed bf16 pair (v_dot2c_f32_bf16 against (1, 1)): the row sum is taken over
+// the rounded probabilities, the same values the PV product uses
+__device__ inline float row_sum_add(float acc, uint32_t pair)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pair), __builtin_bit_cast(bf16x2_t, 0x3F803F80u), acc, false);
+}
+
 // max over the two lanes l and l^32 (they hold the two halves of one query's keys)
 __device__ inline float max_xor32(float x)
 {
@@ -50,9 +60,7 @@ __device__ inline float max_xor32(float x)
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
-constexpr int kAttnThreads = 512;  // 8 waves: two per SIMD, so one wave's softmax overlaps the other's MFMAs
-constexpr int kBM = 256;           // query rows per workgroup: one 32-row block per wave
-constexpr int kBN = 64;            // keys per tile
+constexpr int kBN = 64;               // keys per tile
 constexpr float kRescaleLog2 = 8.f;   // the running maximum is only raised when it grew by 2^8
 
 // Iterates over the 64-key tiles of all segments.  All fields are workgroup-uniform.
@@ -80,96 +88,89 @@ struct TileIter {
     }
 };
 
-template <int D>
-struct TileRegs {   // one thread's share of a K/V tile on its way from global memory to LDS
-    static constexpr int KP = (kBN * D / 8 + kAttnThreads - 1) / kAttnThreads;
-    static constexpr int VP = ((kBN / 4) * (D / 4) + kAttnThreads - 1) / kAttnThreads;
-    u32x4_t k[KP];
-    uint2 v[VP][4];
+// Both tiles go to LDS row-major in 16-byte pieces; the row strides are chosen for the reads:
+// K is read as 16-byte row pieces by 32 lanes on 32 different rows (stride/16 odd), V through
+// the transposing 8-byte read of gfx950, 4 rows x 16 columns per 16 lanes (stride = 16 banks mod 64).
+template <int D> struct TileLayout {
+    static constexpr int KSTR = D + 8;
+    static constexpr int VSTR = D + 32;
 };
 
-template <int D>
-__device__ inline void tile_fetch(TileRegs<D>& r, const TileIter& it, size_t bh, int slots, int Q,
-                                  const bf16_t* __restrict__ Kr, const bf16_t* __restrict__ Vc,
-                                  const bf16_t* __restrict__ Krc, const bf16_t* __restrict__ Vch, int tid)
-{
-    const bf16_t* kbase = it.sg.chunk ? Krc + bh * Q * D : Kr + (bh * slots + it.sg.start) * D;
-    const bf16_t* vbase = it.sg.chunk ? Vch + bh * Q * D : Vc + (bh * slots + it.sg.start) * D;
+// One thread's share of a K/V tile on its way from global memory to LDS: NP 16-byte pieces of
+// each.  The piece -> (row, column) map is fixed per thread, so its offsets are computed once.
+template <int D, int THREADS>
+struct TileMover {
+    static constexpr int NP = (kBN * D / 8 + THREADS - 1) / THREADS;
+    u32x4_t k[NP], v[NP];
+    int row[NP];            // tile row of piece x (kBN for a piece beyond the tile)
+    uint32_t gcol[NP];      // byte offset inside a global row
+    uint32_t lk[NP], lv[NP];   // element offsets inside the LDS tiles
+
+    __device__ void init(int tid)
+    {
 #pragma unroll
-    for (int x = 0; x < TileRegs<D>::KP; ++x) {
-        const int p = tid + x * kAttnThreads;
-        if (p < kBN * D / 8) {
-            const int row = p / (D / 8), c8 = p % (D / 8);
-            const int grow = min(it.t0 + row, it.sg.len - 1);      // rows past the end repeat the last one (masked later)
-            r.k[x] = *reinterpret_cast<const u32x4_t*>(kbase + (size_t)grow * D + c8 * 8);
+        for (int x = 0; x < NP; ++x) {
+            const int p = tid + x * THREADS;
+            row[x] = p < kBN * D / 8 ? p / (D / 8) : kBN;
+            const int c8 = p % (D / 8);
+            gcol[x] = c8 * 16;
+            lk[x] = (p / (D / 8)) * TileLayout<D>::KSTR + c8 * 8;
+            lv[x] = (p / (D / 8)) * TileLayout<D>::VSTR + c8 * 8;
         }
     }
+    // rows past the end of the segment repeat its last row (they are masked later)
+    __device__ void fetch(const TileIter& it, size_t bh, int slots, int Q, const bf16_t* __restrict__ Kr,
+                          const bf16_t* __restrict__ Vc, const bf16_t* __restrict__ Krc, const bf16_t* __restrict__ Vch)
+    {
+        const size_t first = it.sg.chunk ? bh * Q + it.t0 : bh * slots + it.sg.start + it.t0;
+        const char* kt = reinterpret_cast<const char*>((it.sg.chunk ? Krc : Kr) + first * D);
+        const char* vt = reinterpret_cast<const char*>((it.sg.chunk ? Vch : Vc) + first * D);
+        const int last = it.sg.len - 1 - it.t0;
 #pragma unroll
-    for (int x = 0; x < TileRegs<D>::VP; ++x) {
-        const int p = tid + x * kAttnThreads;
-        if (p < (kBN / 4) * (D / 4)) {
-            const int kq = p / (D / 4), dq = p % (D / 4);
-#pragma unroll
-            for (int rr = 0; rr < 4; ++rr) {
-                const int grow = min(it.t0 + kq * 4 + rr, it.sg.len - 1);
-                r.v[x][rr] = *reinterpret_cast<const uint2*>(vbase + (size_t)grow * D + dq * 4);
+        for (int x = 0; x < NP; ++x)
+            if (row[x] < kBN) {
+                const uint32_t off = (uint32_t)min(row[x], last) * (D * 2) + gcol[x];
+                k[x] = *reinterpret_cast<const u32x4_t*>(kt + off);
+                v[x] = *reinterpret_cast<const u32x4_t*>(vt + off);
             }
-        }
     }
-}
+    __device__ void store(bf16_t* __restrict__ Ks, bf16_t* __restrict__ Vs) const
+    {
+#pragma unroll
+        for (int x = 0; x < NP; ++x)
+            if (row[x] < kBN) {
+                *reinterpret_cast<u32x4_t*>(&Ks[lk[x]]) = k[x];
+                *reinterpret_cast<u32x4_t*>(&Vs[lv[x]]) = v[x];
+            }
+    }
+};
 
-// K goes to LDS row-major with a padded stride.  V is transposed in registers: a thread holds
-// 4 keys x 4 columns and writes, for each column, its 4 keys as one 8-byte piece; inside every
-// group of 16 keys the 4-key pieces are stored in the order 0,2,1,3 (the accumulator order).
-template <int D>
-__device__ inline void tile_store(const TileRegs<D>& r, bf16_t* __restrict__ Ks, bf16_t* __restrict__ Vt, int tid)
+typedef short v4i16_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) v4i16_t lds_v4i16_t;
+
+// ds_read_b64_tr_b16: the 16 lanes of a group address a 4-row x 16-column block of 16-bit
+// elements (lane i: row i/4, columns 4*(i%4)..+3); lane n receives column n of the 4 rows.
+__device__ inline uint2 lds_read_tr16(const bf16_t* p)
 {
-    constexpr int KSTR = D + 8, VSTR = kBN + 8;
-#pragma unroll
-    for (int x = 0; x < TileRegs<D>::KP; ++x) {
-        const int p = tid + x * kAttnThreads;
-        if (p < kBN * D / 8) {
-            const int row = p / (D / 8), c8 = p % (D / 8);
-            *reinterpret_cast<u32x4_t*>(&Ks[row * KSTR + c8 * 8]) = r.k[x];
-        }
-    }
-#pragma unroll
-    for (int x = 0; x < TileRegs<D>::VP; ++x) {
-        const int p = tid + x * kAttnThreads;
-        if (p < (kBN / 4) * (D / 4)) {
-            const int kq = p / (D / 4), dq = p % (D / 4);
-            const int sub = kq & 3, pos = ((sub & 1) << 1) | (sub >> 1);
-            const int kcol = (kq >> 2) * 16 + pos * 4;
-            const uint2* u = r.v[x];
-            uint2 w;
-            w.x = (u[0].x & 0xFFFFu) | (u[1].x << 16);
-            w.y = (u[2].x & 0xFFFFu) | (u[3].x << 16);
-            *reinterpret_cast<uint2*>(&Vt[(dq * 4 + 0) * VSTR + kcol]) = w;
-            w.x = (u[0].x >> 16) | (u[1].x & 0xFFFF0000u);
-            w.y = (u[2].x >> 16) | (u[3].x & 0xFFFF0000u);
-            *reinterpret_cast<uint2*>(&Vt[(dq * 4 + 1) * VSTR + kcol]) = w;
-            w.x = (u[0].y & 0xFFFFu) | (u[1].y << 16);
-            w.y = (u[2].y & 0xFFFFu) | (u[3].y << 16);
-            *reinterpret_cast<uint2*>(&Vt[(dq * 4 + 2) * VSTR + kcol]) = w;
-            w.x = (u[0].y >> 16) | (u[1].y & 0xFFFF0000u);
-            w.y = (u[2].y >> 16) | (u[3].y & 0xFFFF0000u);
-            *reinterpret_cast<uint2*>(&Vt[(dq * 4 + 3) * VSTR + kcol]) = w;
-        }
-    }
+    const v4i16_t r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16_t*)p);
+    return __builtin_bit_cast(uint2, r);
 }
 
-template <int D>
-__global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(
+// THREADS / 64 waves, one 32-row query block each.  With 512 threads one workgroup fills a
+// compute unit (two waves per SIMD); with 256 threads two workgroups share it.
+template <int D, int THREADS>
+__global__ __launch_bounds__(THREADS, 512 / THREADS) void attn_mfma_kernel(
     Geom g, SegList sl, int Q, const bf16_t* __restrict__ Qr, const bf16_t* __restrict__ Kr,
     const bf16_t* __restrict__ Vc, const bf16_t* __restrict__ Krc, const bf16_t* __restrict__ Vch,
     bf16_t* __restrict__ out, float* __restrict__ lse)
 {
+    constexpr int BM = THREADS / 2;   // query rows per workgroup
     constexpr int KS = D / 16;        // k-steps of S^T = K Q^T
     constexpr int DB = D / 32;        // 32-wide blocks of the head dimension in O^T
-    constexpr int KSTR = D + 8;       // LDS row stride of the K tile (elements)
-    constexpr int VSTR = kBN + 8;     // LDS row stride of the V^T tile (elements)
+    constexpr int KSTR = TileLayout<D>::KSTR;   // LDS row strides (elements)
+    constexpr int VSTR = TileLayout<D>::VSTR;
     __shared__ __attribute__((aligned(16))) bf16_t Ks[2][kBN * KSTR];
-    __shared__ __attribute__((aligned(16))) bf16_t Vt[2][D * VSTR];
+    __shared__ __attribute__((aligned(16))) bf16_t Vs[2][kBN * VSTR];
 
     const int BH = g.B * g.Hkv;
     const int bh = blockIdx.x % BH, tile = blockIdx.x / BH;   // consecutive workgroups: different KV heads
@@ -178,16 +179,16 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(
     const int GQ = g.G * Q;
 
     // the query of this lane; rows are (head, token) pairs
-    const int r_row = tile * kBM + wave * 32 + l32;
+    const int r_row = tile * BM + wave * 32 + l32;
     const bool qvalid = r_row < GQ;
     const int rc = min(r_row, GQ - 1);
     const int qh = hk * g.G + rc / Q, qi = rc % Q;
     int wave_imax, wave_imin, wg_imax;
     {
-        const int r_lo = min(tile * kBM + wave * 32, GQ - 1), r_hi = min(tile * kBM + wave * 32 + 31, GQ - 1);
+        const int r_lo = min(tile * BM + wave * 32, GQ - 1), r_hi = min(tile * BM + wave * 32 + 31, GQ - 1);
         if (r_lo / Q == r_hi / Q) { wave_imin = r_lo % Q; wave_imax = r_hi % Q; }
         else { wave_imin = 0; wave_imax = Q - 1; }
-        const int w_lo = min(tile * kBM, GQ - 1), w_hi = min(tile * kBM + kBM - 1, GQ - 1);
+        const int w_lo = min(tile * BM, GQ - 1), w_hi = min(tile * BM + BM - 1, GQ - 1);
         wg_imax = (w_lo / Q == w_hi / Q) ? w_hi % Q : Q - 1;
     }
 
@@ -202,12 +203,17 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(
 
     TileIter cur, nxt;
     cur.first(sl, wg_imax);
-    TileRegs<D> regs;
+    TileMover<D, THREADS> mv;
+    mv.init(tid);
     if (cur.valid(sl)) {
-        tile_fetch<D>(regs, cur, (size_t)bh, g.slots, Q, Kr, Vc, Krc, Vch, tid);
-        tile_store<D>(regs, Ks[0], Vt[0], tid);
+        mv.fetch(cur, (size_t)bh, g.slots, Q, Kr, Vc, Krc, Vch);
+        mv.store(Ks[0], Vs[0]);
     }
     __syncthreads();
+
+    // LDS read offsets of this lane (elements)
+    const int k_lane = l32 * KSTR + half * 8;
+    const int v_lane = (4 * half + ((l & 15) >> 2)) * VSTR + 16 * ((l >> 4) & 1) + 4 * (l & 3);
 
     Frag qf[KS];
     int q_seg = -1;
@@ -216,7 +222,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(
         nxt = cur;
         nxt.next(sl, wg_imax);
         const bool has_next = nxt.valid(sl);
-        if (has_next) tile_fetch<D>(regs, nxt, (size_t)bh, g.slots, Q, Kr, Vc, Krc, Vch, tid);
+        if (has_next) mv.fetch(nxt, (size_t)bh, g.slots, Q, Kr, Vc, Krc, Vch);
 
         if (!(cur.sg.chunk && cur.t0 > wave_imax)) {   // else: every key of the tile lies after this wave's rows
             if (q_seg != cur.si) {                     // this segment's rotated copy of the queries
@@ -225,22 +231,56 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(
                 for (int ks = 0; ks < KS; ++ks) qf[ks].u = *reinterpret_cast<const u32x4_t*>(qrow + ks * 16);
                 q_seg = cur.si;
             }
-            const bf16_t* Kb = Ks[buf];
-            const bf16_t* Vb = Vt[buf];
-            // S^T tile: 2 key blocks x this wave's query block
+            const bf16_t* Kb = Ks[buf] + k_lane;
+            const bf16_t* Vb = Vs[buf] + v_lane;
+            // S^T tile: 2 key blocks x this wave's query block.  The fragments are read in two
+            // groups ahead of the MFMAs that use them.
             f32x16_t s[2];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int j = 0; j < 16; ++j) s[kb][j] = 0.f;
+            {
+                Frag kf[2][KS];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
+                for (int ks = 0; ks < KS / 2; ++ks)
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb) {
-                    Frag kf;
-                    kf.u = *reinterpret_cast<const u32x4_t*>(&Kb[(kb * 32 + l32) * KSTR + ks * 16 + half * 8]);
-                    s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[ks].v, s[kb], 0, 0, 0);
+                    for (int kb = 0; kb < 2; ++kb)
+                        kf[kb][ks].u = *reinterpret_cast<const u32x4_t*>(&Kb[kb * 32 * KSTR + ks * 16]);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int ks = KS / 2; ks < KS; ++ks)
+#pragma unroll
+                    for (int kb = 0; kb < 2; ++kb)
+                        kf[kb][ks].u = *reinterpret_cast<const u32x4_t*>(&Kb[kb * 32 * KSTR + ks * 16]);
+#pragma unroll
+                for (int ks = 0; ks < KS / 2; ++ks)
+#pragma unroll
+                    for (int kb = 0; kb < 2; ++kb)
+                        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ks].v, qf[ks].v, s[kb], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int ks = KS / 2; ks < KS; ++ks)
+#pragma unroll
+                    for (int kb = 0; kb < 2; ++kb)
+                        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ks].v, qf[ks].v, s[kb], 0, 0, 0);
+            }
+            // V fragments of the first key block: their latency hides behind the softmax
+            // (V^T as the A operand: row = column of V, 8 keys per lane, through two transposing
+            // reads of 4 keys each: keys 16*(2kb+hf) + 4*half + {0..3} and + 8, the order the
+            // probabilities have in the accumulators)
+            Frag vf[2][2][DB];
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    const bf16_t* p0 = Vb + (hf * 16) * VSTR + db * 32;
+                    const uint2 lo = lds_read_tr16(p0), hi = lds_read_tr16(p0 + 8 * VSTR);
+                    vf[0][hf][db].u[0] = lo.x; vf[0][hf][db].u[1] = lo.y;
+                    vf[0][hf][db].u[2] = hi.x; vf[0][hf][db].u[3] = hi.y;
                 }
+            __builtin_amdgcn_sched_barrier(0);
+
             const int t0 = cur.t0;
             if ((t0 + kBN > cur.sg.len) || (cur.sg.chunk && t0 + kBN - 1 > wave_imin)) {
                 const int lim = cur.sg.chunk ? min(cur.sg.len - 1, qi) : cur.sg.len - 1;   // last visible key
@@ -281,22 +321,33 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(
                     for (int x = 0; x < 4; ++x) {
                         const float p0 = __builtin_amdgcn_exp2f(s[kb][hf * 8 + 2 * x] * c2 - mc);
                         const float p1 = __builtin_amdgcn_exp2f(s[kb][hf * 8 + 2 * x + 1] * c2 - mc);
-                        lsum += p0 + p1;
                         pf[kb][hf].u[x] = cvt_pk_bf16(p0, p1);
+                        lsum = row_sum_add(lsum, pf[kb][hf].u[x]);
                     }
-            // O^T += V^T P^T
+            // O^T += V^T P^T; the fragments of the second key block are read while the MFMAs of
+            // the first run
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+            for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-                for (int hf = 0; hf < 2; ++hf)
+                for (int db = 0; db < DB; ++db) {
+                    const bf16_t* p0 = Vb + (32 + hf * 16) * VSTR + db * 32;
+                    const uint2 lo = lds_read_tr16(p0), hi = lds_read_tr16(p0 + 8 * VSTR);
+                    vf[1][hf][db].u[0] = lo.x; vf[1][hf][db].u[1] = lo.y;
+                    vf[1][hf][db].u[2] = hi.x; vf[1][hf][db].u[3] = hi.y;
+                }
 #pragma unroll
-                    for (int db = 0; db < DB; ++db) {
-                        Frag vf;
-                        vf.u = *reinterpret_cast<const u32x4_t*>(&Vb[(db * 32 + l32) * VSTR + (kb * 2 + hf) * 16 + half * 8]);
-                        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[kb][hf].v, o[db], 0, 0, 0);
-                    }
+            for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[0][hf][db].v, pf[0][hf].v, o[db], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[1][hf][db].v, pf[1][hf].v, o[db], 0, 0, 0);
         }
-        if (has_next) tile_store<D>(regs, Ks[buf ^ 1], Vt[buf ^ 1], tid);
+        if (has_next) mv.store(Ks[buf ^ 1], Vs[buf ^ 1]);
         __syncthreads();   // tile `cur` is consumed everywhere, tile `nxt` is visible
         buf ^= 1;
         cur = nxt;
@@ -320,16 +371,20 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(
     }
 }
 
+template <int D, int THREADS>
+static void attn_launch(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, void* out, hipStream_t s)
+{
+    const int tiles = (g.G * Q + THREADS / 2 - 1) / (THREADS / 2);
+    hipLaunchKernelGGL((attn_mfma_kernel<D, THREADS>), dim3(tiles * g.B * g.Hkv), dim3(THREADS), 0, s, g, sl, Q,
+                       (const bf16_t*)b.Qr, (const bf16_t*)b.Kr, (const bf16_t*)b.Vc, (const bf16_t*)b.Krc,
+                       (const bf16_t*)b.Vch, (bf16_t*)out, b.lse);
+}
+
 void launch_attn_mfma(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, int, void* out, hipStream_t s)
 {
-    const int tiles = (g.G * Q + kBM - 1) / kBM;
-    const dim3 grid(tiles * g.B * g.Hkv), block(kAttnThreads);
-    if (g.d == 128)
-        hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, block, 0, s, g, sl, Q, (const bf16_t*)b.Qr, (const bf16_t*)b.Kr,
-                           (const bf16_t*)b.Vc, (const bf16_t*)b.Krc, (const bf16_t*)b.Vch, (bf16_t*)out, b.lse);
-    else
-        hipLaunchKernelGGL(attn_mfma_kernel<64>, grid, block, 0, s, g, sl, Q, (const bf16_t*)b.Qr, (const bf16_t*)b.Kr,
-                           (const bf16_t*)b.Vc, (const bf16_t*)b.Krc, (const bf16_t*)b.Vch, (bf16_t*)out, b.lse);
+    static const bool small_wg = getenv("CASCADE_KV_ATTN_WG256") != nullptr;   // experiment switch
+    if (g.d == 128) { if (small_wg) attn_launch<128, 256>(g, b, sl, Q, out, s); else attn_launch<128, 512>(g, b, sl, Q, out, s); }
+    else { if (small_wg) attn_launch<64, 256>(g, b, sl, Q, out, s); else attn_launch<64, 512>(g, b, sl, Q, out, s); }
 }
 
 // ------------------------------------------------------------------ exact score sums
