@@ -1,13 +1,14 @@
 // Decode step (Eq. 2): one query per sequence against the whole cache plus its own key.
-// The cache is streamed once: K in decode_qk (logits), V in decode_pv (outputs + EMA scores).
-// Sixteen lanes share a row; every lane owns d/16 contiguous elements of it.
+// The cache is streamed once from HBM: K by decode_qk (logits), V by decode_pv (outputs and
+// EMA scores); the logits of a step (16 bytes per cached row at 4 query heads per KV head)
+// pass through a scratch array because the EMA update needs exact probabilities.
 #include "launch.h"
 
 namespace ckv {
 
 constexpr int kDecThreads = 256;
-constexpr int kLanesPerRow = 16;
-constexpr int kRowsPerIter = kDecThreads / kLanesPerRow;   // 16 rows per workgroup iteration
+constexpr int kLanesPerRow = 16;                            // lanes that share one row in the VALU kernels
+constexpr int kRowGroups = kDecThreads / kLanesPerRow;      // 16 row groups per workgroup
 constexpr int kMaxG = 8;
 
 template <typename T, int EPL> struct VecLoad;
@@ -44,181 +45,342 @@ template <> struct VecLoad<float, 4> {
     }
 };
 
-// index in the concatenation of the cached segments -> (segment, offset)
-__device__ inline int seg_of(const SegList& sl, int j, int* off)
+// (max, sum of exp) pairs combine associatively
+__device__ inline void ml_merge(float& m, float& l, float m2, float l2)
 {
-    int si = 0;
-    while (si < sl.n - 1 && j >= sl.s[si].len) { j -= sl.s[si].len; ++si; }
-    *off = j;
-    return si;
-}
-
-// Rotated query slices of this lane for segment `si`: the stored keys are rotated to their slot
-// index, so the query turns by (own index) - (cache index - slot index), one angle per segment.
-template <typename T, int EPL>
-__device__ inline void load_q_rot(const Geom& g, const SegList& sl, int si, const T* __restrict__ q,
-                                  const float2* __restrict__ rope, int b, int hk, int lane, float (*qr)[EPL])
-{
-    const int half = g.d / 2;
-    const int rot = sl.qrot0[sl.s[si].qvar];
-    for (int hh = 0; hh < g.G; ++hh) {
-        const T* qh = q + ((size_t)b * g.Hq + hk * g.G + hh) * g.d;
-#pragma unroll
-        for (int x = 0; x < EPL; ++x) {
-            const int e = lane * EPL + x;
-            const int pe = e < half ? e : e - half;
-            const float2 cs = rope[(size_t)rot * half + pe];
-            const float a = Elem<T>::load(qh + pe), c = Elem<T>::load(qh + pe + half);
-            qr[hh][x] = (e < half ? a * cs.x - c * cs.y : c * cs.x + a * cs.y) * g.scale;
-        }
+    if (l2 > 0.f) {
+        const float mn = fmaxf(m, m2);
+        l = l * __expf(m - mn) + l2 * __expf(m2 - mn);
+        m = mn;
     }
 }
 
-// logits[b][h][j] = scale * <q_rot, Kr[slot(j)]> for the rows of this split; per split and head
-// the running (max, sum of exp) go to `part`.  Split 0 also handles the token's own key, whose
-// logit needs no rotation (query and key sit at the same index).
-template <typename T, int EPL>
-__global__ void decode_qk_kernel(Geom g, SegList sl, int per_split, const T* __restrict__ q,
-                                 const T* __restrict__ k_new, const T* __restrict__ Kr,
-                                 const float2* __restrict__ rope, float* __restrict__ logits,
-                                 float* __restrict__ part, int n_splits)
+// One rotated, scaled element of the query: the stored keys are rotated to their slot index,
+// so the query turns by (own index) - (cache index - slot index), one angle per segment.
+template <typename T>
+__device__ inline float q_rot_elem(const T* __restrict__ qh, const float2* __restrict__ rope, int rot, int half_d,
+                                   int e, float scale)
 {
-    __shared__ float red_m[kRowsPerIter][kMaxG], red_l[kRowsPerIter][kMaxG];
+    const int pe = e < half_d ? e : e - half_d;
+    const float2 cs = rope[(size_t)rot * half_d + pe];
+    const float a = Elem<T>::load(qh + pe), c = Elem<T>::load(qh + pe + half_d);
+    return (e < half_d ? a * cs.x - c * cs.y : c * cs.x + a * cs.y) * scale;
+}
+
+// ------------------------------------------------------------------ QK, bf16: MFMA 16x16x32
+//
+// v_mfma_f32_16x16x32_bf16: for lane l, A holds row l%16, B column l%16, both with the 8
+// contraction indices 8*(l/16)..+7; D holds column l%16, rows 4*(l/16)..+3.  Rows are 16 keys,
+// columns the query heads of the group (padded with zeros to 16), the contraction runs over the
+// head dimension.  Which element of the head dimension a contraction index means is free as
+// long as A and B agree: lane group c = l/16 takes elements [c*D/4 + 8*ks, +8) in step ks, so a
+// lane reads D/2 contiguous bytes of a key row and four lanes cover the row.
+
+typedef __attribute__((ext_vector_type(8))) __bf16 dbf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float df32x4_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t du32x4_t;
+union DFrag {
+    dbf16x8_t v;
+    du32x4_t u;
+};
+
+__device__ inline uint32_t dec_pack_bf16(float lo, float hi)
+{
+    typedef __attribute__((ext_vector_type(2))) __bf16 b2;
+    typedef __attribute__((ext_vector_type(2))) float f2;
+    const f2 x = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, b2));
+}
+
+constexpr int kQkRowsPerWave = 64;   // four 16-key MFMA groups in flight per wave iteration
+
+template <int D>
+__global__ __launch_bounds__(kDecThreads) void decode_qk_mfma_kernel(
+    Geom g, SegList sl, int per_split, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k_new,
+    const bf16_t* __restrict__ Kr, const float2* __restrict__ rope, float* __restrict__ logits,
+    float* __restrict__ part, int n_splits)
+{
+    constexpr int KS = D / 32;            // MFMA steps over the head dimension
+    constexpr int NG = kQkRowsPerWave / 16;
+    __shared__ float red_m[kDecThreads / 64][16], red_l[kDecThreads / 64][16];
     const int split = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
     const int bh = b * g.Hkv + hk;
-    const int grp = threadIdx.x / kLanesPerRow, lane = threadIdx.x % kLanesPerRow;
-    const int n = sl.n_cached;
-    const int j0 = split * per_split, j1 = min(n, j0 + per_split);
-    const size_t lstride = (size_t)n + 1;
-    float qr[kMaxG][EPL];
-    float m[kMaxG], l[kMaxG];
-    for (int hh = 0; hh < kMaxG; ++hh) { m[hh] = -INFINITY; l[hh] = 0.f; }
-    int cur_seg = -1;
-    for (int jb = j0; jb < j1; jb += kRowsPerIter) {
-        const int j = jb + grp;
-        // segment changes are handled per row group; rows of one iteration may straddle two segments
-        int off = 0, si = (j < j1) ? seg_of(sl, j, &off) : cur_seg;
-        if (j < j1 && si != cur_seg) { load_q_rot<T, EPL>(g, sl, si, q, rope, b, hk, lane, qr); cur_seg = si; }
-        if (j < j1) {
-            const int slot = sl.s[si].start + off;
-            float kv[EPL];
-            VecLoad<T, EPL>::load(Kr + ((size_t)bh * g.slots + slot) * g.d + lane * EPL, kv);
-            for (int hh = 0; hh < g.G; ++hh) {
-                float acc = 0.f;
+    const int wave = threadIdx.x >> 6, l = threadIdx.x & 63, n = l & 15, c = l >> 4;
+    const int ncached = sl.n_cached;
+    const int j0 = split * per_split, j1 = min(ncached, j0 + per_split);
+    const size_t lstride = (size_t)ncached + 1;
+    const bool head_ok = n < g.G;
+    const bf16_t* qh = q + ((size_t)b * g.Hq + hk * g.G + (head_ok ? n : 0)) * D;
+    float* lrow = logits + ((size_t)b * g.Hq + hk * g.G + (head_ok ? n : 0)) * lstride;
+    float m = -INFINITY, lsum = 0.f;
+
+    int seg_first = 0;                    // index of the segment's first row in the concatenation
+    for (int si = 0; si < sl.n; ++si) {
+        const Seg sg = sl.s[si];
+        const int lo = max(j0, seg_first), hi = min(j1, seg_first + sg.len);
+        if (lo < hi) {
+            // B operand: this segment's rotation of the group's queries, scaled, as bf16
+            DFrag qf[KS];
+            const int rot = sl.qrot0[sg.qvar];
 #pragma unroll
-                for (int x = 0; x < EPL; ++x) acc += qr[hh][x] * kv[x];
+            for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-                for (int w = kLanesPerRow / 2; w > 0; w >>= 1) acc += __shfl_xor(acc, w, kLanesPerRow);
-                if (lane == 0) {
-                    logits[((size_t)b * g.Hq + hk * g.G + hh) * lstride + j] = acc;
-                    const float mn = fmaxf(m[hh], acc);
-                    l[hh] = l[hh] * __expf(m[hh] - mn) + __expf(acc - mn);
-                    m[hh] = mn;
+                for (int x = 0; x < 4; ++x) {
+                    const int e = c * (D / 4) + ks * 8 + 2 * x;
+                    const float a0 = head_ok ? q_rot_elem<bf16_t>(qh, rope, rot, D / 2, e, g.scale) : 0.f;
+                    const float a1 = head_ok ? q_rot_elem<bf16_t>(qh, rope, rot, D / 2, e + 1, g.scale) : 0.f;
+                    qf[ks].u[x] = dec_pack_bf16(a0, a1);
+                }
+            // row index = index in the concatenation of the segments
+            const bf16_t* kseg = Kr + ((ptrdiff_t)bh * g.slots + sg.start - seg_first) * D;
+            for (int r0 = lo + wave * kQkRowsPerWave; r0 < hi; r0 += (kDecThreads / 64) * kQkRowsPerWave) {
+                DFrag kf[NG][KS];
+#pragma unroll
+                for (int gi = 0; gi < NG; ++gi) {
+                    const int row = min(r0 + gi * 16 + n, hi - 1);      // rows past the end repeat the last one
+                    const bf16_t* kp = kseg + (size_t)row * D + c * (D / 4);
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) kf[gi][ks].u = *reinterpret_cast<const du32x4_t*>(kp + ks * 8);
+                }
+#pragma unroll
+                for (int gi = 0; gi < NG; ++gi) {
+                    df32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks)
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[gi][ks].v, qf[ks].v, acc, 0, 0, 0);
+                    // this lane: head n, keys r0 + 16*gi + 4*c + {0..3}
+                    const int rbase = r0 + gi * 16 + 4 * c;
+                    if (head_ok) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if (rbase + j < hi) {
+                                const float s = acc[j];
+                                lrow[rbase + j] = s;
+                                const float mn = fmaxf(m, s);
+                                lsum = lsum * __expf(m - mn) + __expf(s - mn);
+                                m = mn;
+                            }
+                    }
                 }
             }
         }
+        seg_first += sg.len;
     }
-    if (split == 0 && grp == 0) {
-        // own key: <R(n) q, R(n) k> = <q, k>
-        float kv[EPL];
-        VecLoad<T, EPL>::load(k_new + ((size_t)b * g.Hkv + hk) * g.d + lane * EPL, kv);
-        for (int hh = 0; hh < g.G; ++hh) {
-            float qv[EPL];
-            VecLoad<T, EPL>::load(q + ((size_t)b * g.Hq + hk * g.G + hh) * g.d + lane * EPL, qv);
+    if (split == 0 && wave == 0) {
+        // own key: <R(n) q, R(n) k> = <q, k>; lanes c = 0 of the valid heads take it
+        if (head_ok && c == 0) {
+            const bf16_t* kn = k_new + ((size_t)b * g.Hkv + hk) * D;
             float acc = 0.f;
-#pragma unroll
-            for (int x = 0; x < EPL; ++x) acc += qv[x] * kv[x];
-#pragma unroll
-            for (int w = kLanesPerRow / 2; w > 0; w >>= 1) acc += __shfl_xor(acc, w, kLanesPerRow);
+            for (int e = 0; e < D; ++e) acc += bf16_to_f32(qh[e]) * bf16_to_f32(kn[e]);
             acc *= g.scale;
-            if (lane == 0) {
-                logits[((size_t)b * g.Hq + hk * g.G + hh) * lstride + n] = acc;
-                const float mn = fmaxf(m[hh], acc);
-                l[hh] = l[hh] * __expf(m[hh] - mn) + __expf(acc - mn);
-                m[hh] = mn;
-            }
+            lrow[ncached] = acc;
+            const float mn = fmaxf(m, acc);
+            lsum = lsum * __expf(m - mn) + __expf(acc - mn);
+            m = mn;
         }
     }
-    if (lane == 0)
-        for (int hh = 0; hh < g.G; ++hh) { red_m[grp][hh] = m[hh]; red_l[grp][hh] = l[hh]; }
+    // combine the four lane groups of a head, then the waves
+#pragma unroll
+    for (int w = 16; w < 64; w <<= 1) {
+        const float m2 = __shfl_xor(m, w, 64), l2 = __shfl_xor(lsum, w, 64);
+        ml_merge(m, lsum, m2, l2);
+    }
+    if (c == 0) { red_m[wave][n] = m; red_l[wave][n] = lsum; }
     __syncthreads();
     if (threadIdx.x < g.G) {
-        const int hh = threadIdx.x;
         float mm = -INFINITY, ll = 0.f;
-        for (int r = 0; r < kRowsPerIter; ++r) {
-            const float mr = red_m[r][hh], lr = red_l[r][hh];
-            if (lr > 0.f) {
-                const float mn = fmaxf(mm, mr);
-                ll = ll * __expf(mm - mn) + lr * __expf(mr - mn);
-                mm = mn;
-            }
-        }
-        float* p = part + (((size_t)b * g.Hq + hk * g.G + hh) * n_splits + split) * 2;
+        for (int w = 0; w < kDecThreads / 64; ++w) ml_merge(mm, ll, red_m[w][threadIdx.x], red_l[w][threadIdx.x]);
+        float* p = part + (((size_t)b * g.Hq + hk * g.G + threadIdx.x) * n_splits + split) * 2;
         p[0] = mm;
         p[1] = ll;
     }
 }
 
-// Outputs and EMA scores of the rows of this split: with the exact log-sum-exp (all splits of
-// decode_qk combined) p = exp(logit - lse) is final, so partial outputs simply add up, and
-// mu <- beta*mu + (1-beta)*reduce_heads(p) can be applied in the same pass (Section 3.1).
-template <typename T, int EPL>
-__global__ void decode_pv_kernel(Geom g, SegList sl, int per_split, const T* __restrict__ Vc,
-                                 const float* __restrict__ logits, const float* __restrict__ part,
-                                 int n_splits, float* __restrict__ opart, float* __restrict__ mu,
-                                 float* __restrict__ lse_out)
+// ------------------------------------------------------------------ QK, any type: VALU
+
+// Sixteen lanes share a row; every lane owns D/16 contiguous elements of it and all heads of
+// the group.  Four rows per lane group are in flight.
+template <typename T, int EPL, int MAXG>
+__global__ __launch_bounds__(kDecThreads) void decode_qk_valu_kernel(
+    Geom g, SegList sl, int per_split, const T* __restrict__ q, const T* __restrict__ k_new,
+    const T* __restrict__ Kr, const float2* __restrict__ rope, float* __restrict__ logits,
+    float* __restrict__ part, int n_splits)
 {
-    __shared__ float lse_s[kMaxG];
-    __shared__ float osum[kDecThreads / 64][kMaxG][kLanesPerRow * EPL];
+    constexpr int U = 4;
+    __shared__ float red_m[kRowGroups][MAXG], red_l[kRowGroups][MAXG];
     const int split = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
     const int bh = b * g.Hkv + hk;
     const int grp = threadIdx.x / kLanesPerRow, lane = threadIdx.x % kLanesPerRow;
-    const int n = sl.n_cached;
-    const size_t lstride = (size_t)n + 1;
+    const int ncached = sl.n_cached, d = g.d;
+    const int j0 = split * per_split, j1 = min(ncached, j0 + per_split);
+    const size_t lstride = (size_t)ncached + 1;
+    float m[MAXG], lsum[MAXG];
+#pragma unroll
+    for (int hh = 0; hh < MAXG; ++hh) { m[hh] = -INFINITY; lsum[hh] = 0.f; }
+
+    int seg_first = 0;
+    for (int si = 0; si < sl.n; ++si) {
+        const Seg sg = sl.s[si];
+        const int lo = max(j0, seg_first), hi = min(j1, seg_first + sg.len);
+        if (lo < hi) {
+            float qr[MAXG][EPL];
+            const int rot = sl.qrot0[sg.qvar];
+#pragma unroll
+            for (int hh = 0; hh < MAXG; ++hh)
+                if (hh < g.G) {
+                    const T* qh = q + ((size_t)b * g.Hq + hk * g.G + hh) * d;
+#pragma unroll
+                    for (int x = 0; x < EPL; ++x) qr[hh][x] = q_rot_elem<T>(qh, rope, rot, d / 2, lane * EPL + x, g.scale);
+                }
+            const T* kseg = Kr + ((ptrdiff_t)bh * g.slots + sg.start - seg_first) * d;
+            for (int r0 = lo + grp * U; r0 < hi; r0 += kRowGroups * U) {
+                float kv[U][EPL];
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    VecLoad<T, EPL>::load(kseg + (size_t)min(r0 + u, hi - 1) * d + lane * EPL, kv[u]);
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int hh = 0; hh < MAXG; ++hh)
+                        if (hh < g.G) {
+                            float acc = 0.f;
+#pragma unroll
+                            for (int x = 0; x < EPL; ++x) acc += qr[hh][x] * kv[u][x];
+#pragma unroll
+                            for (int w = kLanesPerRow / 2; w > 0; w >>= 1) acc += __shfl_xor(acc, w, kLanesPerRow);
+                            if (lane == 0 && r0 + u < hi) {
+                                logits[((size_t)b * g.Hq + hk * g.G + hh) * lstride + r0 + u] = acc;
+                                const float mn = fmaxf(m[hh], acc);
+                                lsum[hh] = lsum[hh] * __expf(m[hh] - mn) + __expf(acc - mn);
+                                m[hh] = mn;
+                            }
+                        }
+            }
+        }
+        seg_first += sg.len;
+    }
+    if (split == 0 && grp == 0) {
+        // own key: <R(n) q, R(n) k> = <q, k>
+        float kv[EPL];
+        VecLoad<T, EPL>::load(k_new + ((size_t)b * g.Hkv + hk) * d + lane * EPL, kv);
+#pragma unroll
+        for (int hh = 0; hh < MAXG; ++hh)
+            if (hh < g.G) {
+                float qv[EPL];
+                VecLoad<T, EPL>::load(q + ((size_t)b * g.Hq + hk * g.G + hh) * d + lane * EPL, qv);
+                float acc = 0.f;
+#pragma unroll
+                for (int x = 0; x < EPL; ++x) acc += qv[x] * kv[x];
+#pragma unroll
+                for (int w = kLanesPerRow / 2; w > 0; w >>= 1) acc += __shfl_xor(acc, w, kLanesPerRow);
+                acc *= g.scale;
+                if (lane == 0) {
+                    logits[((size_t)b * g.Hq + hk * g.G + hh) * lstride + ncached] = acc;
+                    const float mn = fmaxf(m[hh], acc);
+                    lsum[hh] = lsum[hh] * __expf(m[hh] - mn) + __expf(acc - mn);
+                    m[hh] = mn;
+                }
+            }
+    }
+    if (lane == 0) {
+#pragma unroll
+        for (int hh = 0; hh < MAXG; ++hh) { red_m[grp][hh] = m[hh]; red_l[grp][hh] = lsum[hh]; }
+    }
+    __syncthreads();
+    if (threadIdx.x < g.G) {
+        float mm = -INFINITY, ll = 0.f;
+        for (int r = 0; r < kRowGroups; ++r) ml_merge(mm, ll, red_m[r][threadIdx.x], red_l[r][threadIdx.x]);
+        float* p = part + (((size_t)b * g.Hq + hk * g.G + threadIdx.x) * n_splits + split) * 2;
+        p[0] = mm;
+        p[1] = ll;
+    }
+}
+
+// ------------------------------------------------------------------ PV and EMA scores
+
+// With the exact log-sum-exp (all splits of decode_qk combined) p = exp(logit - lse) is final,
+// so the partial outputs of the splits simply add up, and mu <- beta*mu + (1-beta)*reduce_heads(p)
+// is applied in the same pass (Section 3.1).  Sixteen lanes share a row, four rows in flight.
+template <typename T, int EPL, int MAXG>
+__global__ __launch_bounds__(kDecThreads) void decode_pv_kernel(
+    Geom g, SegList sl, int per_split, const T* __restrict__ Vc, const float* __restrict__ logits,
+    const float* __restrict__ part, int n_splits, float* __restrict__ opart, float* __restrict__ mu,
+    float* __restrict__ lse_out)
+{
+    constexpr int U = 4;
+    __shared__ float lse_s[MAXG];
+    __shared__ float osum[kDecThreads / 64][MAXG][kLanesPerRow * EPL];
+    const int split = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
+    const int bh = b * g.Hkv + hk;
+    const int grp = threadIdx.x / kLanesPerRow, lane = threadIdx.x % kLanesPerRow;
+    const int ncached = sl.n_cached, d = g.d;
+    const size_t lstride = (size_t)ncached + 1;
     if (threadIdx.x < g.G) {
         const float* p = part + ((size_t)b * g.Hq + hk * g.G + threadIdx.x) * n_splits * 2;
         float mm = -INFINITY, ll = 0.f;
-        for (int s = 0; s < n_splits; ++s) {
-            const float ms = p[2 * s], ls = p[2 * s + 1];
-            if (ls > 0.f) {
-                const float mn = fmaxf(mm, ms);
-                ll = ll * __expf(mm - mn) + ls * __expf(ms - mn);
-                mm = mn;
-            }
-        }
-        lse_s[threadIdx.x] = mm + __logf(ll);
-        if (split == 0) lse_out[(size_t)b * g.Hq + hk * g.G + threadIdx.x] = mm + __logf(ll);
+        for (int s = 0; s < n_splits; ++s) ml_merge(mm, ll, p[2 * s], p[2 * s + 1]);
+        const float v = mm + __logf(ll);
+        lse_s[threadIdx.x] = v;
+        if (split == 0) lse_out[(size_t)b * g.Hq + hk * g.G + threadIdx.x] = v;
     }
     __syncthreads();
-    float o[kMaxG][EPL];
-    for (int hh = 0; hh < kMaxG; ++hh)
+    float lse_r[MAXG];
+    const float* lrow[MAXG];
+#pragma unroll
+    for (int hh = 0; hh < MAXG; ++hh) {
+        lse_r[hh] = hh < g.G ? lse_s[hh] : 0.f;
+        lrow[hh] = logits + ((size_t)b * g.Hq + hk * g.G + (hh < g.G ? hh : 0)) * lstride;
+    }
+    float o[MAXG][EPL];
+#pragma unroll
+    for (int hh = 0; hh < MAXG; ++hh)
 #pragma unroll
         for (int x = 0; x < EPL; ++x) o[hh][x] = 0.f;
-    const int j0 = split * per_split, j1 = min(n, j0 + per_split);
-    for (int jb = j0; jb < j1; jb += kRowsPerIter) {
-        const int j = jb + grp;
-        if (j < j1) {
-            int off;
-            const int si = seg_of(sl, j, &off);
-            const int slot = sl.s[si].start + off;
-            float vv[EPL];
-            VecLoad<T, EPL>::load(Vc + ((size_t)bh * g.slots + slot) * g.d + lane * EPL, vv);
-            float red = 0.f;
-            for (int hh = 0; hh < g.G; ++hh) {
-                const float p = __expf(logits[((size_t)b * g.Hq + hk * g.G + hh) * lstride + j] - lse_s[hh]);
+    const int j0 = split * per_split, j1 = min(ncached, j0 + per_split);
+    const float beta = g.beta, omb = 1.f - g.beta;
+
+    int seg_first = 0;
+    for (int si = 0; si < sl.n; ++si) {
+        const Seg sg = sl.s[si];
+        const int lo = max(j0, seg_first), hi = min(j1, seg_first + sg.len);
+        if (lo < hi) {
+            const T* vseg = Vc + ((ptrdiff_t)bh * g.slots + sg.start - seg_first) * d;
+            float* museg = mu + ((ptrdiff_t)bh * g.slots + sg.start - seg_first);
+            for (int r0 = lo + grp * U; r0 < hi; r0 += kRowGroups * U) {
+                float vv[U][EPL];
+                float lg[U][MAXG];
 #pragma unroll
-                for (int x = 0; x < EPL; ++x) o[hh][x] += p * vv[x];
-                red = (g.head_reduce == CASCADE_REDUCE_MAX) ? (hh == 0 ? p : fmaxf(red, p)) : red + p;
-            }
-            if (lane == 0) {
-                if (g.head_reduce == CASCADE_REDUCE_MEAN) red /= (float)g.G;
-                float* pm = mu + (size_t)bh * g.slots + slot;
-                *pm = g.beta * *pm + (1.f - g.beta) * red;
+                for (int u = 0; u < U; ++u) {
+                    const int r = min(r0 + u, hi - 1);
+                    VecLoad<T, EPL>::load(vseg + (size_t)r * d + lane * EPL, vv[u]);
+#pragma unroll
+                    for (int hh = 0; hh < MAXG; ++hh) lg[u][hh] = hh < g.G ? lrow[hh][r] : -INFINITY;
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const bool ok = r0 + u < hi;
+                    float red = 0.f;
+#pragma unroll
+                    for (int hh = 0; hh < MAXG; ++hh)
+                        if (hh < g.G) {
+                            const float p = ok ? __expf(lg[u][hh] - lse_r[hh]) : 0.f;
+#pragma unroll
+                            for (int x = 0; x < EPL; ++x) o[hh][x] += p * vv[u][x];
+                            red = (g.head_reduce == CASCADE_REDUCE_MAX) ? fmaxf(red, p) : red + p;
+                        }
+                    if (lane == 0 && ok) {
+                        if (g.head_reduce == CASCADE_REDUCE_MEAN) red /= (float)g.G;
+                        float* pm = museg + r0 + u;
+                        *pm = beta * *pm + omb * red;
+                    }
+                }
             }
         }
+        seg_first += sg.len;
     }
     // the four row groups of a wave first add up through lane shuffles
-    for (int hh = 0; hh < g.G; ++hh)
+#pragma unroll
+    for (int hh = 0; hh < MAXG; ++hh)
 #pragma unroll
         for (int x = 0; x < EPL; ++x) {
             float t = o[hh][x];
@@ -227,11 +389,11 @@ __global__ void decode_pv_kernel(Geom g, SegList sl, int per_split, const T* __r
             if (grp % 4 == 0) osum[grp / 4][hh][lane * EPL + x] = t;
         }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < g.G * g.d; idx += kDecThreads) {
-        const int hh = idx / g.d, e = idx % g.d;
+    for (int idx = threadIdx.x; idx < g.G * d; idx += kDecThreads) {
+        const int hh = idx / d, e = idx % d;
         float s = 0.f;
         for (int r = 0; r < kDecThreads / 64; ++r) s += osum[r][hh][e];
-        opart[(((size_t)b * g.Hq + hk * g.G + hh) * n_splits + split) * g.d + e] = s;
+        opart[(((size_t)b * g.Hq + hk * g.G + hh) * n_splits + split) * d + e] = s;
     }
 }
 
@@ -258,48 +420,74 @@ __global__ void decode_finish_kernel(Geom g, int n_cached, int n_splits, int qst
         for (int hh = 0; hh < g.G; ++hh) {
             const int h = hk * g.G + hh;
             const float p = __expf(logits[((size_t)b * g.Hq + h) * lstride + n_cached] - lse[(size_t)b * g.Hq + h]);
-            red = (g.head_reduce == CASCADE_REDUCE_MAX) ? (hh == 0 ? p : fmaxf(red, p)) : red + p;
+            red = (g.head_reduce == CASCADE_REDUCE_MAX) ? fmaxf(red, p) : red + p;
         }
         if (g.head_reduce == CASCADE_REDUCE_MEAN) red /= (float)g.G;
         mu_chunk[((size_t)b * g.Hkv + hk) * qstride] = (1.f - g.beta) * red;
     }
 }
 
+// ------------------------------------------------------------------ launchers
+
 static int per_split_of(const DevBuffers& bf, int n)
 {
     int per_split = (n + bf.dec_splits - 1) / bf.dec_splits;
-    per_split = ((per_split + kRowsPerIter - 1) / kRowsPerIter) * kRowsPerIter;
-    return per_split == 0 ? kRowsPerIter : per_split;
+    per_split = ((per_split + 63) / 64) * 64;
+    return per_split == 0 ? 64 : per_split;
 }
 
-template <typename T, int EPL>
-static void qk_typed(const Geom& g, const DevBuffers& bf, const SegList& sl, const void* q, const void* k, hipStream_t s)
+static int maxg_of(const Geom& g) { return g.G <= 1 ? 1 : (g.G <= 2 ? 2 : (g.G <= 4 ? 4 : 8)); }
+
+template <typename T, int EPL, int MAXG>
+static void qk_valu(const Geom& g, const DevBuffers& bf, const SegList& sl, const void* q, const void* k, hipStream_t s)
 {
     const dim3 grid(bf.dec_splits, g.Hkv, g.B), block(kDecThreads);
-    hipLaunchKernelGGL((decode_qk_kernel<T, EPL>), grid, block, 0, s, g, sl, per_split_of(bf, sl.n_cached), (const T*)q,
-                       (const T*)k, (const T*)bf.Kr, bf.rope, bf.logits, bf.part, bf.dec_splits);
+    hipLaunchKernelGGL((decode_qk_valu_kernel<T, EPL, MAXG>), grid, block, 0, s, g, sl, per_split_of(bf, sl.n_cached),
+                       (const T*)q, (const T*)k, (const T*)bf.Kr, bf.rope, bf.logits, bf.part, bf.dec_splits);
 }
 
-template <typename T, int EPL>
+template <typename T, int EPL, int MAXG>
 static void pv_typed(const Geom& g, const DevBuffers& bf, const SegList& sl, hipStream_t s)
 {
     const dim3 grid(bf.dec_splits, g.Hkv, g.B), block(kDecThreads);
     // the log-sum-exp of the step lives in the first B*Hq entries of the chunk scratch
-    hipLaunchKernelGGL((decode_pv_kernel<T, EPL>), grid, block, 0, s, g, sl, per_split_of(bf, sl.n_cached), (const T*)bf.Vc,
-                       bf.logits, bf.part, bf.dec_splits, bf.opart, bf.mu, bf.lse);
+    hipLaunchKernelGGL((decode_pv_kernel<T, EPL, MAXG>), grid, block, 0, s, g, sl, per_split_of(bf, sl.n_cached),
+                       (const T*)bf.Vc, bf.logits, bf.part, bf.dec_splits, bf.opart, bf.mu, bf.lse);
 }
 
-#define CKV_DISPATCH(fn, ...)                                                     \
-    do {                                                                          \
-        const int epl = g.d / kLanesPerRow;                                       \
-        if (dtype == CASCADE_F32) { if (epl == 8) fn<float, 8>(__VA_ARGS__); else fn<float, 4>(__VA_ARGS__); } \
-        else { if (epl == 8) fn<bf16_t, 8>(__VA_ARGS__); else fn<bf16_t, 4>(__VA_ARGS__); }                    \
+#define CKV_G_SWITCH(fn, T, EPL, ...)                          \
+    switch (maxg_of(g)) {                                      \
+        case 1: fn<T, EPL, 1>(__VA_ARGS__); break;             \
+        case 2: fn<T, EPL, 2>(__VA_ARGS__); break;             \
+        case 4: fn<T, EPL, 4>(__VA_ARGS__); break;             \
+        default: fn<T, EPL, 8>(__VA_ARGS__); break;            \
+    }
+
+#define CKV_DISPATCH(fn, ...)                                                                   \
+    do {                                                                                        \
+        const int epl = g.d / kLanesPerRow;                                                     \
+        if (dtype == CASCADE_F32) {                                                             \
+            if (epl == 8) { CKV_G_SWITCH(fn, float, 8, __VA_ARGS__) } else { CKV_G_SWITCH(fn, float, 4, __VA_ARGS__) } \
+        } else {                                                                                \
+            if (epl == 8) { CKV_G_SWITCH(fn, bf16_t, 8, __VA_ARGS__) } else { CKV_G_SWITCH(fn, bf16_t, 4, __VA_ARGS__) } \
+        }                                                                                       \
     } while (0)
 
 void launch_decode_qk(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, const void* q, const void* k,
                       hipStream_t s)
 {
-    CKV_DISPATCH(qk_typed, g, b, sl, q, k, s);
+    if (dtype == CASCADE_BF16) {
+        const dim3 grid(b.dec_splits, g.Hkv, g.B), block(kDecThreads);
+        const int ps = per_split_of(b, sl.n_cached);
+        if (g.d == 128)
+            hipLaunchKernelGGL(decode_qk_mfma_kernel<128>, grid, block, 0, s, g, sl, ps, (const bf16_t*)q, (const bf16_t*)k,
+                               (const bf16_t*)b.Kr, b.rope, b.logits, b.part, b.dec_splits);
+        else
+            hipLaunchKernelGGL(decode_qk_mfma_kernel<64>, grid, block, 0, s, g, sl, ps, (const bf16_t*)q, (const bf16_t*)k,
+                               (const bf16_t*)b.Kr, b.rope, b.logits, b.part, b.dec_splits);
+        return;
+    }
+    CKV_DISPATCH(qk_valu, g, b, sl, q, k, s);
 }
 
 void launch_decode_pv(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, hipStream_t s)
