@@ -241,8 +241,16 @@ static int64_t head_count(const oracle_config *cfg, const head_t *H)
 
 /* ------------------------------------------------------------------ one chunk */
 
-static void chunk_one_head(oracle_seq *S, int g, const float *q, const float *k, const float *v,
-                           int Q, double *out)
+/*
+ * Attention of the query rows [row_lo, row_hi) of a chunk of Q tokens for KV head g, against the
+ * cache as it is plus the chunk's own keys up to each row (Eq. 2, Fig. 4), and the EMA recurrence
+ * over exactly those rows, started at 0 before row_lo and reduced over the query heads of the
+ * group.  With row_lo = 0 and row_hi = Q this is the whole chunk.  The state is not modified.
+ * out [Q][Hq][d]: only the evaluated rows and the heads of g are written.
+ * delta [n + Q]: reduced increments in cache order, then chunk tokens.
+ */
+static void eval_rows(const oracle_seq *S, int g, const float *q, const float *k, const float *v,
+                      int Q, int row_lo, int row_hi, double *out, double *delta)
 {
     const oracle_config *cfg = &S->cfg;
     head_t *H = &S->head[g];
@@ -264,21 +272,20 @@ static void chunk_one_head(oracle_seq *S, int g, const float *q, const float *k,
         rope(order[j]->k, d, (double)j, cfg->rope_base, kr + j * d);
         memcpy(vv + j * d, order[j]->v, sizeof(double) * (size_t)d);
     }
-    for (int i = 0; i < Q; ++i) {
+    for (int i = 0; i < row_hi; ++i) {
         const float *ki = k + ((size_t)i * Hkv + g) * d, *vi = v + ((size_t)i * Hkv + g) * d;
         for (int e = 0; e < d; ++e) { tmp[e] = ki[e]; vv[(n + i) * d + e] = vi[e]; }
         rope(tmp, d, (double)(n + i), cfg->rope_base, kr + (n + i) * d);
     }
 
     double *delta_h = (double *)malloc(sizeof(double) * (size_t)nk);   /* one query head */
-    double *delta = (double *)malloc(sizeof(double) * (size_t)nk);     /* reduced over the group */
     double *p = (double *)malloc(sizeof(double) * (size_t)nk);
     double *qr = (double *)malloc(sizeof(double) * (size_t)d);
 
     for (int hh = 0; hh < G; ++hh) {
         const int h = g * G + hh;
         for (int64_t j = 0; j < nk; ++j) delta_h[j] = 0.0;
-        for (int i = 0; i < Q; ++i) {
+        for (int i = row_lo; i < row_hi; ++i) {
             const float *qi = q + ((size_t)i * Hq + h) * d;
             for (int e = 0; e < d; ++e) tmp[e] = qi[e];
             rope(tmp, d, (double)(n + i), cfg->rope_base, qr);
@@ -311,16 +318,34 @@ static void chunk_one_head(oracle_seq *S, int g, const float *q, const float *k,
         }
     }
     if (cfg->head_reduce == 1) for (int64_t j = 0; j < nk; ++j) delta[j] /= (double)G;
+    free(order); free(kr); free(vv); free(tmp); free(delta_h); free(p); free(qr);
+}
+
+static void chunk_one_head(oracle_seq *S, int g, const float *q, const float *k, const float *v,
+                           int Q, double *out)
+{
+    const oracle_config *cfg = &S->cfg;
+    head_t *H = &S->head[g];
+    const int d = cfg->head_dim, Hkv = cfg->n_kv_heads;
+    const double beta = cfg->ema_beta;
+    const int64_t n = head_count(cfg, H);
+    double *delta = (double *)malloc(sizeof(double) * (size_t)(n + Q));
+    eval_rows(S, g, q, k, v, Q, 0, Q, out, delta);
 
     /* cached items decay once per row of the chunk, then receive the reduced increment */
+    int64_t cap_total = cfg->n_sink;
+    for (int c = 0; c < cfg->n_cascades; ++c) cap_total += cfg->cascade_sizes[c];
+    item_t **order = (item_t **)malloc(sizeof(item_t *) * (size_t)(cap_total + 1));
+    head_order(cfg, H, order);
     for (int64_t j = 0; j < n; ++j) {
         double mu = order[j]->mu;
         for (int i = 0; i < Q; ++i) mu *= beta;
         order[j]->mu = mu + delta[j];
     }
+    free(order);
     free(H->last_delta);
     H->last_delta = delta;
-    H->last_delta_n = nk;
+    H->last_delta_n = n + Q;
 
     /* the chunk's tokens enter the cache in order with their frozen scores (Alg. 1, Alg. 2) */
     for (int i = 0; i < Q; ++i) {
@@ -333,8 +358,6 @@ static void chunk_one_head(oracle_seq *S, int g, const float *q, const float *k,
         for (int e = 0; e < d; ++e) { x.k[e] = ki[e]; x.v[e] = vi[e]; }
         cache_insert(cfg, H, x);
     }
-
-    free(order); free(kr); free(vv); free(tmp); free(delta_h); free(p); free(qr);
 }
 
 /*
@@ -350,6 +373,20 @@ int oracle_chunk(oracle_seq *S, const float *q, const float *k, const float *v, 
     if (kv_lo < 0 || kv_hi > S->cfg.n_kv_heads || kv_lo >= kv_hi) return -1;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int g = kv_lo; g < kv_hi; ++g) chunk_one_head(S, g, q, k, v, Q, out);
+    return 0;
+}
+
+/*
+ * Rows [row_lo, row_hi) of a chunk only, for KV head g, without touching the cache: their
+ * outputs and the EMA increments those rows alone produce (see eval_rows).  Lets a test check
+ * sampled rows of a chunk that is too long to evaluate whole.  delta holds count(g) + Q values.
+ */
+int oracle_eval_rows(const oracle_seq *S, int g, const float *q, const float *k, const float *v, int Q,
+                     int row_lo, int row_hi, double *out, double *delta)
+{
+    if (!S || !q || !k || !v || !out || !delta) return -1;
+    if (g < 0 || g >= S->cfg.n_kv_heads || row_lo < 0 || row_hi > Q || row_lo >= row_hi) return -1;
+    eval_rows(S, g, q, k, v, Q, row_lo, row_hi, out, delta);
     return 0;
 }
 

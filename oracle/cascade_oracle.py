@@ -52,6 +52,8 @@ def _lib():
         L.oracle_destroy.argtypes = [P]
         L.oracle_chunk.restype = ctypes.c_int
         L.oracle_chunk.argtypes = [P, P, P, P, ctypes.c_int, P, ctypes.c_int, ctypes.c_int]
+        L.oracle_eval_rows.restype = ctypes.c_int
+        L.oracle_eval_rows.argtypes = [P, ctypes.c_int, P, P, P, ctypes.c_int, ctypes.c_int, ctypes.c_int, P, P]
         L.oracle_insert_scored.restype = ctypes.c_int
         L.oracle_insert_scored.argtypes = [P, ctypes.c_int, ctypes.c_double]
         for name in ("oracle_count", "oracle_t", "oracle_n_seen"):
@@ -157,6 +159,23 @@ class OracleSeq:
         if rc != 0:
             raise RuntimeError("oracle_chunk failed")
         return out
+
+    def eval_rows(self, kv_head: int, q: np.ndarray, k: np.ndarray, v: np.ndarray, row_lo: int, row_hi: int):
+        """Rows [row_lo, row_hi) of the chunk (q, k, v) for one KV head, cache untouched.
+        Returns (out [Q,Hq,d] with only those rows and that head group written,
+        delta [count + Q]: the EMA increments those rows alone produce)."""
+        cfg = self.cfg
+        q = np.ascontiguousarray(q, dtype=np.float32)
+        k = np.ascontiguousarray(k, dtype=np.float32)
+        v = np.ascontiguousarray(v, dtype=np.float32)
+        Q = q.shape[0]
+        assert q.shape == (Q, cfg.n_q_heads, cfg.head_dim) and k.shape == (Q, cfg.n_kv_heads, cfg.head_dim)
+        out = np.zeros((Q, cfg.n_q_heads, cfg.head_dim), dtype=np.float64)
+        delta = np.zeros(self.count(kv_head) + Q, dtype=np.float64)
+        rc = _lib().oracle_eval_rows(self._h, kv_head, _ptr(q), _ptr(k), _ptr(v), Q, row_lo, row_hi, _ptr(out), _ptr(delta))
+        if rc != 0:
+            raise RuntimeError("oracle_eval_rows failed")
+        return out, delta
 
     def decode(self, q: np.ndarray, k: np.ndarray, v: np.ndarray, kv_heads=None) -> np.ndarray:
         """One decode step: q [Hq,d], k, v [Hkv,d] -> out [Hq,d]."""

@@ -126,7 +126,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_qk_mfma_kernel(
             for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
                 for (int x = 0; x < 4; ++x) {
-                    const int e = c * (D / 4) + ks * 8 + 2 * x;
+                    const int e = ks * 32 + c * 8 + 2 * x;
                     const float a0 = head_ok ? q_rot_elem<bf16_t>(qh, rope, rot, D / 2, e, g.scale) : 0.f;
                     const float a1 = head_ok ? q_rot_elem<bf16_t>(qh, rope, rot, D / 2, e + 1, g.scale) : 0.f;
                     qf[ks].u[x] = dec_pack_bf16(a0, a1);
@@ -138,9 +138,9 @@ __global__ __launch_bounds__(kDecThreads) void decode_qk_mfma_kernel(
 #pragma unroll
                 for (int gi = 0; gi < NG; ++gi) {
                     const int row = min(r0 + gi * 16 + n, hi - 1);      // rows past the end repeat the last one
-                    const bf16_t* kp = kseg + (size_t)row * D + c * (D / 4);
+                    const bf16_t* kp = kseg + (size_t)row * D + c * 8;
 #pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) kf[gi][ks].u = *reinterpret_cast<const du32x4_t*>(kp + ks * 8);
+                    for (int ks = 0; ks < KS; ++ks) kf[gi][ks].u = *reinterpret_cast<const du32x4_t*>(kp + ks * 32);
                 }
 #pragma unroll
                 for (int gi = 0; gi < NG; ++gi) {

@@ -60,16 +60,49 @@ class StepReport:
     replay_exact: bool = True
 
 
+def gpu_decision_scores(st, b, g, npre, n_tok) -> np.ndarray:
+    """Scores the library took its insertion decisions with: items cached before the call (cache
+    order before the call), then the call's tokens."""
+    return np.concatenate([st.pre_mu[b, g, :npre], st.chunk_mu[b, g, :n_tok]]).astype(np.float64)
+
+
+def replay_is_exact(cfg: B.cascade_config, prev, st, b, g, mu_gpu) -> bool:
+    """Alg. 2 replayed by the oracle with the library's own scores, from the library's state
+    before the call (`prev`), must give the library's state after it (`st`) bit for bit."""
+    npre = prev.count
+    pol = policy_oracle(cfg)
+    zeros = np.zeros((npre, 2), dtype=np.float32)
+    pol.set_state(0, prev.ids[b, g, :npre].astype(np.int64), mu_gpu[:npre], prev.counts, zeros, zeros,
+                  prev.t, prev.n_seen)
+    for s in mu_gpu[npre:]:
+        pol.insert_scored(0, float(s))
+    ps = pol.state(0)
+    cnt = st.count
+    ok = (ps.ids.tolist() == st.ids[b, g, :cnt].tolist()
+          and np.array_equal(ps.mu.astype(np.float32), st.mu[b, g, :cnt])
+          and ps.counts.tolist() == st.counts.tolist() and ps.t == st.t and ps.n_seen == st.n_seen)
+    pol.close()
+    return bool(ok)
+
+
+def row_errors(out, ref, heads) -> float:
+    """max over rows of ||out - ref|| / ||ref|| for the given query heads; out, ref [rows, Hq, d]."""
+    num = np.linalg.norm(out[:, heads] - ref[:, heads], axis=-1)
+    den = np.linalg.norm(ref[:, heads], axis=-1)
+    return float((num / np.maximum(den, 1e-30)).max())
+
+
 class ParityRun:
-    """One library context and one oracle per sequence, advanced together."""
+    """One library context and one oracle per compared sequence, advanced together."""
 
     def __init__(self, cfg: B.cascade_config, one_step_ahead: bool, kv_heads: Optional[List[int]] = None,
-                 init_state: Optional[B.cascade_init_state] = None, device="cuda:0"):
+                 init_state: Optional[B.cascade_init_state] = None, device="cuda:0", seqs: Optional[List[int]] = None):
         assert cfg.keep_update_scores == 1
         self.cfg = cfg
         self.gpu = CascadeKVCache(cfg, device, init_state)
         self.ocfg = oracle_config_of(cfg)
-        self.oracles = [OracleSeq(self.ocfg) for _ in range(cfg.batch)]
+        self.seqs = list(range(cfg.batch)) if seqs is None else seqs
+        self.oracles = {b: OracleSeq(self.ocfg) for b in self.seqs}
         self.one_step = one_step_ahead
         self.heads = list(range(cfg.n_kv_heads)) if kv_heads is None else kv_heads
         self.G = cfg.n_q_heads // cfg.n_kv_heads
@@ -81,11 +114,18 @@ class ParityRun:
     def sync_oracle_from_gpu(self, st=None):
         st = st if st is not None else self.gpu.read_state(with_kv=True)
         n = st.count
-        for b, o in enumerate(self.oracles):
+        for b, o in self.oracles.items():
             for g in self.heads:
                 o.set_state(g, st.ids[b, g, :n].astype(np.int64), st.mu[b, g, :n].astype(np.float64), st.counts,
                             st.k[b, g, :n], st.v[b, g, :n], st.t, st.n_seen)
         self.prev = st
+
+    def advance_gpu_only(self, dq, dk, dv, decode: bool = False):
+        """A step that is not compared (device tensors); the oracle falls behind until the next sync."""
+        if decode:
+            self.gpu.decode_step(dq, dk, dv)
+        else:
+            self.gpu.prefill_chunk(dq, dk, dv)
 
     # -- one compared step -----------------------------------------------------
     def step(self, q: np.ndarray, k: np.ndarray, v: np.ndarray, decode: bool = False) -> StepReport:
@@ -101,38 +141,26 @@ class ParityRun:
         out = out.float().cpu().numpy()
         rep = StepReport()
         beta = float(np.float32(cfg.ema_beta))
-        for b, o in enumerate(self.oracles):
+        for b, o in self.oracles.items():
             pre = {g: o.state(g) for g in self.heads}
             hs = (min(self.heads), max(self.heads) + 1)
             ref = o.chunk(q[b], k[b], v[b], kv_heads=hs)
             for g in self.heads:
                 hq = slice(g * self.G, (g + 1) * self.G)
-                num = np.linalg.norm(out[b][:, hq] - ref[:, hq], axis=-1)
-                den = np.linalg.norm(ref[:, hq], axis=-1)
-                rep.out_err = max(rep.out_err, float((num / np.maximum(den, 1e-30)).max()))
+                rep.out_err = max(rep.out_err, row_errors(out[b], ref, hq))
                 # scores the decisions are taken with
                 delta = o.last_delta(g)
                 npre = len(pre[g].ids)
                 assert st.pre_count == npre and st.last_tokens == n_tok
                 mu_ref = np.concatenate([pre[g].mu * beta ** n_tok + delta[:npre], delta[npre:]])
-                mu_gpu = np.concatenate([st.pre_mu[b, g, :npre], st.chunk_mu[b, g, :n_tok]]).astype(np.float64)
+                mu_gpu = gpu_decision_scores(st, b, g, npre, n_tok)
                 rel = np.abs(mu_gpu - mu_ref) / np.maximum(np.abs(mu_ref), 1e-12)
                 rep.score_err = max(rep.score_err, float(rel.max()))
                 # decisions: Alg. 2 replayed with the library's scores
-                pol = policy_oracle(cfg)
-                zeros = np.zeros((npre, 2), dtype=np.float32)
-                pol.set_state(0, self.prev.ids[b, g, :npre].astype(np.int64), mu_gpu[:npre], self.prev.counts,
-                              zeros, zeros, self.prev.t, self.prev.n_seen)
-                for s in mu_gpu[npre:]:
-                    pol.insert_scored(0, float(s))
-                ps = pol.state(0)
-                cnt = st.count
-                exact = (ps.ids.tolist() == st.ids[b, g, :cnt].tolist()
-                         and np.array_equal(ps.mu.astype(np.float32), st.mu[b, g, :cnt])
-                         and ps.counts.tolist() == st.counts.tolist() and ps.t == st.t and ps.n_seen == st.n_seen)
-                rep.replay_exact &= bool(exact)
+                rep.replay_exact &= replay_is_exact(cfg, self.prev, st, b, g, mu_gpu)
                 # drift against the oracle on its own scores
                 post = o.state(g)
+                cnt = st.count
                 rep.compared += cnt
                 if post.counts.tolist() != st.counts.tolist():
                     rep.drift += cnt
@@ -147,5 +175,5 @@ class ParityRun:
 
     def close(self):
         self.gpu.close()
-        for o in self.oracles:
+        for o in self.oracles.values():
             o.close()

@@ -189,3 +189,40 @@ def test_rope_relative_shift(oracle_mod):
                            1000.0, d ** -0.5)
     keep = P[:, lead:].sum(axis=1, keepdims=True)     # mass left on the real tokens
     np.testing.assert_allclose(out[:, 0], ref[:, 0] * keep, rtol=1e-9, atol=1e-12)
+
+
+def test_row_range_evaluation_matches_whole_chunk(oracle_mod):
+    """oracle.eval_rows over all rows reproduces the chunk's outputs and increments; over a tail
+    of rows it gives the dense formula restricted to those rows (weights beta^(Q-1-i)(1-beta))."""
+    rng = np.random.default_rng(16)
+    Hq, Hkv, d, Q, beta, base = 4, 2, 8, 12, 0.7, 100.0
+    cfg = OracleConfig(n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, n_sink=2, cascade_sizes=[5, 5],
+                       ema_beta=beta, rope_base=base)
+    o = OracleSeq(cfg)
+    for _ in range(3):
+        o.chunk(_rand(rng, Q, Hq, d), _rand(rng, Q, Hkv, d), _rand(rng, Q, Hkv, d))
+    q, k, v = _rand(rng, Q, Hq, d), _rand(rng, Q, Hkv, d), _rand(rng, Q, Hkv, d)
+    g = 1
+    before = o.state(g, with_kv=True)
+    full_out, full_delta = o.eval_rows(g, q, k, v, 0, Q)
+    tail_out, tail_delta = o.eval_rows(g, q, k, v, Q - 4, Q)
+    assert o.state(g).ids.tolist() == before.ids.tolist()          # the cache is untouched
+    n = len(before.ids)
+    keys = np.concatenate([before.k, k[:, g].astype(np.float64)])
+    vals = np.concatenate([before.v, v[:, g].astype(np.float64)])
+    vis = np.concatenate([np.ones((Q, n), bool), np.tril(np.ones((Q, Q), bool))], axis=1)
+    w = beta ** (Q - 1 - np.arange(Q)) * (1 - beta)
+    d_full, d_tail = [], []
+    for hh in range(Hq // Hkv):
+        h = g * (Hq // Hkv) + hh
+        ref, P = dense_attention(q[:, h].astype(np.float64), n + np.arange(Q), keys, np.arange(n + Q), vals, vis,
+                                 base, d ** -0.5)
+        np.testing.assert_allclose(full_out[:, h], ref, rtol=1e-10, atol=1e-12)
+        np.testing.assert_allclose(tail_out[Q - 4:, h], ref[Q - 4:], rtol=1e-10, atol=1e-12)
+        d_full.append(w @ P)
+        d_tail.append(w[Q - 4:] @ P[Q - 4:])
+    np.testing.assert_allclose(full_delta, np.max(d_full, axis=0), rtol=1e-10, atol=1e-15)
+    np.testing.assert_allclose(tail_delta, np.max(d_tail, axis=0), rtol=1e-10, atol=1e-15)
+    out = o.chunk(q, k, v, kv_heads=(g, g + 1))
+    np.testing.assert_array_equal(out[:, 2:], full_out[:, 2:])
+    np.testing.assert_array_equal(o.last_delta(g), full_delta)
