@@ -156,17 +156,19 @@ __device__ inline uint2 lds_read_tr16(const bf16_t* p)
     return __builtin_bit_cast(uint2, r);
 }
 
-// THREADS / 64 waves, one 32-row query block each.  With 512 threads one workgroup fills a
-// compute unit (two waves per SIMD); with 256 threads two workgroups share it.
-template <int D, int THREADS>
-__global__ __launch_bounds__(THREADS, 512 / THREADS) void attn_mfma_kernel(
+// WAVES waves per workgroup; every wave owns R blocks of 32 query rows (a K or V fragment read
+// from LDS is then used by R MFMAs).  R = 1 with 8 waves puts two waves on each SIMD; R = 2 with
+// 4 waves halves the LDS traffic per MFMA and uses the whole register file for one wave per SIMD.
+template <int D, int WAVES, int R>
+__global__ __launch_bounds__(WAVES * 64, (R == 1 ? 8 / WAVES : 1)) void attn_mfma_kernel(
     Geom g, SegList sl, int Q, const bf16_t* __restrict__ Qr, const bf16_t* __restrict__ Kr,
     const bf16_t* __restrict__ Vc, const bf16_t* __restrict__ Krc, const bf16_t* __restrict__ Vch,
     bf16_t* __restrict__ out, float* __restrict__ lse)
 {
-    constexpr int BM = THREADS / 2;   // query rows per workgroup
-    constexpr int KS = D / 16;        // k-steps of S^T = K Q^T
-    constexpr int DB = D / 32;        // 32-wide blocks of the head dimension in O^T
+    constexpr int THREADS = WAVES * 64;
+    constexpr int BM = WAVES * 32 * R;   // query rows per workgroup
+    constexpr int KS = D / 16;           // k-steps of S^T = K Q^T
+    constexpr int DB = D / 32;           // 32-wide blocks of the head dimension in O^T
     constexpr int KSTR = TileLayout<D>::KSTR;   // LDS row strides (elements)
     constexpr int VSTR = TileLayout<D>::VSTR;
     __shared__ __attribute__((aligned(16))) bf16_t Ks[2][kBN * KSTR];
@@ -178,28 +180,37 @@ __global__ __launch_bounds__(THREADS, 512 / THREADS) void attn_mfma_kernel(
     const int tid = threadIdx.x, wave = tid >> 6, l = tid & 63, l32 = l & 31, half = l >> 5;
     const int GQ = g.G * Q;
 
-    // the query of this lane; rows are (head, token) pairs
-    const int r_row = tile * BM + wave * 32 + l32;
-    const bool qvalid = r_row < GQ;
-    const int rc = min(r_row, GQ - 1);
-    const int qh = hk * g.G + rc / Q, qi = rc % Q;
+    // the queries of this lane (one per 32-row block of the wave); rows are (head, token) pairs
+    int qi[R], qh[R];
+    bool qvalid[R];
+#pragma unroll
+    for (int qb = 0; qb < R; ++qb) {
+        const int r_row = tile * BM + (wave * R + qb) * 32 + l32;
+        qvalid[qb] = r_row < GQ;
+        const int rc = min(r_row, GQ - 1);
+        qh[qb] = hk * g.G + rc / Q;
+        qi[qb] = rc % Q;
+    }
     int wave_imax, wave_imin, wg_imax;
     {
-        const int r_lo = min(tile * BM + wave * 32, GQ - 1), r_hi = min(tile * BM + wave * 32 + 31, GQ - 1);
+        const int r_lo = min(tile * BM + wave * R * 32, GQ - 1), r_hi = min(tile * BM + wave * R * 32 + R * 32 - 1, GQ - 1);
         if (r_lo / Q == r_hi / Q) { wave_imin = r_lo % Q; wave_imax = r_hi % Q; }
         else { wave_imin = 0; wave_imax = Q - 1; }
         const int w_lo = min(tile * BM, GQ - 1), w_hi = min(tile * BM + BM - 1, GQ - 1);
         wg_imax = (w_lo / Q == w_hi / Q) ? w_hi % Q : Q - 1;
     }
 
-    f32x16_t o[DB];
+    f32x16_t o[DB][R];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) o[db][j] = 0.f;
+        for (int qb = 0; qb < R; ++qb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) o[db][qb][j] = 0.f;
     const float c2 = g.scale * 1.4426950408889634f;   // logits to base-2 exponents
-    float m_run = -INFINITY;                           // maximum the exponents are taken against
-    float lsum = 0.f;                                  // this lane's part of the row sum
+    float m_run[R], lsum[R];                           // maximum the exponents are taken against; row sum (this lane's part)
+#pragma unroll
+    for (int qb = 0; qb < R; ++qb) { m_run[qb] = -INFINITY; lsum[qb] = 0.f; }
 
     TileIter cur, nxt;
     cur.first(sl, wg_imax);
@@ -215,7 +226,7 @@ __global__ __launch_bounds__(THREADS, 512 / THREADS) void attn_mfma_kernel(
     const int k_lane = l32 * KSTR + half * 8;
     const int v_lane = (4 * half + ((l & 15) >> 2)) * VSTR + 16 * ((l >> 4) & 1) + 4 * (l & 3);
 
-    Frag qf[KS];
+    Frag qf[R][KS];
     int q_seg = -1;
     int buf = 0;
     while (cur.valid(sl)) {
@@ -226,20 +237,25 @@ __global__ __launch_bounds__(THREADS, 512 / THREADS) void attn_mfma_kernel(
 
         if (!(cur.sg.chunk && cur.t0 > wave_imax)) {   // else: every key of the tile lies after this wave's rows
             if (q_seg != cur.si) {                     // this segment's rotated copy of the queries
-                const bf16_t* qrow = Qr + ((((size_t)cur.sg.qvar * g.B + b) * g.Hq + qh) * Q + qi) * D + half * 8;
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) qf[ks].u = *reinterpret_cast<const u32x4_t*>(qrow + ks * 16);
+                for (int qb = 0; qb < R; ++qb) {
+                    const bf16_t* qrow = Qr + ((((size_t)cur.sg.qvar * g.B + b) * g.Hq + qh[qb]) * Q + qi[qb]) * D + half * 8;
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) qf[qb][ks].u = *reinterpret_cast<const u32x4_t*>(qrow + ks * 16);
+                }
                 q_seg = cur.si;
             }
             const bf16_t* Kb = Ks[buf] + k_lane;
             const bf16_t* Vb = Vs[buf] + v_lane;
-            // S^T tile: 2 key blocks x this wave's query block.  The fragments are read in two
-            // groups ahead of the MFMAs that use them.
-            f32x16_t s[2];
+            // S^T tile: 2 key blocks x R query blocks.  The K fragments are read in two groups
+            // ahead of the MFMAs that use them.
+            f32x16_t s[2][R];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int j = 0; j < 16; ++j) s[kb][j] = 0.f;
+                for (int qb = 0; qb < R; ++qb)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) s[kb][qb][j] = 0.f;
             {
                 Frag kf[2][KS];
 #pragma unroll
@@ -257,13 +273,17 @@ __global__ __launch_bounds__(THREADS, 512 / THREADS) void attn_mfma_kernel(
                 for (int ks = 0; ks < KS / 2; ++ks)
 #pragma unroll
                     for (int kb = 0; kb < 2; ++kb)
-                        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ks].v, qf[ks].v, s[kb], 0, 0, 0);
+#pragma unroll
+                        for (int qb = 0; qb < R; ++qb)
+                            s[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ks].v, qf[qb][ks].v, s[kb][qb], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int ks = KS / 2; ks < KS; ++ks)
 #pragma unroll
                     for (int kb = 0; kb < 2; ++kb)
-                        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ks].v, qf[ks].v, s[kb], 0, 0, 0);
+#pragma unroll
+                        for (int qb = 0; qb < R; ++qb)
+                            s[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ks].v, qf[qb][ks].v, s[kb][qb], 0, 0, 0);
             }
             // V fragments of the first key block: their latency hides behind the softmax
             // (V^T as the A operand: row = column of V, 8 keys per lane, through two transposing
@@ -283,49 +303,52 @@ __global__ __launch_bounds__(THREADS, 512 / THREADS) void attn_mfma_kernel(
 
             const int t0 = cur.t0;
             if ((t0 + kBN > cur.sg.len) || (cur.sg.chunk && t0 + kBN - 1 > wave_imin)) {
-                const int lim = cur.sg.chunk ? min(cur.sg.len - 1, qi) : cur.sg.len - 1;   // last visible key
+#pragma unroll
+                for (int qb = 0; qb < R; ++qb) {
+                    const int lim = cur.sg.chunk ? min(cur.sg.len - 1, qi[qb]) : cur.sg.len - 1;   // last visible key
+#pragma unroll
+                    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                        for (int j = 0; j < 16; ++j) {
+                            const int kk = t0 + kb * 32 + (j >> 2) * 8 + half * 4 + (j & 3);
+                            if (kk > lim) s[kb][qb][j] = -INFINITY;
+                        }
+                }
+            }
+            // raise the running maximum only when it grew by more than 2^kRescaleLog2: the
+            // probabilities then stay below that factor, and most tiles skip the rescaling of O
+            float mt[R];
+            bool grow = false;
+#pragma unroll
+            for (int qb = 0; qb < R; ++qb) {
+                float x = -INFINITY;
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                    for (int j = 0; j < 16; ++j) {
-                        const int kk = t0 + kb * 32 + (j >> 2) * 8 + half * 4 + (j & 3);
-                        if (kk > lim) s[kb][j] = -INFINITY;
-                    }
+                    for (int j = 0; j < 16; ++j) x = fmaxf(x, s[kb][qb][j]);
+                mt[qb] = max_xor32(x);
+                grow |= (mt[qb] - m_run[qb]) * c2 > kRescaleLog2;
             }
-            float mt = -INFINITY;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) mt = fmaxf(mt, s[kb][j]);
-            mt = max_xor32(mt);
-            // raise the running maximum only when it grew by more than 2^kRescaleLog2: the
-            // probabilities then stay below that factor, and most tiles skip the rescaling of O
-            const bool grow = (mt - m_run) * c2 > kRescaleLog2;
             if (__any(grow)) {
-                const float mn = grow ? mt : m_run;
-                const float alpha = __builtin_amdgcn_exp2f((m_run - mn) * c2);   // 0 on the first tile
-                m_run = mn;
-                lsum *= alpha;
 #pragma unroll
-                for (int db = 0; db < DB; ++db)
+                for (int qb = 0; qb < R; ++qb) {
+                    const float mn = (mt[qb] - m_run[qb]) * c2 > kRescaleLog2 ? mt[qb] : m_run[qb];
+                    const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - mn) * c2);   // 0 on the first tile
+                    m_run[qb] = mn;
+                    lsum[qb] *= alpha;
 #pragma unroll
-                    for (int j = 0; j < 16; ++j) o[db][j] *= alpha;
+                    for (int db = 0; db < DB; ++db)
+#pragma unroll
+                        for (int j = 0; j < 16; ++j) o[db][qb][j] *= alpha;
+                }
             }
-            const float mc = m_run * c2;
-            Frag pf[2][2];   // [key block][16-key half]
+            __builtin_amdgcn_sched_barrier(0);
+            // Probabilities and O^T += V^T P^T, 16 keys (one B operand) at a time: while the
+            // MFMAs of one quarter run, the exponentials of the next quarter are issued.
+            float mc[R];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-                    for (int x = 0; x < 4; ++x) {
-                        const float p0 = __builtin_amdgcn_exp2f(s[kb][hf * 8 + 2 * x] * c2 - mc);
-                        const float p1 = __builtin_amdgcn_exp2f(s[kb][hf * 8 + 2 * x + 1] * c2 - mc);
-                        pf[kb][hf].u[x] = cvt_pk_bf16(p0, p1);
-                        lsum = row_sum_add(lsum, pf[kb][hf].u[x]);
-                    }
-            // O^T += V^T P^T; the fragments of the second key block are read while the MFMAs of
-            // the first run
+            for (int qb = 0; qb < R; ++qb) mc[qb] = m_run[qb] * c2;
+            Frag pf[4][R];
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
@@ -336,16 +359,37 @@ __global__ __launch_bounds__(THREADS, 512 / THREADS) void attn_mfma_kernel(
                     vf[1][hf][db].u[2] = hi.x; vf[1][hf][db].u[3] = hi.y;
                 }
 #pragma unroll
-            for (int hf = 0; hf < 2; ++hf)
+            for (int qt = 0; qt < 4; ++qt) {
+                const int kb = qt >> 1, hf = qt & 1;
+#pragma unroll
+                for (int qb = 0; qb < R; ++qb)
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        const float p0 = __builtin_amdgcn_exp2f(s[kb][qb][hf * 8 + 2 * x] * c2 - mc[qb]);
+                        const float p1 = __builtin_amdgcn_exp2f(s[kb][qb][hf * 8 + 2 * x + 1] * c2 - mc[qb]);
+                        pf[qt][qb].u[x] = cvt_pk_bf16(p0, p1);
+                        lsum[qb] = row_sum_add(lsum[qb], pf[qt][qb].u[x]);
+                    }
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
-                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[0][hf][db].v, pf[0][hf].v, o[db], 0, 0, 0);
+#pragma unroll
+                    for (int qb = 0; qb < R; ++qb)
+                        o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kb][hf][db].v, pf[qt][qb].v, o[db][qb], 0, 0, 0);
+            }
+            // issue order asked of the scheduler: the first quarter's exponentials, then one MFMA
+            // followed by a share of the next quarter's vector work (and of the LDS reads of the
+            // second key block's fragments), and so on
+            __builtin_amdgcn_sched_group_barrier(0x402, 24 * R, 0);
+#pragma unroll
+            for (int qt = 0; qt < 3; ++qt)
+#pragma unroll
+                for (int i = 0; i < DB * R; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    if (qt == 0 && i < 8) __builtin_amdgcn_sched_group_barrier(0x100, (16 + 7) / 8 <= 2 ? 2 : 2, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x402, 24 / DB, 0);
+                }
+            __builtin_amdgcn_sched_group_barrier(0x008, DB * R, 0);
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-                for (int db = 0; db < DB; ++db)
-                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[1][hf][db].v, pf[1][hf].v, o[db], 0, 0, 0);
         }
         if (has_next) mv.store(Ks[buf ^ 1], Vs[buf ^ 1]);
         __syncthreads();   // tile `cur` is consumed everywhere, tile `nxt` is visible
@@ -353,55 +397,75 @@ __global__ __launch_bounds__(THREADS, 512 / THREADS) void attn_mfma_kernel(
         cur = nxt;
     }
 
-    // normalise and store: this lane owns one query, columns 32*db + 8*(j/4) + 4*half + j%4
-    const float lt = lsum + __shfl_xor(lsum, 32, 64);
-    if (qvalid) {
+    // normalise and store: a lane owns R queries, columns 32*db + 8*(j/4) + 4*half + j%4
+#pragma unroll
+    for (int qb = 0; qb < R; ++qb) {
+        const float lt = lsum[qb] + __shfl_xor(lsum[qb], 32, 64);
+        if (!qvalid[qb]) continue;
         const float inv = 1.f / lt;
-        bf16_t* orow = out + (((size_t)b * Q + qi) * g.Hq + qh) * D;
+        bf16_t* orow = out + (((size_t)b * Q + qi[qb]) * g.Hq + qh[qb]) * D;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int jq = 0; jq < 4; ++jq) {
                 uint2 w;
-                w.x = cvt_pk_bf16(o[db][jq * 4 + 0] * inv, o[db][jq * 4 + 1] * inv);
-                w.y = cvt_pk_bf16(o[db][jq * 4 + 2] * inv, o[db][jq * 4 + 3] * inv);
+                w.x = cvt_pk_bf16(o[db][qb][jq * 4 + 0] * inv, o[db][qb][jq * 4 + 1] * inv);
+                w.y = cvt_pk_bf16(o[db][qb][jq * 4 + 2] * inv, o[db][qb][jq * 4 + 3] * inv);
                 *reinterpret_cast<uint2*>(orow + db * 32 + jq * 8 + half * 4) = w;
             }
-        if (half == 0) lse[((size_t)b * g.Hq + qh) * Q + qi] = m_run * g.scale + logf(lt);
+        if (half == 0) lse[((size_t)b * g.Hq + qh[qb]) * Q + qi[qb]] = m_run[qb] * g.scale + logf(lt);
     }
 }
 
-template <int D, int THREADS>
+template <int D, int WAVES, int R>
 static void attn_launch(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, void* out, hipStream_t s)
 {
-    const int tiles = (g.G * Q + THREADS / 2 - 1) / (THREADS / 2);
-    hipLaunchKernelGGL((attn_mfma_kernel<D, THREADS>), dim3(tiles * g.B * g.Hkv), dim3(THREADS), 0, s, g, sl, Q,
+    constexpr int BM = WAVES * 32 * R;
+    const int tiles = (g.G * Q + BM - 1) / BM;
+    hipLaunchKernelGGL((attn_mfma_kernel<D, WAVES, R>), dim3(tiles * g.B * g.Hkv), dim3(WAVES * 64), 0, s, g, sl, Q,
                        (const bf16_t*)b.Qr, (const bf16_t*)b.Kr, (const bf16_t*)b.Vc, (const bf16_t*)b.Krc,
                        (const bf16_t*)b.Vch, (bf16_t*)out, b.lse);
 }
 
 void launch_attn_mfma(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, int, void* out, hipStream_t s)
 {
-    static const bool small_wg = getenv("CASCADE_KV_ATTN_WG256") != nullptr;   // experiment switch
-    if (g.d == 128) { if (small_wg) attn_launch<128, 256>(g, b, sl, Q, out, s); else attn_launch<128, 512>(g, b, sl, Q, out, s); }
-    else { if (small_wg) attn_launch<64, 256>(g, b, sl, Q, out, s); else attn_launch<64, 512>(g, b, sl, Q, out, s); }
+    // experiment switch: "8x1" (default), "4x1", "4x2" = waves per workgroup x query blocks per wave
+    static const char* shape = getenv("CASCADE_KV_ATTN_SHAPE");
+    const int mode = !shape ? 0 : (shape[0] == '4' && shape[2] == '1' ? 1 : (shape[0] == '4' && shape[2] == '2' ? 2 : 0));
+    if (g.d == 128) {
+        if (mode == 1) attn_launch<128, 4, 1>(g, b, sl, Q, out, s);
+        else if (mode == 2) attn_launch<128, 4, 2>(g, b, sl, Q, out, s);
+        else attn_launch<128, 8, 1>(g, b, sl, Q, out, s);
+    } else {
+        if (mode == 1) attn_launch<64, 4, 1>(g, b, sl, Q, out, s);
+        else if (mode == 2) attn_launch<64, 4, 2>(g, b, sl, Q, out, s);
+        else attn_launch<64, 8, 1>(g, b, sl, Q, out, s);
+    }
 }
 
 // ------------------------------------------------------------------ exact score sums
 
-// Key-stationary: a wave holds 32 keys as the B operand and runs the last `tail` query rows of
-// every head of the group past them (S = Q K^T, one lane owns one key column).  With the stored
-// log-sum-exp the probabilities are exact; each is weighted by its row's EMA coefficient and the
-// column sums are an in-lane sum plus one exchange with lane l^32.
-constexpr int kScoreKeys = 128;   // keys per workgroup (4 waves x 32)
+// Key-stationary: a wave keeps 64 keys (two 32-key blocks) in registers as the B operand and
+// runs the last `tail` query rows of every head of the group past them (S = Q K^T, one lane owns
+// one key column per block).  The rows of one head are staged through LDS in groups of 256 and
+// shared by the four waves.  With the stored log-sum-exp the probabilities are exact:
+// p = 2^(s*c - t[row]) with t = lse*log2(e) - log2(weight of the row), so a row that does not
+// contribute has t = +inf.  Column sums are an in-lane sum plus one exchange with lane l^32;
+// no atomics, so results are identical from run to run.
+constexpr int kScoreThreads = 256;
+constexpr int kScoreKeys = 256;    // keys per workgroup (4 waves x 2 blocks of 32)
+constexpr int kScoreRows = 256;    // query rows staged per pass
 
 template <int D>
-__global__ __launch_bounds__(256) void score_mfma_kernel(
+__global__ __launch_bounds__(kScoreThreads, 2) void score_mfma_kernel(
     Geom g, SegList sl, int Q, int qstride, int tail, float decay, const bf16_t* __restrict__ Qr,
     const bf16_t* __restrict__ Kr, const bf16_t* __restrict__ Krc, const float* __restrict__ lse,
     const float* __restrict__ wrow, float* __restrict__ mu, float* __restrict__ mu_chunk)
 {
     constexpr int KS = D / 16;
+    constexpr int QSTR = D + 8;
+    __shared__ __attribute__((aligned(16))) bf16_t Qs[kScoreRows * QSTR];
+    __shared__ __attribute__((aligned(16))) float ts[kScoreRows];
     const int BH = g.B * g.Hkv;
     const int bh = blockIdx.x % BH;
     int tile = blockIdx.x / BH;
@@ -413,62 +477,101 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(
         tile -= nt;
         ++si;
     }
-    if (si >= sl.n) return;
+    if (si >= sl.n) return;       // uniform for the workgroup
     const Seg sg = sl.s[si];
     const int tid = threadIdx.x, wave = tid >> 6, l = tid & 63, l32 = l & 31, half = l >> 5;
-    const int kk = tile * kScoreKeys + wave * 32 + l32;      // key index inside the segment
-    if (tile * kScoreKeys + wave * 32 >= sg.len) return;      // whole wave past the end
-    const bool kvalid = kk < sg.len;
-    const int kc = min(kk, sg.len - 1);
-    const bf16_t* krow = sg.chunk ? Krc + ((size_t)bh * Q + kc) * D : Kr + ((size_t)bh * g.slots + sg.start + kc) * D;
-    Frag kf[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) kf[ks].u = *reinterpret_cast<const u32x4_t*>(krow + ks * 16 + half * 8);
+    const int wave_k0 = tile * kScoreKeys + wave * 64;       // first key of this wave inside the segment
+    const float c2 = g.scale * 1.4426950408889634f;
 
-    const int i_first = Q - tail;                       // first row that contributes
-    const int n_rb = (tail + 31) / 32;
-    const int i_start = Q - n_rb * 32;                  // may be negative: those rows are skipped
-    // chunk keys are only seen by rows at or after them: skip row blocks entirely before the wave's keys
-    const int wave_k0 = tile * kScoreKeys + wave * 32;
-    float red = 0.f;
+    // this wave's keys as B operands (rows past the end of the segment repeat its last row)
+    Frag kf[2][KS];
+    int kk[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+        kk[kb] = wave_k0 + kb * 32 + l32;
+        const int kc = min(kk[kb], sg.len - 1);
+        const bf16_t* krow = sg.chunk ? Krc + ((size_t)bh * Q + kc) * D : Kr + ((size_t)bh * g.slots + sg.start + kc) * D;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) kf[kb][ks].u = *reinterpret_cast<const u32x4_t*>(krow + ks * 16 + half * 8);
+    }
+
+    const int i_first = Q - tail;                             // first row that contributes
+    const int n_pass = (tail + kScoreRows - 1) / kScoreRows;
+    float red[2] = {0.f, 0.f};
     for (int hh = 0; hh < g.G; ++hh) {
         const int h = hk * g.G + hh;
         const bf16_t* qbase = Qr + (((size_t)sg.qvar * g.B + b) * g.Hq + h) * (size_t)Q * D;
         const float* lrow = lse + ((size_t)b * g.Hq + h) * Q;
-        float colsum = 0.f;
-        for (int rb = 0; rb < n_rb; ++rb) {
-            const int i0 = i_start + rb * 32;
-            if (sg.chunk && i0 + 31 < wave_k0) continue;
-            const int ia = min(max(i0 + l32, 0), Q - 1);
-            const bf16_t* qrow = qbase + (size_t)ia * D + half * 8;
-            f32x16_t s;
+        float colsum[2] = {0.f, 0.f};
+        for (int ps = 0; ps < n_pass; ++ps) {
+            const int i_base = Q - (n_pass - ps) * kScoreRows;          // may be negative in the first pass
+            __syncthreads();                                            // the previous pass has been consumed
+            // stage 256 rows of this head (16-byte pieces) and their exponent offsets
 #pragma unroll
-            for (int j = 0; j < 16; ++j) s[j] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                Frag qf;
-                qf.u = *reinterpret_cast<const u32x4_t*>(qrow + ks * 16);
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf.v, kf[ks].v, s, 0, 0, 0);
+            for (int x = 0; x < kScoreRows * D / 8 / kScoreThreads; ++x) {
+                const int p = tid + x * kScoreThreads;
+                const int r = p / (D / 8), c8 = p % (D / 8);
+                const int i = min(max(i_base + r, 0), Q - 1);
+                *reinterpret_cast<u32x4_t*>(&Qs[r * QSTR + c8 * 8]) =
+                    *reinterpret_cast<const u32x4_t*>(qbase + (size_t)i * D + c8 * 8);
             }
+            {
+                const int i = i_base + tid;                              // kScoreRows == kScoreThreads
+                float t = INFINITY;
+                if (i >= i_first && i >= 0) t = lrow[i] * 1.4426950408889634f - __log2f(wrow[Q - 1 - i]);
+                ts[tid] = t;
+            }
+            __syncthreads();
+            for (int rb = 0; rb < kScoreRows / 32; ++rb) {
+                const int i0 = i_base + rb * 32;
+                if (i0 + 31 < i_first) continue;                         // no row of the block contributes
+                if (sg.chunk && i0 + 31 < wave_k0) continue;             // chunk keys are seen by later rows only
+                f32x16_t s[2];
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const int i = i0 + (j >> 2) * 8 + half * 4 + (j & 3);
-                const bool ok = i >= i_first && i >= 0 && (!sg.chunk || kk <= i);
-                const int ic = min(max(i, 0), Q - 1);
-                const float p = wrow[Q - 1 - ic] * __expf(s[j] * g.scale - lrow[ic]);
-                colsum += ok ? p : 0.f;
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) s[kb][j] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    Frag qf;
+                    qf.u = *reinterpret_cast<const u32x4_t*>(&Qs[(rb * 32 + l32) * QSTR + ks * 16 + half * 8]);
+#pragma unroll
+                    for (int kb = 0; kb < 2; ++kb)
+                        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf.v, kf[kb][ks].v, s[kb], 0, 0, 0);
+                }
+#pragma unroll
+                for (int jq = 0; jq < 4; ++jq) {
+                    const float4 t4 = *reinterpret_cast<const float4*>(&ts[rb * 32 + jq * 8 + half * 4]);
+                    const float tt[4] = {t4.x, t4.y, t4.z, t4.w};
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        const int i = i0 + jq * 8 + half * 4 + x;
+#pragma unroll
+                        for (int kb = 0; kb < 2; ++kb) {
+                            const float p = __builtin_amdgcn_exp2f(s[kb][jq * 4 + x] * c2 - tt[x]);
+                            colsum[kb] += (!sg.chunk || kk[kb] <= i) ? p : 0.f;
+                        }
+                    }
+                }
             }
         }
-        colsum += __shfl_xor(colsum, 32, 64);
-        if (g.head_reduce == CASCADE_REDUCE_MAX) red = hh == 0 ? colsum : fmaxf(red, colsum);
-        else red += colsum;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            const float cs = colsum[kb] + __shfl_xor(colsum[kb], 32, 64);
+            if (g.head_reduce == CASCADE_REDUCE_MAX) red[kb] = hh == 0 ? cs : fmaxf(red[kb], cs);
+            else red[kb] += cs;
+        }
     }
-    if (g.head_reduce == CASCADE_REDUCE_MEAN) red /= (float)g.G;
-    if (half == 0 && kvalid) {
-        if (sg.chunk) mu_chunk[(size_t)bh * qstride + kk] = red;
-        else {
-            float* p = mu + (size_t)bh * g.slots + sg.start + kk;
-            *p = decay * *p + red;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+        float r = red[kb];
+        if (g.head_reduce == CASCADE_REDUCE_MEAN) r /= (float)g.G;
+        if (half == 0 && kk[kb] < sg.len) {
+            if (sg.chunk) mu_chunk[(size_t)bh * qstride + kk[kb]] = r;
+            else {
+                float* p = mu + (size_t)bh * g.slots + sg.start + kk[kb];
+                *p = decay * *p + r;
+            }
         }
     }
 }
@@ -478,7 +581,7 @@ void launch_score_mfma(const Geom& g, const DevBuffers& b, const SegList& sl, in
 {
     int tiles = 0;
     for (int i = 0; i < sl.n; ++i) tiles += (sl.s[i].len + kScoreKeys - 1) / kScoreKeys;
-    const dim3 grid(tiles * g.B * g.Hkv), block(256);
+    const dim3 grid(tiles * g.B * g.Hkv), block(kScoreThreads);
     if (g.d == 128)
         hipLaunchKernelGGL(score_mfma_kernel<128>, grid, block, 0, s, g, sl, Q, max_chunk, tail_rows, decay,
                            (const bf16_t*)b.Qr, (const bf16_t*)b.Kr, (const bf16_t*)b.Krc, b.lse, b.wrow, b.mu, b.mu_chunk);

@@ -121,14 +121,105 @@ void launch_load_state(const Geom& g, int dtype, const DevBuffers& b, const void
 // ------------------------------------------------------------------ per-chunk rotation
 
 // For every rotated query copy v: Qr[v][b][h][i] = R(qrot0[v] + i) q[b][i][h]; chunk keys are
-// rotated to their chunk index, chunk values are copied head-major.  One thread per rotary pair.
+// rotated to their chunk index, chunk values are copied head-major.  A thread takes 8 rotary
+// pairs of one row (two 16-byte pieces for bf16) and, for a query row, produces all copies.
+template <typename T> struct Vec8;
+template <> struct Vec8<bf16_t> {
+    __device__ static void load(const bf16_t* p, float* o)
+    {
+        const uint4 u = *reinterpret_cast<const uint4*>(p);
+        const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { o[2 * i] = __uint_as_float(w[i] << 16); o[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u); }
+    }
+    __device__ static void store(bf16_t* p, const float* v)
+    {
+        uint4 u;
+        u.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+        u.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+        u.z = (uint32_t)f32_to_bf16(v[4]) | ((uint32_t)f32_to_bf16(v[5]) << 16);
+        u.w = (uint32_t)f32_to_bf16(v[6]) | ((uint32_t)f32_to_bf16(v[7]) << 16);
+        *reinterpret_cast<uint4*>(p) = u;
+    }
+};
+template <> struct Vec8<float> {
+    __device__ static void load(const float* p, float* o)
+    {
+        const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+        o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+    }
+    __device__ static void store(float* p, const float* v)
+    {
+        *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+        *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    }
+};
+
+template <typename T>
+__device__ inline void rotate8(const float* x0, const float* x1, const float2* __restrict__ cs, T* d0, T* d1)
+{
+    float y0[8], y1[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const float2 c = cs[i];
+        y0[i] = x0[i] * c.x - x1[i] * c.y;
+        y1[i] = x1[i] * c.x + x0[i] * c.y;
+    }
+    Vec8<T>::store(d0, y0);
+    Vec8<T>::store(d1, y1);
+}
+
 template <typename T>
 __global__ void prep_kernel(Geom g, SegList sl, int Q, const float2* __restrict__ rope,
                             const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
                             T* __restrict__ Qr, T* __restrict__ Krc, T* __restrict__ Vch)
 {
+    const int half = g.d / 2, groups = half / 8;
+    const int rows_per_tok = g.Hq + 2 * g.Hkv;          // per (b, i): query heads, K heads, V heads
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long total = (long)g.B * Q * rows_per_tok * groups;
+    if (idx >= total) return;
+    const int e = (int)(idx % groups) * 8;
+    long r = idx / groups;
+    const int row = (int)(r % rows_per_tok);
+    r /= rows_per_tok;
+    const int i = (int)(r % Q), b = (int)(r / Q);
+    float x0[8], x1[8];
+    if (row < g.Hq) {
+        const int h = row;
+        const size_t src = (((size_t)b * Q + i) * g.Hq + h) * g.d;
+        Vec8<T>::load(q + src + e, x0);
+        Vec8<T>::load(q + src + e + half, x1);
+        for (int vq = 0; vq < sl.n_qvar; ++vq) {
+            const size_t dst = ((((size_t)vq * g.B + b) * g.Hq + h) * Q + i) * g.d;
+            rotate8<T>(x0, x1, rope + (size_t)(sl.qrot0[vq] + i) * half + e, Qr + dst + e, Qr + dst + e + half);
+        }
+    } else {
+        const int rr = row - g.Hq;
+        const int h = rr % g.Hkv;
+        const size_t src = (((size_t)b * Q + i) * g.Hkv + h) * g.d;
+        const size_t dst = (((size_t)b * g.Hkv + h) * Q + i) * g.d;
+        if (rr < g.Hkv) {
+            Vec8<T>::load(k + src + e, x0);
+            Vec8<T>::load(k + src + e + half, x1);
+            rotate8<T>(x0, x1, rope + (size_t)i * half + e, Krc + dst + e, Krc + dst + e + half);
+        } else {
+            Vec8<T>::load(v + src + e, x0);
+            Vec8<T>::load(v + src + e + half, x1);
+            Vec8<T>::store(Vch + dst + e, x0);
+            Vec8<T>::store(Vch + dst + e + half, x1);
+        }
+    }
+}
+
+// head dimensions that are not a multiple of 16: one thread per rotary pair
+template <typename T>
+__global__ void prep_pair_kernel(Geom g, SegList sl, int Q, const float2* __restrict__ rope,
+                                 const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
+                                 T* __restrict__ Qr, T* __restrict__ Krc, T* __restrict__ Vch)
+{
     const int half = g.d / 2;
-    const int rows_per_tok = sl.n_qvar * g.Hq + 2 * g.Hkv;   // per (b, i): query copies, K, V
+    const int rows_per_tok = sl.n_qvar * g.Hq + 2 * g.Hkv;
     const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
     const long total = (long)g.B * Q * rows_per_tok * half;
     if (idx >= total) return;
@@ -165,14 +256,26 @@ __global__ void prep_kernel(Geom g, SegList sl, int Q, const float2* __restrict_
 void launch_prep(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int Q,
                  const void* q, const void* k, const void* v, hipStream_t s)
 {
+    const dim3 block(256);
+    if (g.d % 16 == 0) {
+        const long n = (long)g.B * Q * (g.Hq + 2 * g.Hkv) * (g.d / 16);
+        const dim3 grid((unsigned)((n + 255) / 256));
+        if (dtype == CASCADE_F32)
+            hipLaunchKernelGGL(prep_kernel<float>, grid, block, 0, s, g, sl, Q, b.rope, (const float*)q, (const float*)k,
+                               (const float*)v, (float*)b.Qr, (float*)b.Krc, (float*)b.Vch);
+        else
+            hipLaunchKernelGGL(prep_kernel<bf16_t>, grid, block, 0, s, g, sl, Q, b.rope, (const bf16_t*)q, (const bf16_t*)k,
+                               (const bf16_t*)v, (bf16_t*)b.Qr, (bf16_t*)b.Krc, (bf16_t*)b.Vch);
+        return;
+    }
     const long n = (long)g.B * Q * (sl.n_qvar * g.Hq + 2 * g.Hkv) * (g.d / 2);
-    const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+    const dim3 grid((unsigned)((n + 255) / 256));
     if (dtype == CASCADE_F32)
-        hipLaunchKernelGGL(prep_kernel<float>, grid, block, 0, s, g, sl, Q, b.rope, (const float*)q, (const float*)k,
+        hipLaunchKernelGGL(prep_pair_kernel<float>, grid, block, 0, s, g, sl, Q, b.rope, (const float*)q, (const float*)k,
                            (const float*)v, (float*)b.Qr, (float*)b.Krc, (float*)b.Vch);
     else
-        hipLaunchKernelGGL(prep_kernel<bf16_t>, grid, block, 0, s, g, sl, Q, b.rope, (const bf16_t*)q, (const bf16_t*)k,
-                           (const bf16_t*)v, (bf16_t*)b.Qr, (bf16_t*)b.Krc, (bf16_t*)b.Vch);
+        hipLaunchKernelGGL(prep_pair_kernel<bf16_t>, grid, block, 0, s, g, sl, Q, b.rope, (const bf16_t*)q,
+                           (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)b.Qr, (bf16_t*)b.Krc, (bf16_t*)b.Vch);
 }
 
 // ------------------------------------------------------------------ cascade update: who ends up where
