@@ -54,7 +54,7 @@ def prefill_bench(args, torch, B, wl):
     res = {
         "tokens_per_s": tokens / seconds, "ms_per_step": seconds * 1e3 / K,
         "kernel_ms_per_step": {k: v[0] / max(v[1], 1) for k, v in prof.items() if v[1]},
-        "roofline": {"bound": "mfma", "kernel": "attn_mfma_kernel", "achieved": achieved / 1e12,
+        "roofline": {"bound": "mfma", "kernel": "attn_stream_kernel", "achieved": achieved / 1e12,
                      "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK,
                      "traffic": None, "flop_per_launch": sum(flops) / K, "avg_launch_ms": avg_s * 1e3},
         "end_to_end_mfma_frac": (sum(flops) / seconds) / MFMA_BF16_PEAK,

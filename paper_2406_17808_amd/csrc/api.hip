@@ -151,6 +151,11 @@ static size_t carve(const cascade_config* c, const Geom& g, char* base, DevBuffe
     b.Qr = take((size_t)n_qvar_max * BHq * mc * g.d * elem);
     b.Krc = take(BH * mc * g.d * elem);
     b.Vch = take(BH * mc * g.d * elem);
+    // every segment list has at most kMaxSegments segments, each ending in one partly filled tile
+    const bool mfma = c->dtype == CASCADE_BF16 && (g.d == 64 || g.d == 128);
+    const int vt_tiles = mfma ? (g.slots + (int)mc) / 64 + kMaxSegments : 0;
+    b.Kt = take(BH * (size_t)vt_tiles * 64 * g.d * elem);
+    b.Vt = take(BH * (size_t)vt_tiles * 64 * g.d * elem);
     b.lse = (float*)take(BHq * mc * 4);
     b.mu_chunk = (float*)take(BH * mc * 4);
     b.offers = (int32_t*)take(BH * 2 * mc * 4);
@@ -160,6 +165,7 @@ static size_t carve(const cascade_config* c, const Geom& g, char* base, DevBuffe
     b.opart = (float*)take(BHq * splits * g.d * 4);
     b.rope_rows = rope_rows;
     b.dec_splits = splits;
+    b.vt_tiles = vt_tiles;
     if (out) *out = b;
     return off;
 }
@@ -336,10 +342,12 @@ extern "C" int cascade_prefill_chunk(cascade_ctx* ctx, const void* dev_q, const 
     {
         Timed t(ctx, CASCADE_K_PREP, s);
         launch_prep(g, ctx->dtype, ctx->buf, sl, Q, dev_q, dev_k, dev_v, s);
+        if (ctx->mfma && !launch_kv_pack(g, ctx->buf, sl, Q, s))
+            return fail(ctx, CASCADE_E_WORKSPACE_TOO_SMALL, "cascade_prefill_chunk: packed K/V buffers too small for this segment list");
     }
     {
         Timed t(ctx, CASCADE_K_ATTENTION, s);
-        if (ctx->mfma) launch_attn_mfma(g, ctx->buf, sl, Q, ctx->max_chunk, dev_out, s);
+        if (ctx->mfma) launch_attn_stream(g, ctx->buf, sl, Q, dev_out, s);
         else launch_attn_simple(g, ctx->dtype, ctx->buf, sl, Q, ctx->max_chunk, dev_out, s);
     }
     const int tail = Q < ctx->tail_k ? Q : ctx->tail_k;

@@ -22,6 +22,8 @@ struct DevBuffers {
     void* Qr;        // [n_qvar_max, B, Hq, max_chunk, d] rotated query copies
     void* Krc;       // [B,Hkv,max_chunk,d] chunk keys rotated to their chunk index
     void* Vch;       // [B,Hkv,max_chunk,d] chunk values, head-major
+    void* Kt;        // [B,Hkv,vt_tiles,64,d] bf16 MFMA path: rotated keys of cache and chunk, tile by tile
+    void* Vt;        // [B,Hkv,vt_tiles,d,64] the same for V, every tile transposed
     float* lse;      // [B,Hq,max_chunk] log-sum-exp of every query row (natural log, scaled logits)
     float* mu_chunk; // [B,Hkv,max_chunk] scores of the chunk's tokens
     int32_t* offers; // [B,Hkv,2,max_chunk]
@@ -32,6 +34,7 @@ struct DevBuffers {
     float* opart;    // [B,Hq,dec_splits,d]
     int rope_rows;
     int dec_splits;
+    int vt_tiles;    // capacity of Kt and Vt per (batch, KV head)
 };
 
 // tables
@@ -54,9 +57,11 @@ void launch_attn_simple(const Geom& g, int dtype, const DevBuffers& b, const Seg
 void launch_score_simple(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int Q,
                          int max_chunk, int tail_rows, float decay, hipStream_t s);
 
-// attention, bf16 MFMA (head_dim 64 or 128)
-void launch_attn_mfma(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, int max_chunk,
-                      void* out, hipStream_t s);
+// attention, bf16 MFMA (head_dim 64 or 128).  launch_kv_pack copies the keys and values of the
+// segment list into Kt / Vt, tile by tile (false if they do not hold that many tiles);
+// launch_attn_stream reads only those copies.
+bool launch_kv_pack(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, hipStream_t s);
+void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, void* out, hipStream_t s);
 void launch_score_mfma(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, int max_chunk,
                        int tail_rows, float decay, hipStream_t s);
 
