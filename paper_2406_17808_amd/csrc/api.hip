@@ -341,7 +341,9 @@ extern "C" int cascade_prefill_chunk(cascade_ctx* ctx, const void* dev_q, const 
     build_segments(g, ctx->st, true, Q, sl);
     {
         Timed t(ctx, CASCADE_K_PREP, s);
-        launch_prep(g, ctx->dtype, ctx->buf, sl, Q, dev_q, dev_k, dev_v, s);
+        // the MFMA kernels take logits directly as base-2 exponents
+        const float qscale = ctx->mfma ? g.scale * 1.4426950408889634f : 1.f;
+        launch_prep(g, ctx->dtype, ctx->buf, sl, Q, qscale, dev_q, dev_k, dev_v, s);
         if (ctx->mfma && !launch_kv_pack(g, ctx->buf, sl, Q, s))
             return fail(ctx, CASCADE_E_WORKSPACE_TOO_SMALL, "cascade_prefill_chunk: packed K/V buffers too small for this segment list");
     }

@@ -165,9 +165,13 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int j = 0; j < 16; ++j) o[db][j] = 0.f;
-    const float c2 = g.scale * 1.4426950408889634f;   // logits to base-2 exponents
-    float m_run = -INFINITY;                           // maximum the exponents are taken against
-    float lsum = 0.f;                                  // this lane's part of the row sum
+    // The queries carry the softmax scale and log2(e): S^T holds base-2 exponents.  m_run is the
+    // maximum the exponents are taken against; the accumulators of S^T start at -m_run (negm, all
+    // sixteen registers the same value: a lane owns one query), so S^T comes out of the MFMAs
+    // already relative to it.
+    float m_run = 0.f;
+    f32x16_t negm;
+    float lsum = 0.f;   // this lane's part of the row sum
 
     // The packed tiles are LDS images: every wave copies PW consecutive KB of each
     const uint32_t lds_k = lds_address(Ks) + (uint32_t)wave * PW * 1024u;
@@ -229,19 +233,19 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
             }
     };
     // The vector block of one tile: mask the keys a query may not see (past the end of the
-    // segment; later chunk tokens), take the row maximum, raise the running maximum only when it
-    // grew by more than 2^kRescaleLog2 (the probabilities then stay below that factor, and most
-    // tiles skip the rescaling of O), and turn S into probabilities.
-    auto softmax_tile = [&](const TileIter& it) {
+    // segment; later chunk tokens), take the row maximum of S^T (relative to m_run), raise m_run only
+    // when that exceeds kRescaleLog2 (the probabilities then stay below 2^kRescaleLog2, and most
+    // tiles skip the rescaling of O), and turn S^T into probabilities.  FIRST: S^T is absolute
+    // and m_run not set yet (the first tile of a workgroup).
+    auto softmax_tile = [&](const TileIter& it, bool first) {
         if ((it.t0 + kBN > it.sg.len) || (it.sg.chunk && it.t0 + kBN - 1 > wave_imin)) {
             const int lim = it.sg.chunk ? min(it.sg.len - 1, qi) : it.sg.len - 1;   // last visible key
+            const int rel = lim - it.t0 - half * 4;   // accumulator j of block kb is key t0 + 4*half + (32 kb + 8 (j/4) + j%4)
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const int kk = it.t0 + kb * 32 + (j >> 2) * 8 + half * 4 + (j & 3);
-                    if (kk > lim) s[kb][j] = -INFINITY;
-                }
+                for (int j = 0; j < 16; ++j)
+                    if (kb * 32 + (j >> 2) * 8 + (j & 3) > rel) s[kb][j] = -INFINITY;
         }
         float x = -INFINITY;
 #pragma unroll
@@ -249,25 +253,30 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
 #pragma unroll
             for (int j = 0; j < 16; ++j) x = fmaxf(x, s[kb][j]);
         const float mt = max_xor32(x);
-        const bool grow = (mt - m_run) * c2 > kRescaleLog2;
+        const bool grow = first || mt > kRescaleLog2;
         if (__any(grow)) {
-            const float mn = grow ? mt : m_run;
-            const float alpha = __builtin_amdgcn_exp2f((m_run - mn) * c2);   // 0 on the first tile
-            m_run = mn;
+            const float delta = grow ? mt : 0.f;   // every row sees a key of the first tile: finite there
+            const float alpha = first ? 1.f : __builtin_amdgcn_exp2f(-delta);   // O and the row sum are still zero on the first tile
+            m_run += delta;
             lsum *= alpha;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int j = 0; j < 16; ++j) o[db][j] *= alpha;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) s[kb][j] -= delta;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) negm[j] = -m_run;
         }
-        const float mc = m_run * c2;
 #pragma unroll
         for (int qt = 0; qt < 4; ++qt) {
             const int kb = qt >> 1, hf = qt & 1;
 #pragma unroll
             for (int x2 = 0; x2 < 4; ++x2) {
-                const float p0 = __builtin_amdgcn_exp2f(s[kb][hf * 8 + 2 * x2] * c2 - mc);
-                const float p1 = __builtin_amdgcn_exp2f(s[kb][hf * 8 + 2 * x2 + 1] * c2 - mc);
+                const float p0 = __builtin_amdgcn_exp2f(s[kb][hf * 8 + 2 * x2]);
+                const float p1 = __builtin_amdgcn_exp2f(s[kb][hf * 8 + 2 * x2 + 1]);
                 pf[qt].u[x2] = cvt_pk_bf16(p0, p1);
                 lsum += p0 + p1;   // plain adds: the dot-product instructions queue behind the MFMAs of the SIMD
             }
@@ -284,9 +293,9 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     if (!it1.valid(sl)) return;          // cannot happen: the chunk itself is always a segment
 
     // Copies.  Batch t is K of tile t+4 and V of tile t+3, each into the stage of the tile four
-    // before it.  A wave issues its share of batch t inside its matrix block t (those tiles were
-    // last read in matrix block t-1, which both groups left before this block began) and, before
-    // the barrier that ends its iteration t, waits until only that batch is still in flight: its
+    // before it.  A wave issues its share of batch t at the start of its vector block t (those
+    // tiles were last read in matrix block t-1, which both groups left before) and, before the
+    // barrier that ends its iteration t, waits until only that batch is still in flight: its
     // share of batch t-1 has landed then.  The early group passes that barrier as 2t+2, the late
     // group as 2t+3, and the first read of batch t-1 (V of tile t+2, read ahead by the early
     // group) comes after barrier 2t+3.
@@ -327,7 +336,7 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     wait_vm<0>();
     __syncthreads();
     qk_tile(Ks);
-    softmax_tile(it1);    // every wave sees the first tile
+    softmax_tile(it1, true);    // every wave sees the first tile
     it1.next(sl, wg_imax);
     __syncthreads();      // barrier 0: every wave has read K of tile 0, its buffer may be refilled
 #pragma unroll
@@ -346,23 +355,16 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
         // ---- matrix block.  A wave that does not see tile t holds zero probabilities; S^T of a
         // tile this wave does not see (or that does not exist: stale buffer) is computed and
         // dropped.  The order of MFMAs and reads is pinned step by step.
-        int in_flight = 0;
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_setprio(1);
         {
             const bf16_t* Vtile = Vs + (n0 & 3) * TILE;
             const bf16_t* Ktile = Ks + ((n0 + 1) & 3) * TILE;
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) s[kb][j] = 0.f;
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
             for (int i = 0; i < NF; ++i) {
                 if (i < NV) o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kAhead].v, pf[i / DB].v, o[i % DB], 0, 0, 0);
-                else s[(i - NV) % 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kAhead].v, qf[(i - NV) / 2].v, s[(i - NV) % 2], 0, 0, 0);
+                else s[(i - NV) % 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kAhead].v, qf[(i - NV) / 2].v, i - NV < 2 ? negm : s[(i - NV) % 2], 0, 0, 0);
                 if (i + kAhead < NF) fr[i % kAhead] = read_frag(Vtile, Ktile, i + kAhead);
-                if (i == 2) in_flight = issue(n0);   // in the shadow of the MFMAs
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -373,9 +375,10 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
         // the first fragments of the next matrix block: V of tile t+1
 #pragma unroll
         for (int i = 0; i < kAhead; ++i) fr[i] = read_frag(Vs + ((n0 + 1) & 3) * TILE, Ks, i);
+        const int in_flight = issue(n0);   // here: a copy instruction can hold a wave up, and this block has time to spare
         // ---- vector block
         if (act_next) {
-            softmax_tile(it1);
+            softmax_tile(it1, false);
         } else {
 #pragma unroll
             for (int qt = 0; qt < 4; ++qt)
@@ -402,7 +405,7 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
                 w.y = cvt_pk_bf16(o[db][jq * 4 + 2] * inv, o[db][jq * 4 + 3] * inv);
                 *reinterpret_cast<uint2*>(orow + db * 32 + jq * 8 + half * 4) = w;
             }
-        if (half == 0) lse[((size_t)b * g.Hq + qh) * Q + qi] = m_run * g.scale + logf(lt);
+        if (half == 0) lse[((size_t)b * g.Hq + qh) * Q + qi] = m_run * 0.6931471805599453f + logf(lt);
     }
 }
 

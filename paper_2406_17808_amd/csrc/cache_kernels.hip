@@ -120,8 +120,9 @@ void launch_load_state(const Geom& g, int dtype, const DevBuffers& b, const void
 
 // ------------------------------------------------------------------ per-chunk rotation
 
-// For every rotated query copy v: Qr[v][b][h][i] = R(qrot0[v] + i) q[b][i][h]; chunk keys are
-// rotated to their chunk index, chunk values are copied head-major.  A thread takes 8 rotary
+// For every rotated query copy v: Qr[v][b][h][i] = qscale * R(qrot0[v] + i) q[b][i][h] (the bf16
+// MFMA kernels want the softmax scale and log2(e) folded into the queries; everybody else passes
+// 1); chunk keys are rotated to their chunk index, chunk values are copied head-major.  A thread takes 8 rotary
 // pairs of one row (two 16-byte pieces for bf16) and, for a query row, produces all copies.
 template <typename T> struct Vec8;
 template <> struct Vec8<bf16_t> {
@@ -170,7 +171,7 @@ __device__ inline void rotate8(const float* x0, const float* x1, const float2* _
 }
 
 template <typename T>
-__global__ void prep_kernel(Geom g, SegList sl, int Q, const float2* __restrict__ rope,
+__global__ void prep_kernel(Geom g, SegList sl, int Q, float qscale, const float2* __restrict__ rope,
                             const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
                             T* __restrict__ Qr, T* __restrict__ Krc, T* __restrict__ Vch)
 {
@@ -190,6 +191,8 @@ __global__ void prep_kernel(Geom g, SegList sl, int Q, const float2* __restrict_
         const size_t src = (((size_t)b * Q + i) * g.Hq + h) * g.d;
         Vec8<T>::load(q + src + e, x0);
         Vec8<T>::load(q + src + e + half, x1);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { x0[j] *= qscale; x1[j] *= qscale; }
         for (int vq = 0; vq < sl.n_qvar; ++vq) {
             const size_t dst = ((((size_t)vq * g.B + b) * g.Hq + h) * Q + i) * g.d;
             rotate8<T>(x0, x1, rope + (size_t)(sl.qrot0[vq] + i) * half + e, Qr + dst + e, Qr + dst + e + half);
@@ -214,7 +217,7 @@ __global__ void prep_kernel(Geom g, SegList sl, int Q, const float2* __restrict_
 
 // head dimensions that are not a multiple of 16: one thread per rotary pair
 template <typename T>
-__global__ void prep_pair_kernel(Geom g, SegList sl, int Q, const float2* __restrict__ rope,
+__global__ void prep_pair_kernel(Geom g, SegList sl, int Q, float qscale, const float2* __restrict__ rope,
                                  const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
                                  T* __restrict__ Qr, T* __restrict__ Krc, T* __restrict__ Vch)
 {
@@ -232,7 +235,7 @@ __global__ void prep_pair_kernel(Geom g, SegList sl, int Q, const float2* __rest
         const int vq = row / g.Hq, h = row % g.Hq;
         const size_t src = (((size_t)b * Q + i) * g.Hq + h) * g.d;
         const size_t dst = ((((size_t)vq * g.B + b) * g.Hq + h) * Q + i) * g.d;
-        const float x0 = Elem<T>::load(q + src + e), x1 = Elem<T>::load(q + src + e + half);
+        const float x0 = qscale * Elem<T>::load(q + src + e), x1 = qscale * Elem<T>::load(q + src + e + half);
         const float2 cs = rope[(size_t)(sl.qrot0[vq] + i) * half + e];
         Elem<T>::store(Qr + dst + e, x0 * cs.x - x1 * cs.y);
         Elem<T>::store(Qr + dst + e + half, x1 * cs.x + x0 * cs.y);
@@ -253,7 +256,7 @@ __global__ void prep_pair_kernel(Geom g, SegList sl, int Q, const float2* __rest
     }
 }
 
-void launch_prep(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int Q,
+void launch_prep(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int Q, float qscale,
                  const void* q, const void* k, const void* v, hipStream_t s)
 {
     const dim3 block(256);
@@ -261,20 +264,20 @@ void launch_prep(const Geom& g, int dtype, const DevBuffers& b, const SegList& s
         const long n = (long)g.B * Q * (g.Hq + 2 * g.Hkv) * (g.d / 16);
         const dim3 grid((unsigned)((n + 255) / 256));
         if (dtype == CASCADE_F32)
-            hipLaunchKernelGGL(prep_kernel<float>, grid, block, 0, s, g, sl, Q, b.rope, (const float*)q, (const float*)k,
+            hipLaunchKernelGGL(prep_kernel<float>, grid, block, 0, s, g, sl, Q, qscale, b.rope, (const float*)q, (const float*)k,
                                (const float*)v, (float*)b.Qr, (float*)b.Krc, (float*)b.Vch);
         else
-            hipLaunchKernelGGL(prep_kernel<bf16_t>, grid, block, 0, s, g, sl, Q, b.rope, (const bf16_t*)q, (const bf16_t*)k,
+            hipLaunchKernelGGL(prep_kernel<bf16_t>, grid, block, 0, s, g, sl, Q, qscale, b.rope, (const bf16_t*)q, (const bf16_t*)k,
                                (const bf16_t*)v, (bf16_t*)b.Qr, (bf16_t*)b.Krc, (bf16_t*)b.Vch);
         return;
     }
     const long n = (long)g.B * Q * (sl.n_qvar * g.Hq + 2 * g.Hkv) * (g.d / 2);
     const dim3 grid((unsigned)((n + 255) / 256));
     if (dtype == CASCADE_F32)
-        hipLaunchKernelGGL(prep_pair_kernel<float>, grid, block, 0, s, g, sl, Q, b.rope, (const float*)q, (const float*)k,
+        hipLaunchKernelGGL(prep_pair_kernel<float>, grid, block, 0, s, g, sl, Q, qscale, b.rope, (const float*)q, (const float*)k,
                            (const float*)v, (float*)b.Qr, (float*)b.Krc, (float*)b.Vch);
     else
-        hipLaunchKernelGGL(prep_pair_kernel<bf16_t>, grid, block, 0, s, g, sl, Q, b.rope, (const bf16_t*)q,
+        hipLaunchKernelGGL(prep_pair_kernel<bf16_t>, grid, block, 0, s, g, sl, Q, qscale, b.rope, (const bf16_t*)q,
                            (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)b.Qr, (bf16_t*)b.Krc, (bf16_t*)b.Vch);
 }
 

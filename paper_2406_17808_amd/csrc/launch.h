@@ -19,7 +19,7 @@ struct DevBuffers {
     float2* rope;    // [rope_rows, d/2] (cos, sin) of index * theta_i
     float* wrow;     // [max_chunk] beta^k (1 - beta): EMA weight of the row that has k rows after it
     // per-call scratch
-    void* Qr;        // [n_qvar_max, B, Hq, max_chunk, d] rotated query copies
+    void* Qr;        // [n_qvar_max, B, Hq, max_chunk, d] rotated query copies (bf16 MFMA path: times scale * log2 e)
     void* Krc;       // [B,Hkv,max_chunk,d] chunk keys rotated to their chunk index
     void* Vch;       // [B,Hkv,max_chunk,d] chunk values, head-major
     void* Kt;        // [B,Hkv,vt_tiles,64,d] bf16 MFMA path: rotated keys of cache and chunk, tile by tile
@@ -45,7 +45,7 @@ void launch_wrow_table(float beta, float* wrow, int n, hipStream_t s);
 void launch_fill_i32(int32_t* p, size_t n, int32_t value, hipStream_t s);
 void launch_load_state(const Geom& g, int dtype, const DevBuffers& b, const void* k, const void* v,
                        const float* mu, const int32_t* ids, const int* counts, int total, hipStream_t s);
-void launch_prep(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int Q,
+void launch_prep(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int Q, float qscale,
                  const void* q, const void* k, const void* v, hipStream_t s);
 void launch_plan(const Geom& g, const DevBuffers& b, const UpdatePlan& pl, int max_chunk, hipStream_t s);
 void launch_moves(const Geom& g, int dtype, const DevBuffers& b, const UpdatePlan& pl, int max_chunk,

@@ -16,7 +16,8 @@ namespace ckv {
 // runs the last `tail` query rows of every head of the group past them (S = Q K^T, one lane owns
 // one key column per block).  The rows of one head are staged through LDS in groups of 256 and
 // shared by the four waves.  With the stored log-sum-exp the probabilities are exact:
-// p = 2^(s*c - t[row]) with t = lse*log2(e) - log2(weight of the row), so a row that does not
+// p = 2^(s - t[row]) (the queries carry the softmax scale and log2 e) with
+// t = lse*log2(e) - log2(weight of the row), so a row that does not
 // contribute has t = +inf.  Column sums are an in-lane sum plus one exchange with lane l^32;
 // no atomics, so results are identical from run to run.
 constexpr int kScoreThreads = 256;
@@ -48,7 +49,6 @@ __global__ __launch_bounds__(kScoreThreads, 2) void score_mfma_kernel(
     const Seg sg = sl.s[si];
     const int tid = threadIdx.x, wave = tid >> 6, l = tid & 63, l32 = l & 31, half = l >> 5;
     const int wave_k0 = tile * kScoreKeys + wave * 64;       // first key of this wave inside the segment
-    const float c2 = g.scale * 1.4426950408889634f;
 
     // this wave's keys as B operands (rows past the end of the segment repeat its last row)
     Frag kf[2][KS];
@@ -115,7 +115,7 @@ __global__ __launch_bounds__(kScoreThreads, 2) void score_mfma_kernel(
                         const int i = i0 + jq * 8 + half * 4 + x;
 #pragma unroll
                         for (int kb = 0; kb < 2; ++kb) {
-                            const float p = __builtin_amdgcn_exp2f(s[kb][jq * 4 + x] * c2 - tt[x]);
+                            const float p = __builtin_amdgcn_exp2f(s[kb][jq * 4 + x] - tt[x]);
                             colsum[kb] += (!sg.chunk || kk[kb] <= i) ? p : 0.f;
                         }
                     }
