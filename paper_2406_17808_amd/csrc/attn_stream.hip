@@ -139,7 +139,8 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     __shared__ __attribute__((aligned(1024))) bf16_t Vs[kSStages * TILE];
 
     const int BH = g.B * g.Hkv;
-    const int bh = blockIdx.x % BH, tile = blockIdx.x / BH;   // consecutive workgroups: different KV heads
+    // consecutive workgroups: different KV heads; row blocks that see more of the chunk (longer loops) start first
+    const int bh = blockIdx.x % BH, tile = (int)(gridDim.x / BH) - 1 - (int)(blockIdx.x / BH);
     const int b = bh / g.Hkv, hk = bh % g.Hkv;
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, l32 = l & 31, half = l >> 5;
     const int GQ = g.G * Q;
@@ -356,7 +357,6 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
         // tile this wave does not see (or that does not exist: stale buffer) is computed and
         // dropped.  The order of MFMAs and reads is pinned step by step.
         __builtin_amdgcn_sched_barrier(0);
-        __builtin_amdgcn_s_setprio(1);
         {
             const bf16_t* Vtile = Vs + (n0 & 3) * TILE;
             const bf16_t* Ktile = Ks + ((n0 + 1) & 3) * TILE;
@@ -368,7 +368,6 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        __builtin_amdgcn_s_setprio(0);
         __builtin_amdgcn_sched_barrier(0);
         if (!has_next) break;
         wg_barrier();     // barrier 2t+1 (early group), 2t+2 (late group)
