@@ -21,6 +21,28 @@ MFMA_BF16_PEAK = 2.5e15     # dense bf16 MFMA FLOP/s of one MI355X
 HBM_PEAK = 8.0e12           # bytes/s
 
 
+def stored_traffic(name):
+    """HBM bytes per launch of a kernel as measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE,
+    scaled by a copy of known size); the figures live with the profile summaries, or None."""
+    path = os.path.join(ROOT, "profiles", name)
+    try:
+        with open(path) as f:
+            return json.load(f).get("hbm_bytes_per_launch")
+    except (OSError, ValueError):
+        return None
+
+
+def calibration_copy(torch, mib):
+    """A plain device-to-device copy of known size, for scaling the HBM counters of a profiler run."""
+    n = mib << 20
+    a = torch.full((n,), 1, dtype=torch.uint8, device="cuda:0")
+    b = torch.empty_like(a)
+    for _ in range(3):
+        b.copy_(a)
+    torch.cuda.synchronize()
+    del a, b
+
+
 def prefill_bench(args, torch, B, wl):
     from paper_2406_17808_amd.cache import CascadeKVCache, config_of
     from paper_2406_17808_amd.workloads import chunk_inputs_torch
@@ -56,7 +78,8 @@ def prefill_bench(args, torch, B, wl):
         "kernel_ms_per_step": {k: v[0] / max(v[1], 1) for k, v in prof.items() if v[1]},
         "roofline": {"bound": "mfma", "kernel": "attn_stream_kernel", "achieved": achieved / 1e12,
                      "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK,
-                     "traffic": None, "flop_per_launch": sum(flops) / K, "avg_launch_ms": avg_s * 1e3},
+                     "traffic": stored_traffic("attn_stream_kernel_prefill_1m_hbm_traffic.json") if wl.name == "prefill_1m" else None,
+                     "flop_per_launch": sum(flops) / K, "avg_launch_ms": avg_s * 1e3},
         "end_to_end_mfma_frac": (sum(flops) / seconds) / MFMA_BF16_PEAK,
     }
     return res, cache, chunks, cfg
@@ -138,7 +161,8 @@ def decode_bench(args, torch, B):
         "decode_kernel_us": {k: v[0] / max(v[1], 1) * 1e3 for k, v in prof.items() if v[1]},
         "roofline_decode": {"bound": "hbm", "kernel": "decode_qk_kernel", "achieved": k_bytes / (qk_ms / 1e3 / max(qk_n, 1)) / 1e9,
                             "peak": HBM_PEAK / 1e9, "unit": "GB/s",
-                            "frac": k_bytes / (qk_ms / 1e3 / max(qk_n, 1)) / HBM_PEAK, "traffic": None},
+                            "frac": k_bytes / (qk_ms / 1e3 / max(qk_n, 1)) / HBM_PEAK,
+                            "traffic": stored_traffic("decode_qk_kernel_decode_b32_hbm_traffic.json")},
     }
     cache.close()
     return res
@@ -156,6 +180,8 @@ def main():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--decode-warmup", type=int, default=16)
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="profiler runs: also do a plain device copy of this size (scales the HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path runs on ONE GPU (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
@@ -166,6 +192,8 @@ def main():
     B.load_library()   # fails loudly if the HIP library has not been built
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     wl = WORKLOADS[args.workload]
+    if args.copy_calibration_mib:
+        calibration_copy(torch, args.copy_calibration_mib)
     res, cache, chunks, cfg = prefill_bench(args, torch, B, wl)
     line = {
         "metric": "prefill_tokens_per_s_per_layer", "value": res["tokens_per_s"], "unit": "tokens/s",
