@@ -124,10 +124,10 @@ __device__ inline void wg_barrier()
 typedef __attribute__((address_space(3))) bf16_t lds_bf16_t;
 __device__ inline uint32_t lds_address(const bf16_t* p) { return (uint32_t)(uintptr_t)(lds_bf16_t*)p; }
 
-template <int D>
+template <int D, bool DBG>
 __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     Geom g, SegList sl, int Q, int tiles_per_bh, const bf16_t* __restrict__ Qr, const bf16_t* __restrict__ Kt,
-    const bf16_t* __restrict__ Vt, bf16_t* __restrict__ out, float* __restrict__ lse)
+    const bf16_t* __restrict__ Vt, bf16_t* __restrict__ out, float* __restrict__ lse, long long* dbg)
 {
     constexpr int BM = kSWaves * 32;       // query rows per workgroup
     constexpr int KS = D / 16;             // k-steps of S^T = K Q^T
@@ -345,6 +345,9 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     if (late) wg_barrier();     // barrier 1
 
     int n0 = 0;   // t
+    long long tc[5] = {0, 0, 0, 0, 0}, tlast = 0;
+    if (DBG) tlast = __builtin_readcyclecounter();
+    auto lap = [&](int i) { if (DBG) { const long long now = __builtin_readcyclecounter(); tc[i] += now - tlast; tlast = now; } };
     while (true) {
         const bool has_next = n0 + 1 < NT;
         const bool act_next = has_next && wave_active(it1);
@@ -356,6 +359,8 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
         // ---- matrix block.  A wave that does not see tile t holds zero probabilities; S^T of a
         // tile this wave does not see (or that does not exist: stale buffer) is computed and
         // dropped.  The order of MFMAs and reads is pinned step by step.
+        lap(0);
+        __builtin_amdgcn_s_setprio(2);
         __builtin_amdgcn_sched_barrier(0);
         {
             const bf16_t* Vtile = Vs + (n0 & 3) * TILE;
@@ -369,8 +374,11 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
             }
         }
         __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_setprio(0);
+        lap(1);
         if (!has_next) break;
         wg_barrier();     // barrier 2t+1 (early group), 2t+2 (late group)
+        lap(2);
         // the first fragments of the next matrix block: V of tile t+1
 #pragma unroll
         for (int i = 0; i < kAhead; ++i) fr[i] = read_frag(Vs + ((n0 + 1) & 3) * TILE, Ks, i);
@@ -384,12 +392,19 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
 #pragma unroll
                 for (int x = 0; x < 4; ++x) pf[qt].u[x] = 0u;
         }
+        lap(3);
         publish(in_flight);
         wg_barrier();     // barrier 2t+2 (early group), 2t+3 (late group)
+        lap(4);
         it1.next(sl, wg_imax);
         ++n0;
     }
     if (!late) wg_barrier();   // the late group passed one barrier more
+    if (DBG && blockIdx.x == 100 && l == 0 && (wave == 0 || wave == 4)) {
+#pragma unroll
+        for (int i = 0; i < 5; ++i) dbg[(wave / 4) * 8 + i] = tc[i];
+        dbg[(wave / 4) * 8 + 5] = n0 + 1;
+    }
     // normalise and store: this lane owns one query, columns 32*db + 8*(j/4) + 4*half + j%4
     const float lt = lsum + __shfl_xor(lsum, 32, 64);
     if (qvalid) {
@@ -436,12 +451,26 @@ void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, i
     constexpr int BM = kSWaves * 32;
     const int tiles = (g.G * Q + BM - 1) / BM;
     const dim3 grid(tiles * g.B * g.Hkv), block(kSWaves * 64);
+    static const char* dbg_env = getenv("CASCADE_KV_ATTN_DEBUG");
+    if (dbg_env && g.d == 128) {   // phase timing of one workgroup (development aid)
+        long long* dbg = (long long*)b.logits;
+        hipLaunchKernelGGL((attn_stream_kernel<128, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)b.Qr,
+                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, dbg);
+        long long h[16];
+        (void)hipStreamSynchronize(s);
+        (void)hipMemcpy(h, dbg, sizeof(h), hipMemcpyDeviceToHost);
+        for (int w = 0; w < 2; ++w)
+            if (h[w * 8 + 5] > 0)
+                printf("wave %d tiles %lld: top %lld mfma %lld wait1 %lld valu %lld wait2 %lld\n", w * 4, h[w * 8 + 5], h[w * 8 + 0] / h[w * 8 + 5],
+                       h[w * 8 + 1] / h[w * 8 + 5], h[w * 8 + 2] / h[w * 8 + 5], h[w * 8 + 3] / h[w * 8 + 5], h[w * 8 + 4] / h[w * 8 + 5]);
+        return;
+    }
     if (g.d == 128)
-        hipLaunchKernelGGL(attn_stream_kernel<128>, grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)b.Qr,
-                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse);
+        hipLaunchKernelGGL((attn_stream_kernel<128, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)b.Qr,
+                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr);
     else
-        hipLaunchKernelGGL(attn_stream_kernel<64>, grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)b.Qr,
-                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse);
+        hipLaunchKernelGGL((attn_stream_kernel<64, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)b.Qr,
+                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr);
 }
 
 }  // namespace ckv
