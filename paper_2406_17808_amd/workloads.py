@@ -5,9 +5,10 @@ the method's arithmetic (no attention, no RoPE, no cache policy), so that both
 the HIP path and the CPU oracle can be fed the same bits from it without
 sharing any code of the method itself.
 
-The five workloads stand in for the paper's latency experiment (a single
+The workloads stand in for the paper's latency experiment (a single
 attention layer at Llama-3.1-8B head geometry streaming a long prompt,
-Section 4.1) and, for the planted key of ``prefill_1m``, for the passkey
+Section 4.1; ``prefill_paper_16k`` has that experiment's own cache size, stride
+and EMA decay) and, for the planted key of ``prefill_1m``, for the passkey
 experiment (Section 4.4); no dataset or trained weight is involved.
 """
 from __future__ import annotations
@@ -54,7 +55,7 @@ class Workload:
         return (self.seq_len + self.chunk - 1) // self.chunk
 
 
-# The five synthetic configurations.  Cascade totals exclude the sink slots
+# The synthetic configurations.  Cascade totals exclude the sink slots
 # (the paper counts sinks in addition to the cache size, Section 4 "Setup").
 WORKLOADS: Dict[str, Workload] = {
     "tiny_f32": Workload(
@@ -73,6 +74,12 @@ WORKLOADS: Dict[str, Workload] = {
         name="prefill_1m", batch=1, n_q_heads=32, n_kv_heads=8, head_dim=128, dtype="bf16",
         n_sink=64, cascade_sizes=(16384,) * 4, seq_len=1048576, chunk=4096,
         ema_beta=0.9, rope_base=500000.0, input_scale=1.0, planted_key=True),
+    # the geometry of the paper's own latency figure (Section 4.1, Appendix "latency"): 16K cache,
+    # stride 4096, EMA decay 0.9999 (every query row of a chunk carries weight in the scores)
+    "prefill_paper_16k": Workload(
+        name="prefill_paper_16k", batch=1, n_q_heads=32, n_kv_heads=8, head_dim=128, dtype="bf16",
+        n_sink=64, cascade_sizes=(4096,) * 4, seq_len=1048576, chunk=4096,
+        ema_beta=0.9999, rope_base=500000.0, input_scale=1.0),
     "decode_b32": Workload(
         name="decode_b32", batch=32, n_q_heads=32, n_kv_heads=8, head_dim=128, dtype="bf16",
         n_sink=64, cascade_sizes=(16384,) * 4, seq_len=1024, chunk=1,

@@ -1,4 +1,4 @@
-"""GPU parity at the full sizes of the five workloads, in the launch configuration bench.py times.
+"""GPU parity at the full sizes of the workloads, in the launch configuration bench.py times.
 
 The library runs every chunk / step; the oracle is brought in at sampled points, loaded with the
 library's state just before (one step ahead), and compares
@@ -87,6 +87,34 @@ def test_prefill_131k_sampled_heads(oracle_mod):
     assert st.n_seen == wl.seq_len
     # Eq. 4: the span of 8 cascades of 2048 exceeds the sequence, so the late cascades are not full
     assert st.counts[1:5].tolist() == [2048] * 4 and st.counts[-1] < 2048
+    run.close()
+
+
+def test_prefill_paper_16k_all_rows_in_scores(oracle_mod):
+    """The geometry of the paper's latency figure: 64 sinks + 4 x 4096 slots, stride 4096, EMA decay
+    0.9999, so every one of the 4096 query rows of a chunk enters the score sums (sixteen passes of
+    the score kernel).  Eight chunks; the seventh (three cascades full, discards under way) compared whole
+    on two KV heads."""
+    from gpu_harness import ParityRun
+    from paper_2406_17808_amd.cache import config_of
+    wl = WORKLOADS["prefill_paper_16k"]
+    cfg = config_of(wl, keep_update_scores=1)
+    run = ParityRun(cfg, one_step_ahead=True, kv_heads=[0, 5])
+    rep = None
+    for c in range(8):
+        dq, dk, dv = chunk_inputs_torch(wl, 0, c, "cuda:0")
+        if c == 6:
+            run.sync_oracle_from_gpu()
+            print("prefill_paper_16k: comparing chunk 6", flush=True)
+            rep = _step_two_heads(run, _host(dq), _host(dk), _host(dv))
+        else:
+            run.advance_gpu_only(dq, dk, dv)
+    print(f"prefill_paper_16k: out {rep.out_err:.3e} score {rep.score_err:.3e} drift {rep.drift}/{rep.compared}")
+    assert rep.replay_exact
+    assert rep.out_err <= TOL_OUT and rep.score_err <= TOL_SCORE
+    st = run.gpu.read_state()
+    # the last cascade takes every eighth token that leaves the first: 32768 tokens do not fill it yet
+    assert st.n_seen == 8 * wl.chunk and st.counts[:4].tolist() == [64, 4096, 4096, 4096] and 3000 < st.counts[4] <= 4096
     run.close()
 
 
