@@ -178,6 +178,7 @@ def main():
     ap.add_argument("--cpu-sample-tokens", type=int, default=640)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--only-decode", action="store_true")
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--decode-warmup", type=int, default=16)
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
@@ -194,6 +195,9 @@ def main():
     wl = WORKLOADS[args.workload]
     if args.copy_calibration_mib:
         calibration_copy(torch, args.copy_calibration_mib)
+    if args.only_decode:   # development aid: the decode section alone, not the contract line
+        print(json.dumps(decode_bench(args, torch, B)))
+        return
     res, cache, chunks, cfg = prefill_bench(args, torch, B, wl)
     line = {
         "metric": "prefill_tokens_per_s_per_layer", "value": res["tokens_per_s"], "unit": "tokens/s",

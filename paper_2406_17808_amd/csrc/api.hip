@@ -160,7 +160,7 @@ static size_t carve(const cascade_config* c, const Geom& g, char* base, DevBuffe
     b.mu_chunk = (float*)take(BH * mc * 4);
     b.offers = (int32_t*)take(BH * 2 * mc * 4);
     b.winners = (int32_t*)take(BH * g.N * (mc + 1) * 4);
-    b.logits = (float*)take(BHq * ((size_t)g.slots + 1) * 4);
+    b.logits = (float*)take(BH * ((size_t)g.slots + 1) * (size_t)(g.G <= 8 ? decode_logit_heads(g) : g.G) * 4);
     b.part = (float*)take(BHq * splits * 2 * 4);
     b.opart = (float*)take(BHq * splits * g.d * 4);
     b.rope_rows = rope_rows;

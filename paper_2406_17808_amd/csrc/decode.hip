@@ -2,6 +2,8 @@
 // The cache is streamed once from HBM: K by decode_qk (logits), V by decode_pv (outputs and
 // EMA scores); the logits of a step (16 bytes per cached row at 4 query heads per KV head)
 // pass through a scratch array because the EMA update needs exact probabilities.
+#include <stdlib.h>
+
 #include "launch.h"
 
 namespace ckv {
@@ -10,6 +12,14 @@ constexpr int kDecThreads = 256;
 constexpr int kLanesPerRow = 16;                            // lanes that share one row in the VALU kernels
 constexpr int kRowGroups = kDecThreads / kLanesPerRow;      // 16 row groups per workgroup
 constexpr int kMaxG = 8;
+
+// Logits of a step: [B][Hkv][n_cached + 1][MAXG] floats, MAXG = group size rounded up to 1, 2, 4
+// or 8 (decode_logit_heads): the heads of a group are adjacent, so the kernel that computes them
+// stores, and the kernel that consumes them loads, whole 64-byte-aligned runs of a row block.
+__device__ inline size_t logit_index(const Geom& g, int maxg, size_t lrows, int b, int hk, int row, int hh)
+{
+    return ((((size_t)b * g.Hkv + hk) * lrows + row) * maxg) + hh;
+}
 
 template <typename T, int EPL> struct VecLoad;
 template <> struct VecLoad<bf16_t, 8> {
@@ -94,7 +104,7 @@ __device__ inline uint32_t dec_pack_bf16(float lo, float hi)
 
 constexpr int kQkRowsPerWave = 64;   // four 16-key MFMA groups in flight per wave iteration
 
-template <int D>
+template <int D, int MAXG>
 __global__ __launch_bounds__(kDecThreads) void decode_qk_mfma_kernel(
     Geom g, SegList sl, int per_split, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k_new,
     const bf16_t* __restrict__ Kr, const float2* __restrict__ rope, float* __restrict__ logits,
@@ -103,15 +113,16 @@ __global__ __launch_bounds__(kDecThreads) void decode_qk_mfma_kernel(
     constexpr int KS = D / 32;            // MFMA steps over the head dimension
     constexpr int NG = kQkRowsPerWave / 16;
     __shared__ float red_m[kDecThreads / 64][16], red_l[kDecThreads / 64][16];
+    __shared__ float stage[kDecThreads / 64][kQkRowsPerWave * MAXG];   // a wave's logits of one iteration, [row][head]
     const int split = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
     const int bh = b * g.Hkv + hk;
     const int wave = threadIdx.x >> 6, l = threadIdx.x & 63, n = l & 15, c = l >> 4;
     const int ncached = sl.n_cached;
     const int j0 = split * per_split, j1 = min(ncached, j0 + per_split);
-    const size_t lstride = (size_t)ncached + 1;
+    const size_t lrows = (size_t)ncached + 1;
     const bool head_ok = n < g.G;
     const bf16_t* qh = q + ((size_t)b * g.Hq + hk * g.G + (head_ok ? n : 0)) * D;
-    float* lrow = logits + ((size_t)b * g.Hq + hk * g.G + (head_ok ? n : 0)) * lstride;
+    float* lbase = logits + logit_index(g, MAXG, lrows, b, hk, 0, 0);
     float m = -INFINITY, lsum = 0.f;
 
     int seg_first = 0;                    // index of the segment's first row in the concatenation
@@ -150,17 +161,31 @@ __global__ __launch_bounds__(kDecThreads) void decode_qk_mfma_kernel(
                         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[gi][ks].v, qf[ks].v, acc, 0, 0, 0);
                     // this lane: head n, keys r0 + 16*gi + 4*c + {0..3}
                     const int rbase = r0 + gi * 16 + 4 * c;
+                    if (n < MAXG) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) stage[wave][(gi * 16 + 4 * c + j) * MAXG + n] = acc[j];
+                    }
                     if (head_ok) {
+                        // one rescaling per four logits: the running maximum rarely moves
+                        float mx = m;
 #pragma unroll
                         for (int j = 0; j < 4; ++j)
-                            if (rbase + j < hi) {
-                                const float s = acc[j];
-                                lrow[rbase + j] = s;
-                                const float mn = fmaxf(m, s);
-                                lsum = lsum * __expf(m - mn) + __expf(s - mn);
-                                m = mn;
-                            }
+                            if (rbase + j < hi) mx = fmaxf(mx, acc[j]);
+                        if (mx > m) {   // (also keeps -inf - -inf out of the arithmetic)
+                            lsum *= __expf(m - mx);
+                            m = mx;
+                        }
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if (rbase + j < hi) lsum += __expf(acc[j] - m);
                     }
+                }
+                // the wave's 64 x MAXG logits leave as contiguous 256-byte stores (LDS accesses of one
+                // wave are ordered; no other wave touches this stage)
+#pragma unroll
+                for (int i = 0; i < MAXG; ++i) {
+                    const int idx = l + 64 * i;
+                    if (r0 + idx / MAXG < hi) lbase[(size_t)r0 * MAXG + idx] = stage[wave][idx];
                 }
             }
         }
@@ -173,7 +198,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_qk_mfma_kernel(
             float acc = 0.f;
             for (int e = 0; e < D; ++e) acc += bf16_to_f32(qh[e]) * bf16_to_f32(kn[e]);
             acc *= g.scale;
-            lrow[ncached] = acc;
+            lbase[(size_t)ncached * MAXG + n] = acc;
             const float mn = fmaxf(m, acc);
             lsum = lsum * __expf(m - mn) + __expf(acc - mn);
             m = mn;
@@ -213,7 +238,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_qk_valu_kernel(
     const int grp = threadIdx.x / kLanesPerRow, lane = threadIdx.x % kLanesPerRow;
     const int ncached = sl.n_cached, d = g.d;
     const int j0 = split * per_split, j1 = min(ncached, j0 + per_split);
-    const size_t lstride = (size_t)ncached + 1;
+    const size_t lrows = (size_t)ncached + 1;
     float m[MAXG], lsum[MAXG];
 #pragma unroll
     for (int hh = 0; hh < MAXG; ++hh) { m[hh] = -INFINITY; lsum[hh] = 0.f; }
@@ -249,7 +274,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_qk_valu_kernel(
 #pragma unroll
                             for (int w = kLanesPerRow / 2; w > 0; w >>= 1) acc += __shfl_xor(acc, w, kLanesPerRow);
                             if (lane == 0 && r0 + u < hi) {
-                                logits[((size_t)b * g.Hq + hk * g.G + hh) * lstride + r0 + u] = acc;
+                                logits[logit_index(g, MAXG, lrows, b, hk, r0 + u, hh)] = acc;
                                 const float mn = fmaxf(m[hh], acc);
                                 lsum[hh] = lsum[hh] * __expf(m[hh] - mn) + __expf(acc - mn);
                                 m[hh] = mn;
@@ -275,7 +300,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_qk_valu_kernel(
                 for (int w = kLanesPerRow / 2; w > 0; w >>= 1) acc += __shfl_xor(acc, w, kLanesPerRow);
                 acc *= g.scale;
                 if (lane == 0) {
-                    logits[((size_t)b * g.Hq + hk * g.G + hh) * lstride + ncached] = acc;
+                    logits[logit_index(g, MAXG, lrows, b, hk, ncached, hh)] = acc;
                     const float mn = fmaxf(m[hh], acc);
                     lsum[hh] = lsum[hh] * __expf(m[hh] - mn) + __expf(acc - mn);
                     m[hh] = mn;
@@ -298,38 +323,87 @@ __global__ __launch_bounds__(kDecThreads) void decode_qk_valu_kernel(
 
 // ------------------------------------------------------------------ PV and EMA scores
 
+// Lane N of every row of 16 lanes, to all lanes of that row (DPP row_newbcast).
+template <int N> __device__ inline float row_bcast(float x)
+{
+    return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), 0x150 + N, 0xf, 0xf, false));
+}
+
+template <int J, int NPL> __device__ inline float pair_value(const float (&pl)[NPL])
+{
+    return row_bcast<J % 16>(pl[J / 16]);
+}
+
+template <int HH, int U, int MAXG, int EPL, int NPL>
+__device__ inline void pv_accumulate_head(const float (&pl)[NPL], const float (&vv)[U][EPL], float (&o)[MAXG][EPL],
+                                          float (&red)[U], bool use_max, int G)
+{
+    if (HH < G) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float p;
+            // the pair index must be a compile-time constant of the broadcast: spelled out per row
+            switch (u) {
+                case 0: p = pair_value<0 * MAXG + HH>(pl); break;
+                case 1: p = pair_value<1 * MAXG + HH>(pl); break;
+                case 2: p = pair_value<2 * MAXG + HH>(pl); break;
+                case 3: p = pair_value<3 * MAXG + HH>(pl); break;
+                case 4: p = pair_value<4 * MAXG + HH>(pl); break;
+                case 5: p = pair_value<5 * MAXG + HH>(pl); break;
+                case 6: p = pair_value<6 * MAXG + HH>(pl); break;
+                default: p = pair_value<7 * MAXG + HH>(pl); break;
+            }
+#pragma unroll
+            for (int x = 0; x < EPL; ++x) o[HH][x] += p * vv[u][x];
+            red[u] = use_max ? fmaxf(red[u], p) : red[u] + p;
+        }
+    }
+}
+
 // With the exact log-sum-exp (all splits of decode_qk combined) p = exp(logit - lse) is final,
 // so the partial outputs of the splits simply add up, and mu <- beta*mu + (1-beta)*reduce_heads(p)
-// is applied in the same pass (Section 3.1).  Sixteen lanes share a row, four rows in flight.
+// is applied in the same pass (Section 3.1).  Sixteen lanes share a row (each owns EPL elements
+// of it), eight rows per lane group are in flight.  The probabilities of those rows (8 x MAXG
+// values) are computed once, spread over the sixteen lanes, and handed round by lane broadcasts.
 template <typename T, int EPL, int MAXG>
 __global__ __launch_bounds__(kDecThreads) void decode_pv_kernel(
     Geom g, SegList sl, int per_split, const T* __restrict__ Vc, const float* __restrict__ logits,
     const float* __restrict__ part, int n_splits, float* __restrict__ opart, float* __restrict__ mu,
     float* __restrict__ lse_out)
 {
-    constexpr int U = 4;
+    constexpr int U = 8;
+    constexpr int NP = U * MAXG, NPL = (NP + kLanesPerRow - 1) / kLanesPerRow;
     __shared__ float lse_s[MAXG];
     __shared__ float osum[kDecThreads / 64][MAXG][kLanesPerRow * EPL];
     const int split = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
     const int bh = b * g.Hkv + hk;
     const int grp = threadIdx.x / kLanesPerRow, lane = threadIdx.x % kLanesPerRow;
     const int ncached = sl.n_cached, d = g.d;
-    const size_t lstride = (size_t)ncached + 1;
-    if (threadIdx.x < g.G) {
-        const float* p = part + ((size_t)b * g.Hq + hk * g.G + threadIdx.x) * n_splits * 2;
-        float mm = -INFINITY, ll = 0.f;
-        for (int s = 0; s < n_splits; ++s) ml_merge(mm, ll, p[2 * s], p[2 * s + 1]);
-        const float v = mm + __logf(ll);
+    const size_t lrows = (size_t)ncached + 1;
+    if (threadIdx.x < MAXG) {
+        float v = 0.f;
+        if (threadIdx.x < g.G) {
+            const float* p = part + ((size_t)b * g.Hq + hk * g.G + threadIdx.x) * n_splits * 2;
+            float mm = -INFINITY, ll = 0.f;
+            for (int s = 0; s < n_splits; ++s) ml_merge(mm, ll, p[2 * s], p[2 * s + 1]);
+            v = mm + __logf(ll);
+            if (split == 0) lse_out[(size_t)b * g.Hq + hk * g.G + threadIdx.x] = v;
+        }
         lse_s[threadIdx.x] = v;
-        if (split == 0) lse_out[(size_t)b * g.Hq + hk * g.G + threadIdx.x] = v;
     }
     __syncthreads();
-    float lse_r[MAXG];
-    const float* lrow[MAXG];
+    // this lane's pairs: pair j = lane + 16 t is (row j / MAXG of the eight, head j % MAXG)
+    // (the pairs of eight consecutive rows are 8 x MAXG consecutive floats of the logits)
+    int pu[NPL];
+    float plse[NPL];
+    bool pvalid[NPL];
+    const float* lbase = logits + logit_index(g, MAXG, lrows, b, hk, 0, 0);
 #pragma unroll
-    for (int hh = 0; hh < MAXG; ++hh) {
-        lse_r[hh] = hh < g.G ? lse_s[hh] : 0.f;
-        lrow[hh] = logits + ((size_t)b * g.Hq + hk * g.G + (hh < g.G ? hh : 0)) * lstride;
+    for (int t = 0; t < NPL; ++t) {
+        const int j = lane + kLanesPerRow * t, hh = j % MAXG;
+        pu[t] = j / MAXG;
+        pvalid[t] = j < NP && hh < g.G;
+        plse[t] = lse_s[hh];
     }
     float o[MAXG][EPL];
 #pragma unroll
@@ -338,6 +412,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_pv_kernel(
         for (int x = 0; x < EPL; ++x) o[hh][x] = 0.f;
     const int j0 = split * per_split, j1 = min(ncached, j0 + per_split);
     const float beta = g.beta, omb = 1.f - g.beta;
+    const bool use_max = g.head_reduce == CASCADE_REDUCE_MAX;
 
     int seg_first = 0;
     for (int si = 0; si < sl.n; ++si) {
@@ -346,34 +421,50 @@ __global__ __launch_bounds__(kDecThreads) void decode_pv_kernel(
         if (lo < hi) {
             const T* vseg = Vc + ((ptrdiff_t)bh * g.slots + sg.start - seg_first) * d;
             float* museg = mu + ((ptrdiff_t)bh * g.slots + sg.start - seg_first);
-            for (int r0 = lo + grp * U; r0 < hi; r0 += kRowGroups * U) {
-                float vv[U][EPL];
-                float lg[U][MAXG];
+            // (holding the next iteration's rows in a second register set costs more in occupancy than it gains)
+            auto fetch = [&](int r0, float (&vv)[U][EPL], float (&lg)[NPL]) {
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int r = min(r0 + u, hi - 1);
-                    VecLoad<T, EPL>::load(vseg + (size_t)r * d + lane * EPL, vv[u]);
+                for (int u = 0; u < U; ++u) VecLoad<T, EPL>::load(vseg + (size_t)min(r0 + u, hi - 1) * d + lane * EPL, vv[u]);
 #pragma unroll
-                    for (int hh = 0; hh < MAXG; ++hh) lg[u][hh] = hh < g.G ? lrow[hh][r] : -INFINITY;
+                for (int t = 0; t < NPL; ++t)
+                    lg[t] = (pvalid[t] && r0 + pu[t] < hi) ? lbase[(size_t)r0 * MAXG + lane + kLanesPerRow * t] : -INFINITY;
+            };
+            auto consume = [&](int r0, const float (&vv)[U][EPL], const float (&lg)[NPL]) {
+                float pl[NPL];
+#pragma unroll
+                for (int t = 0; t < NPL; ++t) pl[t] = __expf(lg[t] - plse[t]);   // exp(-inf) = 0 for pairs that do not exist
+                float red[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) red[u] = 0.f;
+                pv_accumulate_head<0, U, MAXG, EPL, NPL>(pl, vv, o, red, use_max, g.G);
+                if (MAXG > 1) pv_accumulate_head<1 % MAXG, U, MAXG, EPL, NPL>(pl, vv, o, red, use_max, g.G);
+                if (MAXG > 2) {
+                    pv_accumulate_head<2 % MAXG, U, MAXG, EPL, NPL>(pl, vv, o, red, use_max, g.G);
+                    pv_accumulate_head<3 % MAXG, U, MAXG, EPL, NPL>(pl, vv, o, red, use_max, g.G);
                 }
+                if (MAXG > 4) {
+                    pv_accumulate_head<4 % MAXG, U, MAXG, EPL, NPL>(pl, vv, o, red, use_max, g.G);
+                    pv_accumulate_head<5 % MAXG, U, MAXG, EPL, NPL>(pl, vv, o, red, use_max, g.G);
+                    pv_accumulate_head<6 % MAXG, U, MAXG, EPL, NPL>(pl, vv, o, red, use_max, g.G);
+                    pv_accumulate_head<7 % MAXG, U, MAXG, EPL, NPL>(pl, vv, o, red, use_max, g.G);
+                }
+                if (lane == 0) {
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const bool ok = r0 + u < hi;
-                    float red = 0.f;
-#pragma unroll
-                    for (int hh = 0; hh < MAXG; ++hh)
-                        if (hh < g.G) {
-                            const float p = ok ? __expf(lg[u][hh] - lse_r[hh]) : 0.f;
-#pragma unroll
-                            for (int x = 0; x < EPL; ++x) o[hh][x] += p * vv[u][x];
-                            red = (g.head_reduce == CASCADE_REDUCE_MAX) ? fmaxf(red, p) : red + p;
+                    for (int u = 0; u < U; ++u)
+                        if (r0 + u < hi) {
+                            float* pm = museg + r0 + u;
+                            *pm = beta * *pm + omb * (use_max ? red[u] : red[u] / (float)g.G);
                         }
-                    if (lane == 0 && ok) {
-                        if (g.head_reduce == CASCADE_REDUCE_MEAN) red /= (float)g.G;
-                        float* pm = museg + r0 + u;
-                        *pm = beta * *pm + omb * red;
-                    }
                 }
+            };
+            constexpr int STEP = kRowGroups * U;
+            float vvA[U][EPL], lgA[NPL];
+            int r0 = lo + grp * U;
+            if (r0 < hi) fetch(r0, vvA, lgA);
+            while (r0 < hi) {
+                consume(r0, vvA, lgA);
+                r0 += STEP;
+                if (r0 < hi) fetch(r0, vvA, lgA);
             }
         }
         seg_first += sg.len;
@@ -400,16 +491,16 @@ __global__ __launch_bounds__(kDecThreads) void decode_pv_kernel(
 // out = sum of the split outputs + own value weighted by its probability; the new token's
 // score starts at (1-beta) * reduce_heads(p_own).
 template <typename T>
-__global__ void decode_finish_kernel(Geom g, int n_cached, int n_splits, int qstride,
+__global__ void decode_finish_kernel(Geom g, int n_cached, int n_splits, int qstride, int maxg,
                                      const float* __restrict__ opart, const float* __restrict__ logits,
                                      const float* __restrict__ lse, const T* __restrict__ v_new,
                                      T* __restrict__ out, float* __restrict__ mu_chunk)
 {
     const int hk = blockIdx.x, b = blockIdx.y;
-    const size_t lstride = (size_t)n_cached + 1;
+    const size_t lrows = (size_t)n_cached + 1;
     for (int idx = threadIdx.x; idx < g.G * g.d; idx += blockDim.x) {
         const int hh = idx / g.d, e = idx % g.d, h = hk * g.G + hh;
-        const float p = __expf(logits[((size_t)b * g.Hq + h) * lstride + n_cached] - lse[(size_t)b * g.Hq + h]);
+        const float p = __expf(logits[logit_index(g, maxg, lrows, b, hk, n_cached, hh)] - lse[(size_t)b * g.Hq + h]);
         float s = p * Elem<T>::load(v_new + ((size_t)b * g.Hkv + hk) * g.d + e);
         const float* op = opart + ((size_t)b * g.Hq + h) * n_splits * g.d + e;
         for (int sp = 0; sp < n_splits; ++sp) s += op[(size_t)sp * g.d];
@@ -419,7 +510,7 @@ __global__ void decode_finish_kernel(Geom g, int n_cached, int n_splits, int qst
         float red = 0.f;
         for (int hh = 0; hh < g.G; ++hh) {
             const int h = hk * g.G + hh;
-            const float p = __expf(logits[((size_t)b * g.Hq + h) * lstride + n_cached] - lse[(size_t)b * g.Hq + h]);
+            const float p = __expf(logits[logit_index(g, maxg, lrows, b, hk, n_cached, hh)] - lse[(size_t)b * g.Hq + h]);
             red = (g.head_reduce == CASCADE_REDUCE_MAX) ? fmaxf(red, p) : red + p;
         }
         if (g.head_reduce == CASCADE_REDUCE_MEAN) red /= (float)g.G;
@@ -437,6 +528,8 @@ static int per_split_of(const DevBuffers& bf, int n)
 }
 
 static int maxg_of(const Geom& g) { return g.G <= 1 ? 1 : (g.G <= 2 ? 2 : (g.G <= 4 ? 4 : 8)); }
+
+int decode_logit_heads(const Geom& g) { return maxg_of(g); }
 
 template <typename T, int EPL, int MAXG>
 static void qk_valu(const Geom& g, const DevBuffers& bf, const SegList& sl, const void* q, const void* k, hipStream_t s)
@@ -479,12 +572,16 @@ void launch_decode_qk(const Geom& g, int dtype, const DevBuffers& b, const SegLi
     if (dtype == CASCADE_BF16) {
         const dim3 grid(b.dec_splits, g.Hkv, g.B), block(kDecThreads);
         const int ps = per_split_of(b, sl.n_cached);
-        if (g.d == 128)
-            hipLaunchKernelGGL(decode_qk_mfma_kernel<128>, grid, block, 0, s, g, sl, ps, (const bf16_t*)q, (const bf16_t*)k,
-                               (const bf16_t*)b.Kr, b.rope, b.logits, b.part, b.dec_splits);
-        else
-            hipLaunchKernelGGL(decode_qk_mfma_kernel<64>, grid, block, 0, s, g, sl, ps, (const bf16_t*)q, (const bf16_t*)k,
-                               (const bf16_t*)b.Kr, b.rope, b.logits, b.part, b.dec_splits);
+#define CKV_QK_MFMA(D, MG)                                                                                        \
+    hipLaunchKernelGGL((decode_qk_mfma_kernel<D, MG>), grid, block, 0, s, g, sl, ps, (const bf16_t*)q, (const bf16_t*)k, \
+                       (const bf16_t*)b.Kr, b.rope, b.logits, b.part, b.dec_splits)
+        const int mg = maxg_of(g);
+        if (g.d == 128) {
+            if (mg == 1) CKV_QK_MFMA(128, 1); else if (mg == 2) CKV_QK_MFMA(128, 2); else if (mg == 4) CKV_QK_MFMA(128, 4); else CKV_QK_MFMA(128, 8);
+        } else {
+            if (mg == 1) CKV_QK_MFMA(64, 1); else if (mg == 2) CKV_QK_MFMA(64, 2); else if (mg == 4) CKV_QK_MFMA(64, 4); else CKV_QK_MFMA(64, 8);
+        }
+#undef CKV_QK_MFMA
         return;
     }
     CKV_DISPATCH(qk_valu, g, b, sl, q, k, s);
@@ -500,10 +597,10 @@ void launch_decode_finish(const Geom& g, int dtype, const DevBuffers& b, const S
 {
     const dim3 grid(g.Hkv, g.B), block(256);
     if (dtype == CASCADE_F32)
-        hipLaunchKernelGGL(decode_finish_kernel<float>, grid, block, 0, s, g, sl.n_cached, b.dec_splits, qstride, b.opart,
+        hipLaunchKernelGGL(decode_finish_kernel<float>, grid, block, 0, s, g, sl.n_cached, b.dec_splits, qstride, maxg_of(g), b.opart,
                            b.logits, b.lse, (const float*)v, (float*)out, b.mu_chunk);
     else
-        hipLaunchKernelGGL(decode_finish_kernel<bf16_t>, grid, block, 0, s, g, sl.n_cached, b.dec_splits, qstride, b.opart,
+        hipLaunchKernelGGL(decode_finish_kernel<bf16_t>, grid, block, 0, s, g, sl.n_cached, b.dec_splits, qstride, maxg_of(g), b.opart,
                            b.logits, b.lse, (const bf16_t*)v, (bf16_t*)out, b.mu_chunk);
 }
 

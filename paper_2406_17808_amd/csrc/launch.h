@@ -29,7 +29,7 @@ struct DevBuffers {
     int32_t* offers; // [B,Hkv,2,max_chunk]
     int32_t* winners;// [B,Hkv,N,max_chunk+1]
     // decode scratch
-    float* logits;   // [B,Hq,slots+1]
+    float* logits;   // [B,Hkv,slots+1,decode_logit_heads]
     float* part;     // [B,Hq,dec_splits,2] (max, sum) of every split
     float* opart;    // [B,Hq,dec_splits,d]
     int rope_rows;
@@ -72,5 +72,6 @@ void launch_decode_pv(const Geom& g, int dtype, const DevBuffers& b, const SegLi
 void launch_decode_finish(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int qstride,
                           const void* v, void* out, hipStream_t s);
 bool decode_supported(const Geom& g);
+int decode_logit_heads(const Geom& g);   // heads per row of the logits buffer (group size rounded up to 1, 2, 4, 8)
 
 }  // namespace ckv
