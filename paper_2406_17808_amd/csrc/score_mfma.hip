@@ -71,27 +71,40 @@ __global__ __launch_bounds__(kScoreThreads, 2) void score_mfma_kernel(
         const float* lrow = lse + ((size_t)b * g.Hq + h) * Q;
         float colsum[2] = {0.f, 0.f};
         for (int ps = 0; ps < n_pass; ++ps) {
-            const int i_base = Q - (n_pass - ps) * kScoreRows;          // may be negative in the first pass
+            const int i_base = i_first + ps * kScoreRows;               // passes start at the first contributing row
+            const int rows = min(kScoreRows, Q - i_base);               // the last pass may be short
             __syncthreads();                                            // the previous pass has been consumed
-            // stage 256 rows of this head (16-byte pieces) and their exponent offsets
+            // stage the rows of this pass (16-byte pieces) and their exponent offsets.  A full pass
+            // issues all its loads before the first store; a short one (the last) stages only whole
+            // blocks of 32 rows, rows past its end repeating the last row.
+            if (rows == kScoreRows) {
+                u32x4_t buf[kScoreRows * D / 8 / kScoreThreads];
 #pragma unroll
-            for (int x = 0; x < kScoreRows * D / 8 / kScoreThreads; ++x) {
-                const int p = tid + x * kScoreThreads;
-                const int r = p / (D / 8), c8 = p % (D / 8);
-                const int i = min(max(i_base + r, 0), Q - 1);
-                *reinterpret_cast<u32x4_t*>(&Qs[r * QSTR + c8 * 8]) =
-                    *reinterpret_cast<const u32x4_t*>(qbase + (size_t)i * D + c8 * 8);
+                for (int x = 0; x < kScoreRows * D / 8 / kScoreThreads; ++x) {
+                    const int p = tid + x * kScoreThreads;
+                    buf[x] = *reinterpret_cast<const u32x4_t*>(qbase + (size_t)(i_base + p / (D / 8)) * D + (p % (D / 8)) * 8);
+                }
+#pragma unroll
+                for (int x = 0; x < kScoreRows * D / 8 / kScoreThreads; ++x) {
+                    const int p = tid + x * kScoreThreads;
+                    *reinterpret_cast<u32x4_t*>(&Qs[(p / (D / 8)) * QSTR + (p % (D / 8)) * 8]) = buf[x];
+                }
+            } else {
+                for (int p = tid; p < ((rows + 31) & ~31) * (D / 8); p += kScoreThreads) {
+                    const int r = p / (D / 8), c8 = p % (D / 8);
+                    *reinterpret_cast<u32x4_t*>(&Qs[r * QSTR + c8 * 8]) =
+                        *reinterpret_cast<const u32x4_t*>(qbase + (size_t)min(i_base + r, Q - 1) * D + c8 * 8);
+                }
             }
             {
                 const int i = i_base + tid;                              // kScoreRows == kScoreThreads
                 float t = INFINITY;
-                if (i >= i_first && i >= 0) t = lrow[i] * 1.4426950408889634f - __log2f(wrow[Q - 1 - i]);
+                if (i < Q) t = lrow[i] * 1.4426950408889634f - __log2f(wrow[Q - 1 - i]);
                 ts[tid] = t;
             }
             __syncthreads();
-            for (int rb = 0; rb < kScoreRows / 32; ++rb) {
+            for (int rb = 0; rb < (rows + 31) / 32; ++rb) {
                 const int i0 = i_base + rb * 32;
-                if (i0 + 31 < i_first) continue;                         // no row of the block contributes
                 if (sg.chunk && i0 + 31 < wave_k0) continue;             // chunk keys are seen by later rows only
                 f32x16_t s[2];
 #pragma unroll
