@@ -17,6 +17,7 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include "async_copy.h"
 #include "mfma_util.h"
 
 namespace ckv {
@@ -92,37 +93,6 @@ __global__ __launch_bounds__(kPackThreads) void kv_pack_kernel(Geom g, SegList s
         *reinterpret_cast<u32x4_t*>(dst + (size_t)p * 8) = v;
     }
 }
-
-// One asynchronous 1 KB copy: lane i moves the 16 bytes at base + voff(i) to LDS address
-// lds + 16 i.  The instruction is written out so that the waits on it stay under this file's
-// control (s_waitcnt vmcnt before the barrier that publishes a tile); loads are retired in order,
-// so the compiler's own vmcnt waits for its ordinary loads can only wait longer, never less.
-__device__ inline void async_copy_1k(const bf16_t* base, uint32_t voff, uint32_t lds)
-{
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :
-                 : "v"(voff), "s"(base), "s"(lds)
-                 : "memory");
-}
-
-template <int N> __device__ inline void wait_vm()   // at most N vector memory operations outstanding
-{
-    static_assert(N >= 0 && N < 64, "vmcnt range");
-    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
-}
-
-// Workgroup barrier without the memory fence of __syncthreads (which would wait for the copies
-// still in flight).  The callers wait for exactly the copies the barrier publishes; the empty asm
-// statements keep the compiler from moving LDS accesses across it.
-__device__ inline void wg_barrier()
-{
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-}
-
-typedef __attribute__((address_space(3))) bf16_t lds_bf16_t;
-__device__ inline uint32_t lds_address(const bf16_t* p) { return (uint32_t)(uintptr_t)(lds_bf16_t*)p; }
 
 template <int D, bool DBG>
 __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(

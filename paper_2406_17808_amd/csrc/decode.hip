@@ -4,6 +4,7 @@
 // pass through a scratch array because the EMA update needs exact probabilities.
 #include <stdlib.h>
 
+#include "async_copy.h"
 #include "launch.h"
 
 namespace ckv {
@@ -518,6 +519,256 @@ __global__ void decode_finish_kernel(Geom g, int n_cached, int n_splits, int qst
     }
 }
 
+// ------------------------------------------------------------------ PV and EMA scores, bf16: MFMA fed from LDS
+//
+// O^T = V^T P^T with v_mfma_f32_16x16x32_bf16: rows are 16 elements of the head dimension, columns
+// the query heads of the group (padded to 16), the contraction runs over 32 cached rows.  Every
+// wave streams its own 32-row tiles of V (and the tiles' logits and scores) through a private
+// ring of LDS stages filled by asynchronous copies, so the bytes in flight do not depend on what
+// the wave is computing and no workgroup barrier is needed inside the loop.  The A operand wants
+// 8 rows of one column per lane: ds_read_b64_tr_b16 transposes on the way out of LDS.
+//
+// A staged V tile keeps rows of D elements; the 16-byte pieces of a row are permuted (piece ^
+// swizzle(row)) so that the 8 rows one half of a wave reads in a transposing read fall into
+// different banks.  The copy applies the permutation on the global side (a copy instruction
+// writes LDS contiguously).
+constexpr int kPvStages = 4;
+constexpr int kPvRows = 32;           // cached rows per tile = contraction length of the MFMA
+constexpr int kPvWaves = kDecThreads / 64;
+
+template <int D> struct PvSwizzle;
+template <> struct PvSwizzle<128> {
+    __device__ static int of(int row) { return 2 * ((((row >> 3) & 1) << 2) | (row & 3)); }
+};
+template <> struct PvSwizzle<64> {
+    __device__ static int of(int row) { return 2 * ((((row >> 3) & 1) << 1) | ((row >> 1) & 1)); }
+};
+
+typedef short pv_v4i16_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) pv_v4i16_t pv_lds_v4i16_t;
+
+// ds_read_b64_tr_b16: the 16 lanes of a group address a 4-row x 16-column block of 16-bit
+// elements (lane i: row i/4, columns 4*(i%4)..+3); lane i receives column i of the 4 rows.
+__device__ inline uint2 pv_read_tr16(const unsigned char* p)
+{
+    const pv_v4i16_t r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((pv_lds_v4i16_t*)p);
+    return __builtin_bit_cast(uint2, r);
+}
+
+// The tiles of one wave in order: inside every segment's part of [j0, j1) the waves take tiles
+// of 32 rows in turn.
+struct PvTiles {
+    int si, seg_first, r0, hi, start;
+    bool valid;
+    __device__ void seek(const SegList& sl, int j0, int j1, int wave)
+    {
+        while (si < sl.n) {
+            const int len = sl.s[si].len;
+            hi = min(j1, seg_first + len);
+            r0 = max(j0, seg_first) + wave * kPvRows;
+            start = sl.s[si].start;
+            if (r0 < hi) { valid = true; return; }
+            seg_first += len;
+            ++si;
+        }
+        valid = false;
+    }
+    __device__ void begin(const SegList& sl, int j0, int j1, int wave)
+    {
+        si = 0; seg_first = 0; r0 = 0; hi = 0; start = 0;
+        seek(sl, j0, j1, wave);
+    }
+    __device__ void next(const SegList& sl, int j0, int j1, int wave)
+    {
+        r0 += kPvWaves * kPvRows;
+        if (r0 >= hi) {
+            seg_first += sl.s[si].len;
+            ++si;
+            seek(sl, j0, j1, wave);
+        }
+    }
+};
+
+template <int D, int MAXG>
+struct PvStage {
+    static constexpr int kVBytes = kPvRows * D * 2;
+    static constexpr int kLogitCopies = (kPvRows * MAXG * 4 + 255) / 256;
+    static constexpr int kLgOff = kVBytes;                        // logits of the tile, [row][head]
+    static constexpr int kMuOff = kLgOff + kLogitCopies * 256;    // scores of the tile's rows
+    static constexpr int kBytes = kMuOff + 256;
+    static constexpr int kVCopies = kVBytes / 1024;
+    static constexpr int kCopies = kVCopies + kLogitCopies + 1;   // vector memory operations per tile
+};
+
+// Waits until the copies of the oldest tile in flight have landed: `ahead` later tiles have been
+// issued after it, and (in steady state) kPvStages - 1 score stores.  Counting fewer operations
+// than are really outstanding only waits longer.
+template <int NT> __device__ inline void pv_wait(int ahead, bool steady)
+{
+    static_assert(kPvStages == 4, "cases below");
+    if (steady) {
+        if (ahead >= 3) wait_vm_fenced<3 * NT + 3>();
+        else if (ahead == 2) wait_vm_fenced<2 * NT + 3>();
+        else if (ahead == 1) wait_vm_fenced<NT + 3>();
+        else wait_vm_fenced<0>();
+    } else {
+        if (ahead >= 3) wait_vm_fenced<3 * NT>();
+        else if (ahead == 2) wait_vm_fenced<2 * NT>();
+        else if (ahead == 1) wait_vm_fenced<NT>();
+        else wait_vm_fenced<0>();
+    }
+}
+
+template <int D, int MAXG>
+__global__ __launch_bounds__(kDecThreads, 1) void decode_pv_mfma_kernel(
+    Geom g, SegList sl, int per_split, const bf16_t* __restrict__ Vc, const float* __restrict__ logits,
+    const float* __restrict__ part, int n_splits, float* __restrict__ opart, float* __restrict__ mu,
+    float* __restrict__ lse_out)
+{
+    using St = PvStage<D, MAXG>;
+    constexpr int DB = D / 16;                 // MFMA row blocks over the head dimension
+    constexpr int PPR = D / 8;                 // 16-byte pieces per row
+    constexpr int RPI = 64 / PPR;              // rows per copy instruction
+    __shared__ __attribute__((aligned(1024))) unsigned char ring[kPvWaves][kPvStages][St::kBytes];
+    __shared__ __attribute__((aligned(16))) bf16_t Pt[kPvWaves][MAXG][kPvRows];
+    __shared__ float lse_s[MAXG];
+    static_assert(sizeof(float) * kPvWaves * MAXG * D <= sizeof(ring), "the partial outputs reuse the ring");
+    const int split = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
+    const int bh = b * g.Hkv + hk;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), l = threadIdx.x & 63, n = l & 15, c = l >> 4;
+    const int ncached = sl.n_cached;
+    const size_t lrows = (size_t)ncached + 1;
+    if (threadIdx.x < MAXG) {
+        float v = 0.f;
+        if (threadIdx.x < g.G) {
+            const float* p = part + ((size_t)b * g.Hq + hk * g.G + threadIdx.x) * n_splits * 2;
+            float mm = -INFINITY, ll = 0.f;
+            for (int s = 0; s < n_splits; ++s) ml_merge(mm, ll, p[2 * s], p[2 * s + 1]);
+            v = mm + __logf(ll);
+            if (split == 0) lse_out[(size_t)b * g.Hq + hk * g.G + threadIdx.x] = v;
+        }
+        lse_s[threadIdx.x] = v;
+    }
+    __syncthreads();   // (also: every ordinary load of this kernel has returned before the first copy)
+
+    const int j0 = split * per_split, j1 = min(ncached, j0 + per_split);
+    const float* lbase = logits + logit_index(g, MAXG, lrows, b, hk, 0, 0);
+    const bf16_t* vbh = Vc + (size_t)bh * g.slots * D;
+    float* mubh = mu + (size_t)bh * g.slots;
+    const uint32_t ring_lds = lds_address(&ring[wave][0][0]);
+    unsigned char* ring_w = &ring[wave][0][0];
+
+    // copy addressing of this lane: V copy x brings rows x*RPI + l/PPR, piece l%PPR of the LDS row
+    // holds piece (l%PPR) ^ swizzle(row) of the global row
+    auto issue = [&](const PvTiles& t, int stage) {
+        const int nvalid = min(kPvRows, t.hi - t.r0);          // rows past the end repeat the last one
+        const uint32_t dst = ring_lds + (uint32_t)stage * St::kBytes;
+        const int phys = t.start + (t.r0 - t.seg_first);       // first slot of the tile
+        const bf16_t* vsrc = vbh + (size_t)phys * D;
+#pragma unroll
+        for (int x = 0; x < St::kVCopies; ++x) {
+            const int row = x * RPI + l / PPR;
+            const int piece = (l % PPR) ^ PvSwizzle<D>::of(row);
+            async_copy_1k(vsrc, (uint32_t)((min(row, nvalid - 1) * PPR + piece) * 16),
+                          __builtin_amdgcn_readfirstlane(dst + x * 1024u));
+        }
+        const float* lsrc = lbase + (size_t)t.r0 * MAXG;
+#pragma unroll
+        for (int x = 0; x < St::kLogitCopies; ++x)
+            async_copy_256(lsrc, (uint32_t)(min(x * 64 + l, nvalid * MAXG - 1) * 4),
+                           __builtin_amdgcn_readfirstlane(dst + St::kLgOff + x * 256u));
+        async_copy_256(mubh + phys, (uint32_t)(min(l, nvalid - 1) * 4), __builtin_amdgcn_readfirstlane(dst + St::kMuOff));
+    };
+
+    // transposing reads of this lane: rows 8c + 4*hf + (n>>2), column block db, 8 bytes at element 4*(n&3)
+    int tr_row[2], tr_sw[2];
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+        tr_row[hf] = 8 * c + 4 * hf + (n >> 2);
+        tr_sw[hf] = PvSwizzle<D>::of(tr_row[hf]);
+    }
+
+    df32x4_t acc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) acc[db] = df32x4_t{0.f, 0.f, 0.f, 0.f};
+    const float beta = g.beta, omb = 1.f - g.beta;
+    const bool use_max = g.head_reduce == CASCADE_REDUCE_MAX;
+    float lse_r[MAXG];
+#pragma unroll
+    for (int hh = 0; hh < MAXG; ++hh) lse_r[hh] = lse_s[hh];
+
+    PvTiles prod, cons;
+    prod.begin(sl, j0, j1, wave);
+    cons = prod;
+    int issued = 0, done = 0;
+    for (; issued < kPvStages && prod.valid; ++issued) {
+        issue(prod, issued);
+        prod.next(sl, j0, j1, wave);
+    }
+    while (cons.valid) {
+        const int stage = done % kPvStages;
+        pv_wait<St::kCopies>(issued - done - 1, done >= kPvStages - 1);
+        const unsigned char* sp = ring_w + stage * St::kBytes;
+        const int nvalid = min(kPvRows, cons.hi - cons.r0);
+        // probabilities of the tile: lane x < 32 takes row x and all heads
+        if (l < kPvRows) {
+            const float* lg = reinterpret_cast<const float*>(sp + St::kLgOff) + l * MAXG;
+            float red = 0.f;
+#pragma unroll
+            for (int hh = 0; hh < MAXG; ++hh) {
+                const float p = (hh < g.G && l < nvalid) ? __expf(lg[hh] - lse_r[hh]) : 0.f;
+                red = use_max ? fmaxf(red, p) : red + p;
+                Pt[wave][hh][l] = (bf16_t)(dec_pack_bf16(p, 0.f) & 0xFFFFu);
+            }
+            if (l < nvalid) {   // lane 0 always stores: the operation count of pv_wait relies on it
+                const float old = reinterpret_cast<const float*>(sp + St::kMuOff)[l];
+                const int phys = cons.start + (cons.r0 - cons.seg_first);
+                counted_store_f32(mubh + phys, (uint32_t)(l * 4), beta * old + omb * (use_max ? red : red / (float)g.G));
+            }
+        }
+        __builtin_amdgcn_wave_barrier();   // LDS accesses of one wave are executed in order
+        DFrag pf;
+        pf.u = du32x4_t{0u, 0u, 0u, 0u};
+        if (n < MAXG) pf.u = *reinterpret_cast<const du32x4_t*>(&Pt[wave][n][8 * c]);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            DFrag vf;
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+                const int piece = (2 * db + ((n & 3) >> 1)) ^ tr_sw[hf];
+                const uint2 r = pv_read_tr16(sp + tr_row[hf] * (D * 2) + piece * 16 + (n & 1) * 8);
+                vf.u[2 * hf] = r.x;
+                vf.u[2 * hf + 1] = r.y;
+            }
+            acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf.v, acc[db], 0, 0, 0);
+        }
+        wait_lds_reads();                  // the stage may be overwritten now
+        ++done;
+        cons.next(sl, j0, j1, wave);
+        if (prod.valid) {
+            issue(prod, stage);
+            ++issued;
+            prod.next(sl, j0, j1, wave);
+        }
+    }
+    wait_vm_fenced<0>();
+    __syncthreads();                       // every wave is done with its ring
+    // this lane holds, for head n, elements 16*db + 4*c + j of the wave's partial output
+    float* osum = reinterpret_cast<float*>(&ring[0][0][0]);   // [wave][MAXG][D]
+    if (n < MAXG) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+            *reinterpret_cast<df32x4_t*>(&osum[((size_t)wave * MAXG + n) * D + 16 * db + 4 * c]) = acc[db];
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < g.G * D; idx += kDecThreads) {
+        const int hh = idx / D, e = idx % D;
+        float s = 0.f;
+        for (int w = 0; w < kPvWaves; ++w) s += osum[((size_t)w * MAXG + hh) * D + e];
+        opart[(((size_t)b * g.Hq + hk * g.G + hh) * n_splits + split) * D + e] = s;
+    }
+}
+
 // ------------------------------------------------------------------ launchers
 
 static int per_split_of(const DevBuffers& bf, int n)
@@ -589,6 +840,22 @@ void launch_decode_qk(const Geom& g, int dtype, const DevBuffers& b, const SegLi
 
 void launch_decode_pv(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, hipStream_t s)
 {
+    static const bool valu_only = getenv("CASCADE_KV_DECODE_PV_VALU") != nullptr;
+    if (dtype == CASCADE_BF16 && !valu_only) {
+        const dim3 grid(b.dec_splits, g.Hkv, g.B), block(kDecThreads);
+        const int ps = per_split_of(b, sl.n_cached);
+#define CKV_PV_MFMA(D, MG)                                                                                 \
+    hipLaunchKernelGGL((decode_pv_mfma_kernel<D, MG>), grid, block, 0, s, g, sl, ps, (const bf16_t*)b.Vc, b.logits, \
+                       b.part, b.dec_splits, b.opart, b.mu, b.lse)
+        const int mg = maxg_of(g);
+        if (g.d == 128) {
+            if (mg == 1) CKV_PV_MFMA(128, 1); else if (mg == 2) CKV_PV_MFMA(128, 2); else if (mg == 4) CKV_PV_MFMA(128, 4); else CKV_PV_MFMA(128, 8);
+        } else {
+            if (mg == 1) CKV_PV_MFMA(64, 1); else if (mg == 2) CKV_PV_MFMA(64, 2); else if (mg == 4) CKV_PV_MFMA(64, 4); else CKV_PV_MFMA(64, 8);
+        }
+#undef CKV_PV_MFMA
+        return;
+    }
     CKV_DISPATCH(pv_typed, g, b, sl, s);
 }
 

@@ -103,11 +103,13 @@ def test_prefill_one_step_ahead(oracle_mod, case):
     run.close()
 
 
-@pytest.mark.parametrize("dtype,d", [(B.CASCADE_F32, 64), (B.CASCADE_BF16, 128)])
-def test_prefill_then_decode(oracle_mod, dtype, d):
-    """A decode step has the semantics of a chunk of one token (Eq. 2)."""
+@pytest.mark.parametrize("dtype,d,hq,hkv", [(B.CASCADE_F32, 64, 8, 2), (B.CASCADE_BF16, 128, 8, 2),
+                                            (B.CASCADE_BF16, 64, 8, 1), (B.CASCADE_BF16, 64, 2, 2),
+                                            (B.CASCADE_BF16, 128, 4, 2), (B.CASCADE_BF16, 128, 3, 1)])
+def test_prefill_then_decode(oracle_mod, dtype, d, hq, hkv):
+    """A decode step has the semantics of a chunk of one token (Eq. 2); group sizes 1, 2, 3, 4, 8."""
     from gpu_harness import ParityRun
-    cfg = B.make_config(batch=2, n_q_heads=8, n_kv_heads=2, head_dim=d, dtype=dtype, n_sink=4,
+    cfg = B.make_config(batch=2, n_q_heads=hq, n_kv_heads=hkv, head_dim=d, dtype=dtype, n_sink=4,
                         cascade_sizes=[20, 12, 12], ema_beta=0.9, rope_base=10000.0, max_chunk=64,
                         keep_update_scores=1)
     tol_out, tol_score = _tolerances(cfg)
@@ -121,7 +123,7 @@ def test_prefill_then_decode(oracle_mod, dtype, d):
         rep = run.step(q, k, v, decode=(kind == "d"))
         assert rep.replay_exact, i
         worst_out, worst_score = max(worst_out, rep.out_err), max(worst_score, rep.score_err)
-    print(f"prefill_then_decode {dtype}: out {worst_out:.3e} score {worst_score:.3e}")
+    print(f"prefill_then_decode {dtype} d={d} {hq}/{hkv}: out {worst_out:.3e} score {worst_score:.3e}")
     assert worst_out <= tol_out and worst_score <= tol_score
     run.close()
 
