@@ -555,17 +555,17 @@ __device__ inline uint2 pv_read_tr16(const unsigned char* p)
     return __builtin_bit_cast(uint2, r);
 }
 
-// The tiles of one wave in order: inside every segment's part of [j0, j1) the waves take tiles
-// of 32 rows in turn.
-struct PvTiles {
-    int si, seg_first, r0, hi, start;
+// The tiles of one wave in order: inside every segment's part of [j0, j1) the tiles of 32 rows
+// first, first + stride, ... counted from the start of that part.
+struct WaveTiles {
+    int si, seg_first, r0, hi, start, first, stride;
     bool valid;
-    __device__ void seek(const SegList& sl, int j0, int j1, int wave)
+    __device__ void seek(const SegList& sl, int j0, int j1)
     {
         while (si < sl.n) {
             const int len = sl.s[si].len;
             hi = min(j1, seg_first + len);
-            r0 = max(j0, seg_first) + wave * kPvRows;
+            r0 = max(j0, seg_first) + first;
             start = sl.s[si].start;
             if (r0 < hi) { valid = true; return; }
             seg_first += len;
@@ -573,18 +573,19 @@ struct PvTiles {
         }
         valid = false;
     }
-    __device__ void begin(const SegList& sl, int j0, int j1, int wave)
+    __device__ void begin(const SegList& sl, int j0, int j1, int first_row, int row_stride)
     {
         si = 0; seg_first = 0; r0 = 0; hi = 0; start = 0;
-        seek(sl, j0, j1, wave);
+        first = first_row; stride = row_stride;
+        seek(sl, j0, j1);
     }
-    __device__ void next(const SegList& sl, int j0, int j1, int wave)
+    __device__ void next(const SegList& sl, int j0, int j1)
     {
-        r0 += kPvWaves * kPvRows;
+        r0 += stride;
         if (r0 >= hi) {
             seg_first += sl.s[si].len;
             ++si;
-            seek(sl, j0, j1, wave);
+            seek(sl, j0, j1);
         }
     }
 };
@@ -600,21 +601,23 @@ struct PvStage {
     static constexpr int kCopies = kVCopies + kLogitCopies + 1;   // vector memory operations per tile
 };
 
-// Waits until the copies of the oldest tile in flight have landed: `ahead` later tiles have been
-// issued after it, and (in steady state) kPvStages - 1 score stores.  Counting fewer operations
-// than are really outstanding only waits longer.
-template <int NT> __device__ inline void pv_wait(int ahead, bool steady)
+// Waits until the copies of the oldest tile in flight have landed: `ahead` later tiles (NC copies
+// each) have been issued after it, and (in steady state) the stores of kPvStages - 1 tiles (NS
+// each).  Counting fewer operations than are really outstanding only waits longer.
+template <int NC, int NS> __device__ inline void ring_wait(int ahead, bool steady)
 {
     static_assert(kPvStages == 4, "cases below");
+    constexpr int ST = (kPvStages - 1) * NS;
+    static_assert(3 * NC + ST < 64, "vmcnt range");
     if (steady) {
-        if (ahead >= 3) wait_vm_fenced<3 * NT + 3>();
-        else if (ahead == 2) wait_vm_fenced<2 * NT + 3>();
-        else if (ahead == 1) wait_vm_fenced<NT + 3>();
+        if (ahead >= 3) wait_vm_fenced<3 * NC + ST>();
+        else if (ahead == 2) wait_vm_fenced<2 * NC + ST>();
+        else if (ahead == 1) wait_vm_fenced<NC + ST>();
         else wait_vm_fenced<0>();
     } else {
-        if (ahead >= 3) wait_vm_fenced<3 * NT>();
-        else if (ahead == 2) wait_vm_fenced<2 * NT>();
-        else if (ahead == 1) wait_vm_fenced<NT>();
+        if (ahead >= 3) wait_vm_fenced<3 * NC>();
+        else if (ahead == 2) wait_vm_fenced<2 * NC>();
+        else if (ahead == 1) wait_vm_fenced<NC>();
         else wait_vm_fenced<0>();
     }
 }
@@ -660,7 +663,7 @@ __global__ __launch_bounds__(kDecThreads, 1) void decode_pv_mfma_kernel(
 
     // copy addressing of this lane: V copy x brings rows x*RPI + l/PPR, piece l%PPR of the LDS row
     // holds piece (l%PPR) ^ swizzle(row) of the global row
-    auto issue = [&](const PvTiles& t, int stage) {
+    auto issue = [&](const WaveTiles& t, int stage) {
         const int nvalid = min(kPvRows, t.hi - t.r0);          // rows past the end repeat the last one
         const uint32_t dst = ring_lds + (uint32_t)stage * St::kBytes;
         const int phys = t.start + (t.r0 - t.seg_first);       // first slot of the tile
@@ -697,17 +700,17 @@ __global__ __launch_bounds__(kDecThreads, 1) void decode_pv_mfma_kernel(
 #pragma unroll
     for (int hh = 0; hh < MAXG; ++hh) lse_r[hh] = lse_s[hh];
 
-    PvTiles prod, cons;
-    prod.begin(sl, j0, j1, wave);
+    WaveTiles prod, cons;
+    prod.begin(sl, j0, j1, wave * kPvRows, kPvWaves * kPvRows);
     cons = prod;
     int issued = 0, done = 0;
     for (; issued < kPvStages && prod.valid; ++issued) {
         issue(prod, issued);
-        prod.next(sl, j0, j1, wave);
+        prod.next(sl, j0, j1);
     }
     while (cons.valid) {
         const int stage = done % kPvStages;
-        pv_wait<St::kCopies>(issued - done - 1, done >= kPvStages - 1);
+        ring_wait<St::kCopies, 1>(issued - done - 1, done >= kPvStages - 1);
         const unsigned char* sp = ring_w + stage * St::kBytes;
         const int nvalid = min(kPvRows, cons.hi - cons.r0);
         // probabilities of the tile: lane x < 32 takes row x and all heads
@@ -720,7 +723,7 @@ __global__ __launch_bounds__(kDecThreads, 1) void decode_pv_mfma_kernel(
                 red = use_max ? fmaxf(red, p) : red + p;
                 Pt[wave][hh][l] = (bf16_t)(dec_pack_bf16(p, 0.f) & 0xFFFFu);
             }
-            if (l < nvalid) {   // lane 0 always stores: the operation count of pv_wait relies on it
+            if (l < nvalid) {   // lane 0 always stores: the operation count of ring_wait relies on it
                 const float old = reinterpret_cast<const float*>(sp + St::kMuOff)[l];
                 const int phys = cons.start + (cons.r0 - cons.seg_first);
                 counted_store_f32(mubh + phys, (uint32_t)(l * 4), beta * old + omb * (use_max ? red : red / (float)g.G));
@@ -744,11 +747,11 @@ __global__ __launch_bounds__(kDecThreads, 1) void decode_pv_mfma_kernel(
         }
         wait_lds_reads();                  // the stage may be overwritten now
         ++done;
-        cons.next(sl, j0, j1, wave);
+        cons.next(sl, j0, j1);
         if (prod.valid) {
             issue(prod, stage);
             ++issued;
-            prod.next(sl, j0, j1, wave);
+            prod.next(sl, j0, j1);
         }
     }
     wait_vm_fenced<0>();
@@ -766,6 +769,196 @@ __global__ __launch_bounds__(kDecThreads, 1) void decode_pv_mfma_kernel(
         float s = 0.f;
         for (int w = 0; w < kPvWaves; ++w) s += osum[((size_t)w * MAXG + hh) * D + e];
         opart[(((size_t)b * g.Hq + hk * g.G + hh) * n_splits + split) * D + e] = s;
+    }
+}
+
+// ------------------------------------------------------------------ QK, bf16: MFMA fed from LDS
+//
+// The same streaming structure for K: 32-row tiles through a private ring per wave, the A
+// fragments (16 keys x 8 elements per lane) read with ds_read_b128.  The 16-byte pieces of a
+// staged row are permuted so that the 16 rows of a fragment read fall into different banks.
+// The rotated, scaled query fragments of every rotation the step uses are computed once per
+// workgroup and kept in LDS, so the loop issues no ordinary load and no wait of the compiler's
+// drains the ring.
+template <int D> struct QkSwizzle;
+template <> struct QkSwizzle<128> { __device__ static int of(int row) { return row & 15; } };
+template <> struct QkSwizzle<64> { __device__ static int of(int row) { return (row >> 1) & 7; } };
+
+template <int MAXG> struct QkLimits {
+    static constexpr int kRotations = 96 / MAXG < kMaxSegments ? 96 / MAXG : kMaxSegments;   // query copies held in LDS
+};
+
+template <int D, int MAXG>
+__global__ __launch_bounds__(kDecThreads, 1) void decode_qk_stream_kernel(
+    Geom g, SegList sl, int per_split, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k_new,
+    const bf16_t* __restrict__ Kr, const float2* __restrict__ rope, float* __restrict__ logits,
+    float* __restrict__ part, int n_splits)
+{
+    constexpr int KS = D / 32;                 // MFMA steps over the head dimension
+    constexpr int PPR = D / 8;                 // 16-byte pieces per row
+    constexpr int RPI = 64 / PPR;              // rows per copy instruction
+    constexpr int kTileBytes = kPvRows * D * 2;
+    constexpr int NC = kTileBytes / 1024;      // copies per tile
+    constexpr int NS = (kPvRows * MAXG * 4 + 255) / 256;   // logit stores per tile
+    constexpr int NR = QkLimits<MAXG>::kRotations;
+    __shared__ __attribute__((aligned(1024))) unsigned char ring[kPvWaves][kPvStages][kTileBytes];
+    __shared__ __attribute__((aligned(16))) du32x4_t qfr[NR][KS][4][MAXG];
+    __shared__ __attribute__((aligned(16))) float stage[kPvWaves][kPvRows * MAXG];   // a tile's logits, [row][head]
+    __shared__ float red_m[kPvWaves][16], red_l[kPvWaves][16];
+    const int split = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
+    const int bh = b * g.Hkv + hk;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), l = threadIdx.x & 63, n = l & 15, c = l >> 4;
+    const int ncached = sl.n_cached;
+    const size_t lrows = (size_t)ncached + 1;
+    const bool head_ok = n < g.G;
+    float* lbase = logits + logit_index(g, MAXG, lrows, b, hk, 0, 0);
+
+    // B operands: every rotation of the group's queries, scaled, as bf16 (zero for padded heads)
+    for (int idx = threadIdx.x; idx < sl.n_qvar * KS * 4 * MAXG; idx += kDecThreads) {
+        const int hh = idx % MAXG, cc = (idx / MAXG) % 4, ks = (idx / (4 * MAXG)) % KS, v = idx / (4 * MAXG * KS);
+        du32x4_t f = {0u, 0u, 0u, 0u};
+        if (hh < g.G) {
+            const bf16_t* qh = q + ((size_t)b * g.Hq + hk * g.G + hh) * D;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const int e = ks * 32 + cc * 8 + 2 * x;
+                f[x] = dec_pack_bf16(q_rot_elem<bf16_t>(qh, rope, sl.qrot0[v], D / 2, e, g.scale),
+                                     q_rot_elem<bf16_t>(qh, rope, sl.qrot0[v], D / 2, e + 1, g.scale));
+            }
+        }
+        qfr[v][ks][cc][hh] = f;
+    }
+    __syncthreads();   // (also: every ordinary load so far has returned before the first copy)
+
+    const int j0 = split * per_split, j1 = min(ncached, j0 + per_split);
+    const bf16_t* kbh = Kr + (size_t)bh * g.slots * D;
+    const uint32_t ring_lds = lds_address(&ring[wave][0][0]);
+    const unsigned char* ring_w = &ring[wave][0][0];
+
+    auto issue = [&](const WaveTiles& t, int stg) {
+        const int nvalid = min(kPvRows, t.hi - t.r0);          // rows past the end repeat the last one
+        const uint32_t dst = ring_lds + (uint32_t)stg * kTileBytes;
+        const bf16_t* ksrc = kbh + (size_t)(t.start + (t.r0 - t.seg_first)) * D;
+#pragma unroll
+        for (int x = 0; x < NC; ++x) {
+            const int row = x * RPI + l / PPR;
+            const int piece = (l % PPR) ^ QkSwizzle<D>::of(row);
+            async_copy_1k(ksrc, (uint32_t)((min(row, nvalid - 1) * PPR + piece) * 16),
+                          __builtin_amdgcn_readfirstlane(dst + x * 1024u));
+        }
+    };
+
+    // fragment reads of this lane: key group gi, step ks: row 16*gi + n, piece 4*ks + c
+    int a_off[2][KS];
+#pragma unroll
+    for (int gi = 0; gi < 2; ++gi)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int row = 16 * gi + n;
+            a_off[gi][ks] = row * (D * 2) + (((4 * ks + c) ^ QkSwizzle<D>::of(row)) * 16);
+        }
+
+    float m = -INFINITY, lsum = 0.f;
+    DFrag qf[KS];
+    int q_si = -1;
+    WaveTiles prod, cons;
+    prod.begin(sl, j0, j1, wave * kPvRows, kPvWaves * kPvRows);
+    cons = prod;
+    int issued = 0, done = 0;
+    for (; issued < kPvStages && prod.valid; ++issued) {
+        issue(prod, issued);
+        prod.next(sl, j0, j1);
+    }
+    while (cons.valid) {
+        const int stg = done % kPvStages;
+        if (cons.si != q_si) {             // uniform for the wave
+            q_si = cons.si;
+            const int v = sl.s[q_si].qvar;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                qf[ks].u = du32x4_t{0u, 0u, 0u, 0u};
+                if (n < MAXG) qf[ks].u = qfr[v][ks][c][n];
+            }
+        }
+        ring_wait<NC, NS>(issued - done - 1, done >= kPvStages - 1);
+        const unsigned char* sp = ring_w + stg * kTileBytes;
+        const int nvalid = min(kPvRows, cons.hi - cons.r0);
+#pragma unroll
+        for (int gi = 0; gi < 2; ++gi) {
+            DFrag kf[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) kf[ks].u = *reinterpret_cast<const du32x4_t*>(sp + a_off[gi][ks]);
+            df32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks].v, qf[ks].v, acc, 0, 0, 0);
+            // this lane: head n, tile rows 16*gi + 4*c + {0..3}
+            const int rb = gi * 16 + 4 * c;
+            if (n < MAXG) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) stage[wave][(rb + j) * MAXG + n] = acc[j];
+            }
+            if (head_ok) {
+                // one rescaling per four logits: the running maximum rarely moves
+                float mx = m;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (rb + j < nvalid) mx = fmaxf(mx, acc[j]);
+                if (mx > m) {   // (also keeps -inf - -inf out of the arithmetic)
+                    lsum *= __expf(m - mx);
+                    m = mx;
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (rb + j < nvalid) lsum += __expf(acc[j] - m);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();   // LDS accesses of one wave are executed in order
+        // the tile's logits leave as contiguous runs; every store is issued by all lanes (lanes past
+        // the end repeat the last logit), the operation count of ring_wait relies on it
+        float* ltile = lbase + (size_t)cons.r0 * MAXG;
+#pragma unroll
+        for (int x = 0; x < NS; ++x) {
+            const int idx = min(x * 64 + l, nvalid * MAXG - 1);
+            counted_store_f32(ltile, (uint32_t)(idx * 4), stage[wave][idx]);
+        }
+        wait_lds_reads();                  // the stage may be overwritten now
+        ++done;
+        cons.next(sl, j0, j1);
+        if (prod.valid) {
+            issue(prod, stg);
+            ++issued;
+            prod.next(sl, j0, j1);
+        }
+    }
+    wait_vm_fenced<0>();
+    if (split == 0 && wave == 0) {
+        // own key: <R(n) q, R(n) k> = <q, k>; lanes c = 0 of the valid heads take it
+        if (head_ok && c == 0) {
+            const bf16_t* qh = q + ((size_t)b * g.Hq + hk * g.G + n) * D;
+            const bf16_t* kn = k_new + ((size_t)b * g.Hkv + hk) * D;
+            float acc = 0.f;
+            for (int e = 0; e < D; ++e) acc += bf16_to_f32(qh[e]) * bf16_to_f32(kn[e]);
+            acc *= g.scale;
+            lbase[(size_t)ncached * MAXG + n] = acc;
+            const float mn = fmaxf(m, acc);
+            lsum = lsum * __expf(m - mn) + __expf(acc - mn);
+            m = mn;
+        }
+    }
+    // combine the four lane groups of a head, then the waves
+#pragma unroll
+    for (int w = 16; w < 64; w <<= 1) {
+        const float m2 = __shfl_xor(m, w, 64), l2 = __shfl_xor(lsum, w, 64);
+        ml_merge(m, lsum, m2, l2);
+    }
+    if (c == 0) { red_m[wave][n] = m; red_l[wave][n] = lsum; }
+    __syncthreads();
+    if (threadIdx.x < g.G) {
+        float mm = -INFINITY, ll = 0.f;
+        for (int w = 0; w < kPvWaves; ++w) ml_merge(mm, ll, red_m[w][threadIdx.x], red_l[w][threadIdx.x]);
+        float* p = part + (((size_t)b * g.Hq + hk * g.G + threadIdx.x) * n_splits + split) * 2;
+        p[0] = mm;
+        p[1] = ll;
     }
 }
 
@@ -823,10 +1016,20 @@ void launch_decode_qk(const Geom& g, int dtype, const DevBuffers& b, const SegLi
     if (dtype == CASCADE_BF16) {
         const dim3 grid(b.dec_splits, g.Hkv, g.B), block(kDecThreads);
         const int ps = per_split_of(b, sl.n_cached);
-#define CKV_QK_MFMA(D, MG)                                                                                        \
-    hipLaunchKernelGGL((decode_qk_mfma_kernel<D, MG>), grid, block, 0, s, g, sl, ps, (const bf16_t*)q, (const bf16_t*)k, \
-                       (const bf16_t*)b.Kr, b.rope, b.logits, b.part, b.dec_splits)
+        static const bool direct_only = getenv("CASCADE_KV_DECODE_QK_DIRECT") != nullptr;
         const int mg = maxg_of(g);
+        const int rotations = 96 / mg < kMaxSegments ? 96 / mg : kMaxSegments;
+        // the streaming kernel keeps every rotation of the queries in LDS
+        const bool stream = !direct_only && sl.n_qvar <= rotations;
+#define CKV_QK_MFMA(D, MG)                                                                                        \
+    do {                                                                                                          \
+        if (stream)                                                                                               \
+            hipLaunchKernelGGL((decode_qk_stream_kernel<D, MG>), grid, block, 0, s, g, sl, ps, (const bf16_t*)q,    \
+                               (const bf16_t*)k, (const bf16_t*)b.Kr, b.rope, b.logits, b.part, b.dec_splits);    \
+        else                                                                                                      \
+            hipLaunchKernelGGL((decode_qk_mfma_kernel<D, MG>), grid, block, 0, s, g, sl, ps, (const bf16_t*)q,      \
+                               (const bf16_t*)k, (const bf16_t*)b.Kr, b.rope, b.logits, b.part, b.dec_splits);    \
+    } while (0)
         if (g.d == 128) {
             if (mg == 1) CKV_QK_MFMA(128, 1); else if (mg == 2) CKV_QK_MFMA(128, 2); else if (mg == 4) CKV_QK_MFMA(128, 4); else CKV_QK_MFMA(128, 8);
         } else {
