@@ -191,18 +191,6 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
                 s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[ks].v, s[kb], 0, 0, 0);
             }
     };
-    // O^T += V^T P^T for the packed V tile at Vtile: the A operand (row = column of V, 8 keys per
-    // lane in the order of the probabilities) is one chunk of the tile
-    auto pv_tile = [&](const bf16_t* Vtile) {
-#pragma unroll
-        for (int g16 = 0; g16 < 4; ++g16)
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                Frag vf;
-                vf.u = *reinterpret_cast<const u32x4_t*>(Vtile + voff[g16] + db * (32 * kBN));
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[g16].v, o[db], 0, 0, 0);
-            }
-    };
     // The vector block of one tile: mask the keys a query may not see (past the end of the
     // segment; later chunk tokens), take the row maximum of S^T (relative to m_run), raise m_run only
     // when that exceeds kRescaleLog2 (the probabilities then stay below 2^kRescaleLog2, and most

@@ -26,6 +26,7 @@ struct DevBuffers {
     void* Vt;        // [B,Hkv,vt_tiles,d,64] the same for V, every tile transposed
     float* lse;      // [B,Hq,max_chunk] log-sum-exp of every query row (natural log, scaled logits)
     float* mu_chunk; // [B,Hkv,max_chunk] scores of the chunk's tokens
+    float* negt;     // [B,Hq,max_chunk+64] bf16 MFMA path: exponent offsets of the score sums (-inf: row does not contribute)
     int32_t* offers; // [B,Hkv,2,max_chunk]
     int32_t* winners;// [B,Hkv,N,max_chunk+1]
     // decode scratch

@@ -6,6 +6,7 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include "async_copy.h"
 #include "mfma_util.h"
 
 namespace ckv {
@@ -14,26 +15,52 @@ namespace ckv {
 
 // Key-stationary: a wave keeps 64 keys (two 32-key blocks) in registers as the B operand and
 // runs the last `tail` query rows of every head of the group past them (S = Q K^T, one lane owns
-// one key column per block).  The rows of one head are staged through LDS in groups of 256 and
-// shared by the four waves.  With the stored log-sum-exp the probabilities are exact:
+// one key column per block).  With the stored log-sum-exp the probabilities are exact:
 // p = 2^(s - t[row]) (the queries carry the softmax scale and log2 e) with
-// t = lse*log2(e) - log2(weight of the row), so a row that does not
-// contribute has t = +inf.  Column sums are an in-lane sum plus one exchange with lane l^32;
-// no atomics, so results are identical from run to run.
+// t = lse*log2(e) - log2(weight of the row).  Column sums are an in-lane sum plus one exchange
+// with lane l^32; no atomics, so results are identical from run to run.
+//
+// The query rows reach LDS by asynchronous copies through a ring of three 64-row stages shared
+// by the workgroup (one barrier per stage, the copies of the next two stages in flight while a
+// stage is used; three workgroups per CU), running on across the heads of the group, so no wave
+// waits for a staging round trip.  The exponent offsets come from a small table
+// negt[head][row] = -t (-inf for rows that do not contribute, and for the padding behind the
+// chunk), which the accumulators start from: a probability is then one v_exp_f32 of an
+// accumulator.
 constexpr int kScoreThreads = 256;
 constexpr int kScoreKeys = 256;    // keys per workgroup (4 waves x 2 blocks of 32)
-constexpr int kScoreRows = 256;    // query rows staged per pass
+constexpr int kStStages = 3;
+constexpr int kStRows = 64;
+
+__global__ void score_offsets_kernel(int Q, int qpad, int tail, const float* __restrict__ lse,
+                                     const float* __restrict__ wrow, float* __restrict__ negt)
+{
+    const int head = blockIdx.y;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= qpad) return;
+    float v = -INFINITY;
+    if (i < Q && i >= Q - tail) v = __log2f(wrow[Q - 1 - i]) - lse[(size_t)head * Q + i] * 1.4426950408889634f;
+    negt[(size_t)head * qpad + i] = v;
+}
+
+template <int D> struct ScoreSwz {   // permutation of the 16-byte pieces of a staged row
+    __device__ static int of(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
+};
 
 template <int D>
-__global__ __launch_bounds__(kScoreThreads, 2) void score_mfma_kernel(
-    Geom g, SegList sl, int Q, int qstride, int tail, float decay, const bf16_t* __restrict__ Qr,
-    const bf16_t* __restrict__ Kr, const bf16_t* __restrict__ Krc, const float* __restrict__ lse,
-    const float* __restrict__ wrow, float* __restrict__ mu, float* __restrict__ mu_chunk)
+__global__ __launch_bounds__(kScoreThreads, 3) void score_stream_kernel(
+    Geom g, SegList sl, int Q, int qstride, int tail, int qpad, float decay, const bf16_t* __restrict__ Qr,
+    const bf16_t* __restrict__ Kr, const bf16_t* __restrict__ Krc, const float* __restrict__ negt,
+    float* __restrict__ mu, float* __restrict__ mu_chunk)
 {
     constexpr int KS = D / 16;
-    constexpr int QSTR = D + 8;
-    __shared__ __attribute__((aligned(16))) bf16_t Qs[kScoreRows * QSTR];
-    __shared__ __attribute__((aligned(16))) float ts[kScoreRows];
+    constexpr int PPR = D / 8;                       // 16-byte pieces per row
+    constexpr int RPI = 64 / PPR;                    // rows per copy instruction
+    constexpr int kStageBytes = kStRows * D * 2;
+    constexpr int NCW = kStageBytes / 1024 / 4;      // row copies per wave and stage
+    constexpr int NOPS = NCW + 1;                    // vector memory operations per wave and stage
+    __shared__ __attribute__((aligned(1024))) unsigned char ring[kStStages][kStageBytes];
+    __shared__ __attribute__((aligned(256))) float tneg[kStStages][4][kStRows];   // every wave keeps its own copy
     const int BH = g.B * g.Hkv;
     const int bh = blockIdx.x % BH;
     int tile = blockIdx.x / BH;
@@ -47,7 +74,7 @@ __global__ __launch_bounds__(kScoreThreads, 2) void score_mfma_kernel(
     }
     if (si >= sl.n) return;       // uniform for the workgroup
     const Seg sg = sl.s[si];
-    const int tid = threadIdx.x, wave = tid >> 6, l = tid & 63, l32 = l & 31, half = l >> 5;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, l32 = l & 31, half = l >> 5;
     const int wave_k0 = tile * kScoreKeys + wave * 64;       // first key of this wave inside the segment
 
     // this wave's keys as B operands (rows past the end of the segment repeat its last row)
@@ -61,85 +88,105 @@ __global__ __launch_bounds__(kScoreThreads, 2) void score_mfma_kernel(
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) kf[kb][ks].u = *reinterpret_cast<const u32x4_t*>(krow + ks * 16 + half * 8);
     }
+    // fragment reads of this lane: row block rb, step ks: row 32*rb + l32, piece 2*ks + half
+    int a_off[2][KS];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int row = 32 * rb + l32;
+            a_off[rb][ks] = row * (D * 2) + (((2 * ks + half) ^ ScoreSwz<D>::of(row)) * 16);
+        }
 
-    const int i_first = Q - tail;                             // first row that contributes
-    const int n_pass = (tail + kScoreRows - 1) / kScoreRows;
-    float red[2] = {0.f, 0.f};
-    for (int hh = 0; hh < g.G; ++hh) {
-        const int h = hk * g.G + hh;
+    const int i_first = Q - tail;                              // first row that contributes
+    const int spp = (tail + kStRows - 1) / kStRows;            // stages per head
+    const int T = g.G * spp;
+    const uint32_t ring_lds = lds_address(&ring[0][0]), tneg_lds = lds_address(&tneg[0][0][0]);
+    // the keys are in registers before the first copy is issued (a wait for them inside the loop
+    // would also wait for every copy in flight)
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(kf[kb][ks].u));
+    auto issue = [&](int s) {
+        const int hh = s / spp, i_base = i_first + (s - hh * spp) * kStRows;
+        const int h = hk * g.G + hh, slot = s % kStStages;
         const bf16_t* qbase = Qr + (((size_t)sg.qvar * g.B + b) * g.Hq + h) * (size_t)Q * D;
-        const float* lrow = lse + ((size_t)b * g.Hq + h) * Q;
-        float colsum[2] = {0.f, 0.f};
-        for (int ps = 0; ps < n_pass; ++ps) {
-            const int i_base = i_first + ps * kScoreRows;               // passes start at the first contributing row
-            const int rows = min(kScoreRows, Q - i_base);               // the last pass may be short
-            __syncthreads();                                            // the previous pass has been consumed
-            // stage the rows of this pass (16-byte pieces) and their exponent offsets.  A full pass
-            // issues all its loads before the first store; a short one (the last) stages only whole
-            // blocks of 32 rows, rows past its end repeating the last row.
-            if (rows == kScoreRows) {
-                u32x4_t buf[kScoreRows * D / 8 / kScoreThreads];
 #pragma unroll
-                for (int x = 0; x < kScoreRows * D / 8 / kScoreThreads; ++x) {
-                    const int p = tid + x * kScoreThreads;
-                    buf[x] = *reinterpret_cast<const u32x4_t*>(qbase + (size_t)(i_base + p / (D / 8)) * D + (p % (D / 8)) * 8);
-                }
+        for (int y = 0; y < NCW; ++y) {
+            const int x = wave * NCW + y;
+            const int row = x * RPI + l / PPR;
+            const int piece = (l % PPR) ^ ScoreSwz<D>::of(row);
+            async_copy_1k(qbase, (uint32_t)((min(i_base + row, Q - 1) * PPR + piece) * 16),
+                          __builtin_amdgcn_readfirstlane(ring_lds + slot * kStageBytes + x * 1024));
+        }
+        async_copy_256(negt + ((size_t)b * g.Hq + h) * qpad + i_base, (uint32_t)(l * 4),
+                       __builtin_amdgcn_readfirstlane(tneg_lds + (uint32_t)((slot * 4 + wave) * kStRows * 4)));
+    };
+
+    int issued = 0;
+    for (; issued < kStStages - 1 && issued < T; ++issued) issue(issued);
+    float red[2] = {0.f, 0.f}, colsum[2] = {0.f, 0.f};
+    int hh = 0, sp = 0;                                         // stage s = stage sp of head hh
+    for (int s = 0; s < T; ++s) {
+        const int ahead = issued - s - 1;                       // stages issued after stage s
+        static_assert(kStStages == 3 || kStStages == 4, "cases below");
+        if (kStStages == 4 && ahead >= 2) wait_vm<2 * NOPS>();
+        else if (ahead >= 1) wait_vm<NOPS>();
+        else wait_vm<0>();
+        wg_barrier();    // stage s is complete for every wave, and every wave has left stage s - 1
+        if (issued < T) { issue(issued); ++issued; }            // into the slot of stage s - 1
+        const int slot = s % kStStages;
+        const int i_base = i_first + sp * kStRows;
+        const int rows = min(kStRows, Q - i_base);
+        const unsigned char* qs = &ring[slot][0];
 #pragma unroll
-                for (int x = 0; x < kScoreRows * D / 8 / kScoreThreads; ++x) {
-                    const int p = tid + x * kScoreThreads;
-                    *reinterpret_cast<u32x4_t*>(&Qs[(p / (D / 8)) * QSTR + (p % (D / 8)) * 8]) = buf[x];
-                }
-            } else {
-                for (int p = tid; p < ((rows + 31) & ~31) * (D / 8); p += kScoreThreads) {
-                    const int r = p / (D / 8), c8 = p % (D / 8);
-                    *reinterpret_cast<u32x4_t*>(&Qs[r * QSTR + c8 * 8]) =
-                        *reinterpret_cast<const u32x4_t*>(qbase + (size_t)min(i_base + r, Q - 1) * D + c8 * 8);
-                }
+        for (int rb = 0; rb < 2; ++rb) {
+            const int i0 = i_base + rb * 32;
+            if (rb * 32 >= rows) continue;
+            if (sg.chunk && i0 + 31 < wave_k0) continue;        // chunk keys are seen by later rows only
+            f32x16_t acc[2];
+#pragma unroll
+            for (int jq = 0; jq < 4; ++jq) {
+                const float4 t4 = *reinterpret_cast<const float4*>(&tneg[slot][wave][rb * 32 + jq * 8 + half * 4]);
+                acc[0][jq * 4 + 0] = t4.x; acc[0][jq * 4 + 1] = t4.y; acc[0][jq * 4 + 2] = t4.z; acc[0][jq * 4 + 3] = t4.w;
             }
-            {
-                const int i = i_base + tid;                              // kScoreRows == kScoreThreads
-                float t = INFINITY;
-                if (i < Q) t = lrow[i] * 1.4426950408889634f - __log2f(wrow[Q - 1 - i]);
-                ts[tid] = t;
-            }
-            __syncthreads();
-            for (int rb = 0; rb < (rows + 31) / 32; ++rb) {
-                const int i0 = i_base + rb * 32;
-                if (sg.chunk && i0 + 31 < wave_k0) continue;             // chunk keys are seen by later rows only
-                f32x16_t s[2];
+            acc[1] = acc[0];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                Frag qf;
+                qf.u = *reinterpret_cast<const u32x4_t*>(qs + a_off[rb][ks]);
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
+                    acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf.v, kf[kb][ks].v, acc[kb], 0, 0, 0);
+            }
+            if (sg.chunk && i0 < wave_k0 + 63) {                // the diagonal crosses this block: mask
 #pragma unroll
-                    for (int j = 0; j < 16; ++j) s[kb][j] = 0.f;
+                for (int j = 0; j < 16; ++j) {
+                    const int i = i0 + (j >> 2) * 8 + half * 4 + (j & 3);
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    Frag qf;
-                    qf.u = *reinterpret_cast<const u32x4_t*>(&Qs[(rb * 32 + l32) * QSTR + ks * 16 + half * 8]);
-#pragma unroll
-                    for (int kb = 0; kb < 2; ++kb)
-                        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf.v, kf[kb][ks].v, s[kb], 0, 0, 0);
-                }
-#pragma unroll
-                for (int jq = 0; jq < 4; ++jq) {
-                    const float4 t4 = *reinterpret_cast<const float4*>(&ts[rb * 32 + jq * 8 + half * 4]);
-                    const float tt[4] = {t4.x, t4.y, t4.z, t4.w};
-#pragma unroll
-                    for (int x = 0; x < 4; ++x) {
-                        const int i = i0 + jq * 8 + half * 4 + x;
-#pragma unroll
-                        for (int kb = 0; kb < 2; ++kb) {
-                            const float p = __builtin_amdgcn_exp2f(s[kb][jq * 4 + x] - tt[x]);
-                            colsum[kb] += (!sg.chunk || kk[kb] <= i) ? p : 0.f;
-                        }
+                    for (int kb = 0; kb < 2; ++kb) {
+                        const float p = __builtin_amdgcn_exp2f(acc[kb][j]);
+                        colsum[kb] += kk[kb] <= i ? p : 0.f;
                     }
                 }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+#pragma unroll
+                    for (int kb = 0; kb < 2; ++kb) colsum[kb] += __builtin_amdgcn_exp2f(acc[kb][j]);
             }
         }
+        if (++sp == spp) {                                      // the head is finished
+            sp = 0;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            const float cs = colsum[kb] + __shfl_xor(colsum[kb], 32, 64);
-            if (g.head_reduce == CASCADE_REDUCE_MAX) red[kb] = hh == 0 ? cs : fmaxf(red[kb], cs);
-            else red[kb] += cs;
+            for (int kb = 0; kb < 2; ++kb) {
+                const float cs = colsum[kb] + __shfl_xor(colsum[kb], 32, 64);
+                if (g.head_reduce == CASCADE_REDUCE_MAX) red[kb] = hh == 0 ? cs : fmaxf(red[kb], cs);
+                else red[kb] += cs;
+                colsum[kb] = 0.f;
+            }
+            ++hh;
         }
     }
 #pragma unroll
@@ -162,12 +209,15 @@ void launch_score_mfma(const Geom& g, const DevBuffers& b, const SegList& sl, in
     int tiles = 0;
     for (int i = 0; i < sl.n; ++i) tiles += (sl.s[i].len + kScoreKeys - 1) / kScoreKeys;
     const dim3 grid(tiles * g.B * g.Hkv), block(kScoreThreads);
+    const int qpad = max_chunk + kStRows;
+    hipLaunchKernelGGL(score_offsets_kernel, dim3((qpad + 255) / 256, g.B * g.Hq), dim3(256), 0, s, Q, qpad, tail_rows,
+                       b.lse, b.wrow, b.negt);
     if (g.d == 128)
-        hipLaunchKernelGGL(score_mfma_kernel<128>, grid, block, 0, s, g, sl, Q, max_chunk, tail_rows, decay,
-                           (const bf16_t*)b.Qr, (const bf16_t*)b.Kr, (const bf16_t*)b.Krc, b.lse, b.wrow, b.mu, b.mu_chunk);
+        hipLaunchKernelGGL(score_stream_kernel<128>, grid, block, 0, s, g, sl, Q, max_chunk, tail_rows, qpad, decay,
+                           (const bf16_t*)b.Qr, (const bf16_t*)b.Kr, (const bf16_t*)b.Krc, b.negt, b.mu, b.mu_chunk);
     else
-        hipLaunchKernelGGL(score_mfma_kernel<64>, grid, block, 0, s, g, sl, Q, max_chunk, tail_rows, decay,
-                           (const bf16_t*)b.Qr, (const bf16_t*)b.Kr, (const bf16_t*)b.Krc, b.lse, b.wrow, b.mu, b.mu_chunk);
+        hipLaunchKernelGGL(score_stream_kernel<64>, grid, block, 0, s, g, sl, Q, max_chunk, tail_rows, qpad, decay,
+                           (const bf16_t*)b.Qr, (const bf16_t*)b.Kr, (const bf16_t*)b.Krc, b.negt, b.mu, b.mu_chunk);
 }
 
 }  // namespace ckv
