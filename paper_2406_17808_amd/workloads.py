@@ -8,8 +8,10 @@ sharing any code of the method itself.
 The workloads stand in for the paper's latency experiment (a single
 attention layer at Llama-3.1-8B head geometry streaming a long prompt,
 Section 4.1; ``prefill_paper_16k`` has that experiment's own cache size, stride
-and EMA decay) and, for the planted key of ``prefill_1m``, for the passkey
-experiment (Section 4.4); no dataset or trained weight is involved.
+and EMA decay; ``prefill_passkey_*`` and ``prefill_longbench_8k`` have the cache
+geometries of the passkey and long-context-understanding experiments) and, for
+the planted key of ``prefill_1m``, for the passkey experiment (Section 4.4); no
+dataset or trained weight is involved.
 """
 from __future__ import annotations
 
@@ -79,6 +81,22 @@ WORKLOADS: Dict[str, Workload] = {
     "prefill_paper_16k": Workload(
         name="prefill_paper_16k", batch=1, n_q_heads=32, n_kv_heads=8, head_dim=128, dtype="bf16",
         n_sink=64, cascade_sizes=(4096,) * 4, seq_len=1048576, chunk=4096,
+        ema_beta=0.9999, rope_base=500000.0, input_scale=1.0),
+    # the geometries of the paper's other experiments (all with its EMA decay 0.9999):
+    # passkey retrieval (Section 4.4): 8 cascades, caches of 32K and 65K, stride 4096
+    "prefill_passkey_32k": Workload(
+        name="prefill_passkey_32k", batch=1, n_q_heads=32, n_kv_heads=8, head_dim=128, dtype="bf16",
+        n_sink=64, cascade_sizes=(4096,) * 8, seq_len=1048576, chunk=4096,
+        ema_beta=0.9999, rope_base=500000.0, input_scale=1.0),
+    "prefill_passkey_65k": Workload(
+        name="prefill_passkey_65k", batch=1, n_q_heads=32, n_kv_heads=8, head_dim=128, dtype="bf16",
+        n_sink=64, cascade_sizes=(8192,) * 8, seq_len=1048576, chunk=4096,
+        ema_beta=0.9999, rope_base=500000.0, input_scale=1.0),
+    # long-context understanding (Section 4.3): cache 2^floor(log2(L/4)) for a prompt of L tokens,
+    # stride 512; L = 40000 gives an 8192-slot cache and a last chunk of 64 tokens
+    "prefill_longbench_8k": Workload(
+        name="prefill_longbench_8k", batch=1, n_q_heads=32, n_kv_heads=8, head_dim=128, dtype="bf16",
+        n_sink=64, cascade_sizes=(2048,) * 4, seq_len=40000, chunk=512,
         ema_beta=0.9999, rope_base=500000.0, input_scale=1.0),
     "decode_b32": Workload(
         name="decode_b32", batch=32, n_q_heads=32, n_kv_heads=8, head_dim=128, dtype="bf16",

@@ -118,6 +118,40 @@ def test_prefill_paper_16k_all_rows_in_scores(oracle_mod):
     run.close()
 
 
+@pytest.mark.parametrize("name,n_chunks,compare,kv_heads", [
+    # 8 cascades of 4096: at chunk 20 three cascades are full, the fourth is filling
+    ("prefill_passkey_32k", 21, (20,), [1, 6]),
+    # 8 cascades of 8192: at chunk 36 cascades 1-2 are full (many query rotations in one step)
+    ("prefill_passkey_65k", 37, (36,), [2, 7]),
+    # stride 512 into an 8K cache: a chunk in steady state and the ragged last chunk (64 tokens)
+    ("prefill_longbench_8k", 79, (60, 78), [0, 4]),
+])
+def test_other_experiment_geometries(oracle_mod, name, n_chunks, compare, kv_heads):
+    """Cache geometries of the paper's passkey (Section 4.4) and long-context-understanding
+    (Section 4.3) experiments with its EMA decay: the compared chunks whole on two KV heads,
+    one step ahead of the GPU state."""
+    from gpu_harness import ParityRun
+    from paper_2406_17808_amd.cache import config_of
+    wl = WORKLOADS[name]
+    cfg = config_of(wl, keep_update_scores=1)
+    run = ParityRun(cfg, one_step_ahead=True, kv_heads=kv_heads)
+    for c in range(n_chunks):
+        dq, dk, dv = chunk_inputs_torch(wl, 0, c, "cuda:0")
+        if c in compare:
+            run.sync_oracle_from_gpu()
+            print(f"{name}: comparing chunk {c} ({dq.shape[1]} tokens)", flush=True)
+            rep = _step_two_heads(run, _host(dq), _host(dk), _host(dv))
+            print(f"{name}: chunk {c}: out {rep.out_err:.3e} score {rep.score_err:.3e} drift {rep.drift}/{rep.compared}", flush=True)
+            assert rep.replay_exact
+            assert rep.out_err <= TOL_OUT and rep.score_err <= TOL_SCORE
+        else:
+            run.advance_gpu_only(dq, dk, dv)
+    st = run.gpu.read_state()
+    assert st.n_seen == min(wl.seq_len, n_chunks * wl.chunk)
+    assert st.counts[0] == wl.n_sink and st.counts[1] == wl.cascade_sizes[0]
+    run.close()
+
+
 def _step_two_heads(run, q, k, v):
     """run.step, but with the oracle evaluating only the listed (non-adjacent) KV heads, each
     on its own thread."""
