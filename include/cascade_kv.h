@@ -145,6 +145,25 @@ int cascade_init(const cascade_config* cfg, void* dev_workspace, size_t workspac
 void cascade_destroy(cascade_ctx* ctx);
 
 /*
+ * Several layers over one workspace (the inner loop of Alg. 1 runs cache.get, the layer and
+ * cache.update once per layer for every chunk).  Every layer gets a context and a cache of
+ * its own; the buffers that live only inside one call (rotated queries, packed tiles, decode
+ * logits, ...) exist once and are shared, so the workspace is n_layers states plus one
+ * scratch instead of n_layers times both.  The contexts are ordinary contexts: use them with
+ * every other call and free each with cascade_destroy.  Because they share scratch, calls on
+ * ANY of them must be ordered with each other (one stream, or streams the caller orders), and
+ * none may be in flight when the workspace is released.
+ *   cascade_layers_workspace_bytes: bytes for n_layers layers; 0 if the configuration is
+ *     invalid or n_layers < 1.
+ *   cascade_init_layers: init_states is NULL (all caches start empty) or an array of n_layers
+ *     pointers, each NULL or the state to copy into that layer; out_ctxs receives n_layers
+ *     contexts (all NULL on failure).  Errors as for cascade_init, BAD_ARG for n_layers < 1.
+ */
+size_t cascade_layers_workspace_bytes(const cascade_config* cfg, int32_t n_layers);
+int cascade_init_layers(const cascade_config* cfg, int32_t n_layers, void* dev_workspace, size_t workspace_bytes,
+                        const cascade_init_state* const* init_states, void* stream, cascade_ctx** out_ctxs);
+
+/*
  * One step of strided prefill (Alg. 1) for every sequence of the batch:
  *   1. out <- softmax attention of the chunk's queries over the cache as it is before the
  *      call plus the chunk's own keys up to each query (Eq. 2, Fig. 4), RoPE by cache index;

@@ -30,7 +30,7 @@ CASCADE_REDUCE_MEAN = 1
 EXPORTED_SYMBOLS = [
     "cascade_workspace_bytes", "cascade_init", "cascade_destroy", "cascade_prefill_chunk",
     "cascade_decode_step", "cascade_read_state", "cascade_simulate_structure", "cascade_last_error",
-    "cascade_profile_begin", "cascade_profile_end",
+    "cascade_profile_begin", "cascade_profile_end", "cascade_layers_workspace_bytes", "cascade_init_layers",
 ]
 
 CASCADE_K_FAMILIES = 7
@@ -100,6 +100,10 @@ def load_library():
         L.cascade_init.restype = ctypes.c_int
         L.cascade_init.argtypes = [ctypes.POINTER(cascade_config), P, ctypes.c_size_t,
                                    ctypes.POINTER(cascade_init_state), P, ctypes.POINTER(P)]
+        L.cascade_layers_workspace_bytes.restype = ctypes.c_size_t
+        L.cascade_layers_workspace_bytes.argtypes = [ctypes.POINTER(cascade_config), ctypes.c_int32]
+        L.cascade_init_layers.restype = ctypes.c_int
+        L.cascade_init_layers.argtypes = [ctypes.POINTER(cascade_config), ctypes.c_int32, P, ctypes.c_size_t, P, P, P]
         L.cascade_destroy.restype = None
         L.cascade_destroy.argtypes = [P]
         L.cascade_prefill_chunk.restype = ctypes.c_int
@@ -159,6 +163,27 @@ def cascade_init(cfg: cascade_config, dev_workspace: int, workspace_bytes: int,
                                      stream, ctypes.byref(ctx))
     _check(rc, None)
     return ctx
+
+
+def cascade_layers_workspace_bytes(cfg: cascade_config, n_layers: int) -> int:
+    return int(load_library().cascade_layers_workspace_bytes(ctypes.byref(cfg), n_layers))
+
+
+def cascade_init_layers(cfg: cascade_config, n_layers: int, dev_workspace: int, workspace_bytes: int,
+                        init_states: Optional[Sequence[Optional[cascade_init_state]]] = None, stream: int = 0):
+    """n_layers contexts that share the per-call scratch of one workspace; returns them as a list."""
+    n = max(int(n_layers), 0)
+    ctxs = (ctypes.c_void_p * max(n, 1))()
+    states = None
+    if init_states is not None:
+        assert len(init_states) == n
+        states = (ctypes.c_void_p * max(n, 1))()
+        for i, st in enumerate(init_states):
+            states[i] = ctypes.cast(ctypes.pointer(st), ctypes.c_void_p).value if st is not None else None
+    rc = load_library().cascade_init_layers(ctypes.byref(cfg), n_layers, dev_workspace, workspace_bytes,
+                                            states, stream, ctxs)
+    _check(rc, None)
+    return [ctypes.c_void_p(ctxs[i]) for i in range(n)]
 
 
 def cascade_destroy(ctx) -> None:

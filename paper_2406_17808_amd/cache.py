@@ -23,10 +23,14 @@ def config_of(wl: Workload, max_chunk: Optional[int] = None, batch: Optional[int
 
 
 class CascadeKVCache:
-    def __init__(self, cfg: B.cascade_config, device: str = "cuda:0", init_state: Optional[B.cascade_init_state] = None):
+    def __init__(self, cfg: B.cascade_config, device: str = "cuda:0", init_state: Optional[B.cascade_init_state] = None,
+                 _layer_of=None):
         self.cfg = cfg
         self.device = torch.device(device)
         self.torch_dtype = torch.bfloat16 if cfg.dtype == B.CASCADE_BF16 else torch.float32
+        if _layer_of is not None:      # a layer of CascadeKVLayers: the context exists, the workspace is the owner's
+            self.workspace, self.ctx, self.workspace_bytes = _layer_of
+            return
         nbytes = B.cascade_workspace_bytes(cfg)
         if nbytes == 0:
             # let cascade_init report why
@@ -81,3 +85,33 @@ class CascadeKVCache:
 
     def read_state(self, with_kv: bool = False) -> B.StateArrays:
         return B.cascade_read_state(self.ctx, self.cfg, with_kv, self._stream())
+
+
+class CascadeKVLayers:
+    """The caches of several attention layers over one workspace (the layer loop of Alg. 1): every
+    layer is a CascadeKVCache of its own, the per-call scratch exists once.  Calls on the layers
+    must be ordered with each other; issuing them on one stream, as here, does that."""
+
+    def __init__(self, cfg: B.cascade_config, n_layers: int, device: str = "cuda:0", init_states=None):
+        self.cfg = cfg
+        self.device = torch.device(device)
+        nbytes = B.cascade_layers_workspace_bytes(cfg, n_layers)
+        if nbytes == 0:
+            B.cascade_init_layers(cfg, n_layers, 256, 0)      # reports why
+        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+        self.workspace_bytes = nbytes
+        ptr = (self.workspace.data_ptr() + 255) & ~255
+        with torch.cuda.device(self.device):
+            ctxs = B.cascade_init_layers(cfg, n_layers, ptr, nbytes, init_states,
+                                         torch.cuda.current_stream(self.device).cuda_stream)
+        self.layers = [CascadeKVCache(cfg, device, _layer_of=(self.workspace, c, nbytes)) for c in ctxs]
+
+    def __len__(self):
+        return len(self.layers)
+
+    def __getitem__(self, i) -> CascadeKVCache:
+        return self.layers[i]
+
+    def close(self):
+        for layer in self.layers:
+            layer.close()

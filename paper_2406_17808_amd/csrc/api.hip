@@ -126,8 +126,14 @@ static int decode_splits(const Geom& g)
     return s;
 }
 
-// Workspace layout; with base == nullptr only the total size is computed.
-static size_t carve(const cascade_config* c, const Geom& g, char* base, DevBuffers* out)
+// Workspace layout in two regions: the state of one layer (the cache itself) and the buffers
+// that live only inside one call (plus the two tables, which depend on the configuration
+// alone), which several layers may share.  With null bases only the sizes are computed.
+struct WorkspaceBytes {
+    size_t state, shared;
+};
+
+static WorkspaceBytes carve(const cascade_config* c, const Geom& g, char* state_base, char* shared_base, DevBuffers* out)
 {
     const size_t elem = c->dtype == CASCADE_BF16 ? 2 : 4;
     const size_t BH = (size_t)g.B * g.Hkv, BHq = (size_t)g.B * g.Hq;
@@ -136,6 +142,7 @@ static size_t carve(const cascade_config* c, const Geom& g, char* base, DevBuffe
     const int splits = decode_splits(g);
     const int rope_rows = 2 * g.slots + c->max_chunk + 1;
     size_t off = 0;
+    char* base = state_base;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return base ? (void*)(base + o) : (void*)nullptr; };
     DevBuffers b;
     memset(&b, 0, sizeof(b));
@@ -146,6 +153,10 @@ static size_t carve(const cascade_config* c, const Geom& g, char* base, DevBuffe
     b.ids = (int32_t*)take(BH * g.slots * 4);
     b.swaps = (int32_t*)take(BH * g.N * 4);
     b.mu_snap = (float*)take(c->keep_update_scores ? BH * g.slots * 4 : 0);
+    WorkspaceBytes bytes;
+    bytes.state = off;
+    off = 0;
+    base = shared_base;
     b.rope = (float2*)take((size_t)rope_rows * (g.d / 2) * 8);
     b.wrow = (float*)take(mc * 4);
     b.Qr = take((size_t)n_qvar_max * BHq * mc * g.d * elem);
@@ -164,11 +175,12 @@ static size_t carve(const cascade_config* c, const Geom& g, char* base, DevBuffe
     b.logits = (float*)take(BH * ((size_t)g.slots + 1) * (size_t)(g.G <= 8 ? decode_logit_heads(g) : g.G) * 4);
     b.part = (float*)take(BHq * splits * 2 * 4);
     b.opart = (float*)take(BHq * splits * g.d * 4);
+    bytes.shared = off;
     b.rope_rows = rope_rows;
     b.dec_splits = splits;
     b.vt_tiles = vt_tiles;
     if (out) *out = b;
-    return off;
+    return bytes;
 }
 
 extern "C" size_t cascade_workspace_bytes(const cascade_config* cfg)
@@ -178,7 +190,19 @@ extern "C" size_t cascade_workspace_bytes(const cascade_config* cfg)
     if (check_config(cfg, why) != CASCADE_OK) return 0;
     Geom g;
     make_geom(cfg, g);
-    return carve(cfg, g, nullptr, nullptr);
+    const WorkspaceBytes w = carve(cfg, g, nullptr, nullptr, nullptr);
+    return w.state + w.shared;
+}
+
+extern "C" size_t cascade_layers_workspace_bytes(const cascade_config* cfg, int32_t n_layers)
+{
+    if (!cfg || n_layers < 1) return 0;
+    std::string why;
+    if (check_config(cfg, why) != CASCADE_OK) return 0;
+    Geom g;
+    make_geom(cfg, g);
+    const WorkspaceBytes w = carve(cfg, g, nullptr, nullptr, nullptr);
+    return w.state * (size_t)n_layers + w.shared;
 }
 
 static int hip_check(cascade_ctx* ctx, hipError_t e, const char* what)
@@ -189,41 +213,38 @@ static int hip_check(cascade_ctx* ctx, hipError_t e, const char* what)
 
 // ------------------------------------------------------------------ init / destroy
 
-extern "C" int cascade_init(const cascade_config* cfg, void* dev_workspace, size_t workspace_bytes,
-                            const cascade_init_state* init_state, void* stream, cascade_ctx** out_ctx)
+// Host-side check of an initial state (may be null: empty cache); fills the host mirror.
+static int check_init_state(const std::string& name, const Geom& g, const cascade_init_state* init_state, HostState& st, int& total)
 {
-    if (!cfg || !dev_workspace || !out_ctx) return fail(nullptr, CASCADE_E_NULL_ARG, "cascade_init: NULL argument");
-    *out_ctx = nullptr;
-    std::string why;
-    int rc = check_config(cfg, why);
-    if (rc != CASCADE_OK) return fail(nullptr, rc, "cascade_init: " + why);
-    if (((uintptr_t)dev_workspace & 255) != 0) return fail(nullptr, CASCADE_E_BAD_ARG, "cascade_init: workspace must be 256-byte aligned");
-    Geom g;
-    make_geom(cfg, g);
-    const size_t need = carve(cfg, g, nullptr, nullptr);
-    if (workspace_bytes < need) return fail(nullptr, CASCADE_E_WORKSPACE_TOO_SMALL, "cascade_init: workspace too small");
-
-    HostState st;
-    int total = 0;
-    if (init_state) {
-        if (init_state->counts[0] < 0 || init_state->counts[0] > g.n_sink)
-            return fail(nullptr, CASCADE_E_BAD_ARG, "cascade_init: sink count exceeds n_sink");
-        st.sink_fill = init_state->counts[0];
-        total = st.sink_fill;
-        for (int c = 0; c < g.N; ++c) {
-            const int cnt = init_state->counts[1 + c];
-            if (cnt < 0 || cnt > g.cap[c]) return fail(nullptr, CASCADE_E_BAD_ARG, "cascade_init: a cascade count exceeds its capacity");
-            st.count[c] = cnt;
-            total += cnt;
-        }
-        if (init_state->t < 0 || init_state->n_seen < 0 || init_state->n_seen > 0x7FFFFFFF)
-            return fail(nullptr, CASCADE_E_BAD_ARG, "cascade_init: t / n_seen out of range");
-        st.t = init_state->t;
-        st.n_seen = init_state->n_seen;
-        if (total > 0 && (!init_state->dev_k || !init_state->dev_v || !init_state->dev_mu || !init_state->dev_ids))
-            return fail(nullptr, CASCADE_E_NULL_ARG, "cascade_init: init_state with items needs k, v, mu and ids");
+    total = 0;
+    if (!init_state) return CASCADE_OK;
+    if (init_state->counts[0] < 0 || init_state->counts[0] > g.n_sink)
+        return fail(nullptr, CASCADE_E_BAD_ARG, name + ": sink count exceeds n_sink");
+    st.sink_fill = init_state->counts[0];
+    total = st.sink_fill;
+    for (int c = 0; c < g.N; ++c) {
+        const int cnt = init_state->counts[1 + c];
+        if (cnt < 0 || cnt > g.cap[c]) return fail(nullptr, CASCADE_E_BAD_ARG, name + ": a cascade count exceeds its capacity");
+        st.count[c] = cnt;
+        total += cnt;
     }
+    if (init_state->t < 0 || init_state->n_seen < 0 || init_state->n_seen > 0x7FFFFFFF)
+        return fail(nullptr, CASCADE_E_BAD_ARG, name + ": t / n_seen out of range");
+    st.t = init_state->t;
+    st.n_seen = init_state->n_seen;
+    if (total > 0 && (!init_state->dev_k || !init_state->dev_v || !init_state->dev_mu || !init_state->dev_ids))
+        return fail(nullptr, CASCADE_E_NULL_ARG, name + ": init_state with items needs k, v, mu and ids");
+    return CASCADE_OK;
+}
 
+// One context over a state region and a shared region that the caller has already zeroed;
+// `tables` says whether this call fills the tables of the shared region.  st / total come from
+// check_init_state.
+static int init_context(const char* who, const cascade_config* cfg, const Geom& g, char* state_base, char* shared_base,
+                        bool tables, const cascade_init_state* init_state, const HostState& st, int total,
+                        hipStream_t s, cascade_ctx** out_ctx)
+{
+    const std::string name = who;
     cascade_ctx* ctx = new cascade_ctx();
     ctx->cfg = *cfg;
     ctx->g = g;
@@ -231,7 +252,7 @@ extern "C" int cascade_init(const cascade_config* cfg, void* dev_workspace, size
     ctx->dtype = cfg->dtype;
     ctx->elem = cfg->dtype == CASCADE_BF16 ? 2 : 4;
     ctx->max_chunk = cfg->max_chunk;
-    carve(cfg, g, (char*)dev_workspace, &ctx->buf);
+    carve(cfg, g, state_base, shared_base, &ctx->buf);
     ctx->mfma = cfg->dtype == CASCADE_BF16;
     if (const char* e = getenv("CASCADE_KV_SCALAR_ATTENTION")) if (e[0] == '1') ctx->mfma = false;
 
@@ -251,21 +272,85 @@ extern "C" int cascade_init(const cascade_config* cfg, void* dev_workspace, size
         ctx->tail_k = k;
     }
 
-    hipStream_t s = (hipStream_t)stream;
     const DevBuffers& b = ctx->buf;
     const size_t BH = (size_t)g.B * g.Hkv;
-    // zero the cache (rows of empty slots are read, masked, by the attention tiles) and scratch
-    hipError_t e = hipMemsetAsync(dev_workspace, 0, need, s);
-    if (e != hipSuccess) { rc = hip_check(nullptr, e, "cascade_init: memset"); delete ctx; return rc; }
     launch_fill_i32(b.ids, BH * g.slots, -1, s);
-    launch_rope_table(g, cfg->rope_base, b.rope, b.rope_rows, s);
-    launch_wrow_table(cfg->ema_beta, b.wrow, cfg->max_chunk, s);
+    if (tables) {
+        launch_rope_table(g, cfg->rope_base, b.rope, b.rope_rows, s);
+        launch_wrow_table(cfg->ema_beta, b.wrow, cfg->max_chunk, s);
+    }
     if (init_state && total > 0)
         launch_load_state(g, ctx->dtype, b, init_state->dev_k, init_state->dev_v, init_state->dev_mu,
                           init_state->dev_ids, init_state->counts, total, s);
-    e = hipGetLastError();
-    if (e != hipSuccess) { rc = hip_check(nullptr, e, "cascade_init: launch"); delete ctx; return rc; }
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        const int rc = hip_check(nullptr, e, (name + ": launch").c_str());
+        delete ctx;
+        return rc;
+    }
     *out_ctx = ctx;
+    return CASCADE_OK;
+}
+
+extern "C" int cascade_init(const cascade_config* cfg, void* dev_workspace, size_t workspace_bytes,
+                            const cascade_init_state* init_state, void* stream, cascade_ctx** out_ctx)
+{
+    if (!cfg || !dev_workspace || !out_ctx) return fail(nullptr, CASCADE_E_NULL_ARG, "cascade_init: NULL argument");
+    *out_ctx = nullptr;
+    std::string why;
+    int rc = check_config(cfg, why);
+    if (rc != CASCADE_OK) return fail(nullptr, rc, "cascade_init: " + why);
+    if (((uintptr_t)dev_workspace & 255) != 0) return fail(nullptr, CASCADE_E_BAD_ARG, "cascade_init: workspace must be 256-byte aligned");
+    Geom g;
+    make_geom(cfg, g);
+    const WorkspaceBytes need = carve(cfg, g, nullptr, nullptr, nullptr);
+    if (workspace_bytes < need.state + need.shared) return fail(nullptr, CASCADE_E_WORKSPACE_TOO_SMALL, "cascade_init: workspace too small");
+    HostState st;
+    int total = 0;
+    rc = check_init_state("cascade_init", g, init_state, st, total);
+    if (rc != CASCADE_OK) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    // zero the cache (rows of empty slots are read, masked, by the attention tiles) and scratch
+    const hipError_t e = hipMemsetAsync(dev_workspace, 0, need.state + need.shared, s);
+    if (e != hipSuccess) return hip_check(nullptr, e, "cascade_init: memset");
+    char* base = (char*)dev_workspace;
+    return init_context("cascade_init", cfg, g, base, base + need.state, true, init_state, st, total, s, out_ctx);
+}
+
+extern "C" int cascade_init_layers(const cascade_config* cfg, int32_t n_layers, void* dev_workspace, size_t workspace_bytes,
+                                   const cascade_init_state* const* init_states, void* stream, cascade_ctx** out_ctxs)
+{
+    if (!cfg || !dev_workspace || !out_ctxs) return fail(nullptr, CASCADE_E_NULL_ARG, "cascade_init_layers: NULL argument");
+    if (n_layers < 1) return fail(nullptr, CASCADE_E_BAD_ARG, "cascade_init_layers: n_layers must be at least 1");
+    for (int i = 0; i < n_layers; ++i) out_ctxs[i] = nullptr;
+    std::string why;
+    int rc = check_config(cfg, why);
+    if (rc != CASCADE_OK) return fail(nullptr, rc, "cascade_init_layers: " + why);
+    if (((uintptr_t)dev_workspace & 255) != 0) return fail(nullptr, CASCADE_E_BAD_ARG, "cascade_init_layers: workspace must be 256-byte aligned");
+    Geom g;
+    make_geom(cfg, g);
+    const WorkspaceBytes need = carve(cfg, g, nullptr, nullptr, nullptr);
+    const size_t total = need.state * (size_t)n_layers + need.shared;
+    if (workspace_bytes < total) return fail(nullptr, CASCADE_E_WORKSPACE_TOO_SMALL, "cascade_init_layers: workspace too small");
+    std::vector<HostState> sts(n_layers);
+    std::vector<int> totals(n_layers, 0);
+    for (int i = 0; i < n_layers; ++i) {
+        rc = check_init_state("cascade_init_layers", g, init_states ? init_states[i] : nullptr, sts[i], totals[i]);
+        if (rc != CASCADE_OK) return rc;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    const hipError_t e = hipMemsetAsync(dev_workspace, 0, total, s);
+    if (e != hipSuccess) return hip_check(nullptr, e, "cascade_init_layers: memset");
+    char* base = (char*)dev_workspace;
+    char* shared = base + need.state * (size_t)n_layers;
+    for (int i = 0; i < n_layers; ++i) {
+        rc = init_context("cascade_init_layers", cfg, g, base + need.state * (size_t)i, shared, i == 0,
+                          init_states ? init_states[i] : nullptr, sts[i], totals[i], s, &out_ctxs[i]);
+        if (rc != CASCADE_OK) {
+            for (int j = 0; j < i; ++j) { cascade_destroy(out_ctxs[j]); out_ctxs[j] = nullptr; }
+            return rc;
+        }
+    }
     return CASCADE_OK;
 }
 

@@ -96,10 +96,11 @@ class ParityRun:
     """One library context and one oracle per compared sequence, advanced together."""
 
     def __init__(self, cfg: B.cascade_config, one_step_ahead: bool, kv_heads: Optional[List[int]] = None,
-                 init_state: Optional[B.cascade_init_state] = None, device="cuda:0", seqs: Optional[List[int]] = None):
+                 init_state: Optional[B.cascade_init_state] = None, device="cuda:0", seqs: Optional[List[int]] = None,
+                 gpu: Optional[CascadeKVCache] = None):
         assert cfg.keep_update_scores == 1
         self.cfg = cfg
-        self.gpu = CascadeKVCache(cfg, device, init_state)
+        self.gpu = gpu if gpu is not None else CascadeKVCache(cfg, device, init_state)   # gpu: an existing context
         self.ocfg = oracle_config_of(cfg)
         self.seqs = list(range(cfg.batch)) if seqs is None else seqs
         self.oracles = {b: OracleSeq(self.ocfg) for b in self.seqs}

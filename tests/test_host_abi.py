@@ -88,6 +88,38 @@ def test_init_argument_errors(lib):
     assert lib.cascade_read_state(None, None, None) == B.CASCADE_E_NULL_ARG
 
 
+def test_layers_share_one_scratch(lib):
+    """n layers need n states and one scratch: the size is affine in n, one layer is the plain
+    workspace, and a large cache costs little more than its three row arrays per extra layer."""
+    cfg = _cfg()
+    one = B.cascade_workspace_bytes(cfg)
+    sizes = [B.cascade_layers_workspace_bytes(cfg, n) for n in (1, 2, 3, 7)]
+    assert sizes[0] == one
+    state = sizes[1] - sizes[0]
+    assert 0 < state < one
+    assert sizes[2] == one + 2 * state and sizes[3] == one + 6 * state
+    assert B.cascade_layers_workspace_bytes(cfg, 0) == 0
+    assert B.cascade_layers_workspace_bytes(_cfg(batch=0), 2) == 0
+    huge = _cfg(dtype=B.CASCADE_BF16, head_dim=128, n_q_heads=32, n_kv_heads=8, n_sink=64,
+                cascade_sizes=[16384] * 4, max_chunk=1)
+    rows = 8 * 65600 * 128 * 2
+    per_layer = B.cascade_layers_workspace_bytes(huge, 5) - B.cascade_layers_workspace_bytes(huge, 4)
+    assert 3 * rows < per_layer < 3.1 * rows
+    # argument errors
+    with pytest.raises(B.CascadeError) as e:
+        B.cascade_init_layers(cfg, 0, 4096, 1 << 30)
+    assert e.value.code == B.CASCADE_E_BAD_ARG
+    with pytest.raises(B.CascadeError) as e:
+        B.cascade_init_layers(cfg, 2, 4096, sizes[1] - 1)
+    assert e.value.code == B.CASCADE_E_WORKSPACE_TOO_SMALL
+    with pytest.raises(B.CascadeError) as e:
+        B.cascade_init_layers(cfg, 2, 0, sizes[1])
+    assert e.value.code == B.CASCADE_E_NULL_ARG
+    with pytest.raises(B.CascadeError) as e:
+        B.cascade_init_layers(_cfg(ema_beta=1.0), 2, 4096, 1 << 30)
+    assert e.value.code == B.CASCADE_E_INVALID_CONFIG
+
+
 def test_workspace_grows_with_the_cache(lib):
     small = B.cascade_workspace_bytes(_cfg())
     big = B.cascade_workspace_bytes(_cfg(cascade_sizes=[64, 64, 64]))
