@@ -159,10 +159,10 @@ def decode_bench(args, torch, B):
         "decode_step_us": dt / steps * 1e6, "decode_steps": steps, "decode_tokens_per_s": wl.batch * steps / dt,
         "decode_hbm_frac": bytes_step / (dt / steps) / HBM_PEAK,
         "decode_kernel_us": {k: v[0] / max(v[1], 1) * 1e3 for k, v in prof.items() if v[1]},
-        "roofline_decode": {"bound": "hbm", "kernel": "decode_qk_kernel", "achieved": k_bytes / (qk_ms / 1e3 / max(qk_n, 1)) / 1e9,
+        "roofline_decode": {"bound": "hbm", "kernel": "decode_qk_stream_kernel", "achieved": k_bytes / (qk_ms / 1e3 / max(qk_n, 1)) / 1e9,
                             "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                             "frac": k_bytes / (qk_ms / 1e3 / max(qk_n, 1)) / HBM_PEAK,
-                            "traffic": stored_traffic("decode_qk_kernel_decode_b32_hbm_traffic.json")},
+                            "traffic": stored_traffic("decode_qk_stream_kernel_decode_b32_hbm_traffic.json")},
     }
     cache.close()
     return res
