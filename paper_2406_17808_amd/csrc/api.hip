@@ -170,6 +170,7 @@ static WorkspaceBytes carve(const cascade_config* c, const Geom& g, char* state_
     b.lse = (float*)take(BHq * mc * 4);
     b.mu_chunk = (float*)take(BH * mc * 4);
     b.negt = (float*)take(mfma ? BHq * (mc + 64) * 4 : 0);
+    b.attn_part = (float*)take(mfma ? (size_t)kAttnPartRows * (g.d + 2) * 4 : 0);
     b.offers = (int32_t*)take(BH * 2 * mc * 4);
     b.winners = (int32_t*)take(BH * g.N * (mc + 1) * 4);
     b.logits = (float*)take(BH * ((size_t)g.slots + 1) * (size_t)(g.G <= 8 ? decode_logit_heads(g) : g.G) * 4);

@@ -14,6 +14,10 @@
 // reads only) and a vector block (mask, maximum, exponentials of tile t+1).  The two waves of a
 // SIMD run these blocks in opposite phase, held there by two barriers per tile, so the matrix
 // pipe and the vector ALU of the SIMD work at the same time.
+//
+// A chunk too short to give every compute unit a workgroup is split over the keys as well: up to
+// eight workgroups share the tiles of one row block and write unnormalised partial results,
+// which attn_merge_kernel combines (online-softmax merge of Eq. 2's sums).
 #include <stdio.h>
 #include <stdlib.h>
 
@@ -94,10 +98,14 @@ __global__ __launch_bounds__(kPackThreads) void kv_pack_kernel(Geom g, SegList s
     }
 }
 
-template <int D, bool DBG>
+// SPLIT: the tiles a row block visits are divided over n_split workgroups (for launches too small
+// to fill the chip otherwise); each writes its unnormalised output, running maximum and row sum
+// to part_o / part_ml, and attn_merge_kernel combines them.
+template <int D, bool DBG, bool SPLIT>
 __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     Geom g, SegList sl, int Q, int tiles_per_bh, const bf16_t* __restrict__ Qr, const bf16_t* __restrict__ Kt,
-    const bf16_t* __restrict__ Vt, bf16_t* __restrict__ out, float* __restrict__ lse, long long* dbg)
+    const bf16_t* __restrict__ Vt, bf16_t* __restrict__ out, float* __restrict__ lse, long long* dbg,
+    int n_split, float* __restrict__ part_o, float* __restrict__ part_ml)
 {
     constexpr int BM = kSWaves * 32;       // query rows per workgroup
     constexpr int KS = D / 16;             // k-steps of S^T = K Q^T
@@ -110,7 +118,9 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
 
     const int BH = g.B * g.Hkv;
     // consecutive workgroups: different KV heads; row blocks that see more of the chunk (longer loops) start first
-    const int bh = blockIdx.x % BH, tile = (int)(gridDim.x / BH) - 1 - (int)(blockIdx.x / BH);
+    const int n_tiles = (int)(gridDim.x / BH) / (SPLIT ? n_split : 1);
+    const int rest = (int)(blockIdx.x / BH);
+    const int bh = blockIdx.x % BH, split = SPLIT ? rest % n_split : 0, tile = n_tiles - 1 - (SPLIT ? rest / n_split : rest);
     const int b = bh / g.Hkv, hk = bh % g.Hkv;
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, l32 = l & 31, half = l >> 5;
     const int GQ = g.G * Q;
@@ -142,12 +152,15 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     // already relative to it.
     float m_run = 0.f;
     f32x16_t negm;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) negm[j] = 0.f;
     float lsum = 0.f;   // this lane's part of the row sum
+    bool seen = false;  // SPLIT: this row has seen a key
 
     // The packed tiles are LDS images: every wave copies PW consecutive KB of each
     const uint32_t lds_k = lds_address(Ks) + (uint32_t)wave * PW * 1024u;
     const uint32_t lds_v = lds_address(Vs) + (uint32_t)wave * PW * 1024u;
-    const bf16_t* kt_bh = Kt + (size_t)bh * tiles_per_bh * TILE + (size_t)wave * PW * 512;
+    const bf16_t* kt_bh = Kt + (size_t)bh * tiles_per_bh * TILE + (size_t)wave * PW * 512;   // (SPLIT: moved to the first tile of the range below)
     const bf16_t* vt_bh = Vt + (size_t)bh * tiles_per_bh * TILE + (size_t)wave * PW * 512;
     auto copy_tile = [&](const bf16_t* src_bh, uint32_t lds, int n, int stage) {   // tile n of a packed copy
         const bf16_t* base = src_bh + (size_t)n * TILE;
@@ -212,10 +225,14 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
 #pragma unroll
             for (int j = 0; j < 16; ++j) x = fmaxf(x, s[kb][j]);
         const float mt = max_xor32(x);
-        const bool grow = first || mt > kRescaleLog2;
+        // SPLIT: a range may start with chunk tiles some rows do not see at all, so "first" is kept
+        // per row: until a row has seen a key its m_run stays 0 and everything it holds is zero
+        const bool fresh = SPLIT ? !seen : first;
+        const bool grow = SPLIT ? (fresh ? mt > -INFINITY : mt > kRescaleLog2) : (first || mt > kRescaleLog2);
+        if (SPLIT) seen = seen || mt > -INFINITY;
         if (__any(grow)) {
-            const float delta = grow ? mt : 0.f;   // every row sees a key of the first tile: finite there
-            const float alpha = first ? 1.f : __builtin_amdgcn_exp2f(-delta);   // O and the row sum are still zero on the first tile
+            const float delta = grow ? mt : 0.f;   // not SPLIT: every row sees a key of the first tile, finite there
+            const float alpha = fresh ? 1.f : __builtin_amdgcn_exp2f(-delta);   // O and the row sum are still zero for a fresh row
             m_run += delta;
             lsum *= alpha;
 #pragma unroll
@@ -250,6 +267,19 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     TileIter it1;
     it1.first(sl, wg_imax);
     if (!it1.valid(sl)) return;          // cannot happen: the chunk itself is always a segment
+    // this lane's row of the partial results
+    const size_t prow = ((((size_t)split * BH + bh) * n_tiles + tile) * BM) + wave * 32 + l32;
+    if (SPLIT) {
+        const int tb = (int)((long long)NT * split / n_split), te = (int)((long long)NT * (split + 1) / n_split);
+        if (tb == te) {                  // nothing to do (uniform for the workgroup): an empty partial result
+            if (half == 0) { part_ml[prow * 2] = 0.f; part_ml[prow * 2 + 1] = 0.f; }
+            return;
+        }
+        for (int i = 0; i < tb; ++i) it1.next(sl, wg_imax);
+        kt_bh += (size_t)tb * TILE;
+        vt_bh += (size_t)tb * TILE;
+        NT = te - tb;
+    }
 
     // Copies.  Batch t is K of tile t+4 and V of tile t+3, each into the stage of the tile four
     // before it.  A wave issues its share of batch t at the start of its vector block t (those
@@ -295,7 +325,16 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     wait_vm<0>();
     __syncthreads();
     qk_tile(Ks);
-    softmax_tile(it1, true);    // every wave sees the first tile
+    if (!SPLIT || wave_active(it1)) {
+        softmax_tile(it1, true);    // not SPLIT: every wave sees the first tile
+    } else {
+#pragma unroll
+        for (int qt = 0; qt < 4; ++qt)
+#pragma unroll
+            for (int x = 0; x < 4; ++x) pf[qt].u[x] = 0u;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) negm[j] = 0.f;
+    }
     it1.next(sl, wg_imax);
     __syncthreads();      // barrier 0: every wave has read K of tile 0, its buffer may be refilled
 #pragma unroll
@@ -365,6 +404,18 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     }
     // normalise and store: this lane owns one query, columns 32*db + 8*(j/4) + 4*half + j%4
     const float lt = lsum + __shfl_xor(lsum, 32, 64);
+    if (SPLIT) {
+        float* prow_o = part_o + prow * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int jq = 0; jq < 4; ++jq) {
+                const float4 w = {o[db][jq * 4 + 0], o[db][jq * 4 + 1], o[db][jq * 4 + 2], o[db][jq * 4 + 3]};
+                *reinterpret_cast<float4*>(prow_o + db * 32 + jq * 8 + half * 4) = w;
+            }
+        if (half == 0) { part_ml[prow * 2] = m_run; part_ml[prow * 2 + 1] = lt; }
+        return;
+    }
     if (qvalid) {
         const float inv = 1.f / lt;
         bf16_t* orow = out + (((size_t)b * Q + qi) * g.Hq + qh) * D;
@@ -403,17 +454,77 @@ bool launch_kv_pack(const Geom& g, const DevBuffers& b, const SegList& sl, int Q
     return true;
 }
 
+// out = sum_s O_s 2^(m_s - M) / sum_s l_s 2^(m_s - M), M = max over the splits that saw a key;
+// one workgroup of D threads per (KV head, query row of the group).
+template <int D>
+__global__ __launch_bounds__(D) void attn_merge_kernel(Geom g, int Q, int n_tiles, int n_split, int BM,
+                                                       const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                                                       bf16_t* __restrict__ out, float* __restrict__ lse)
+{
+    const int BH = g.B * g.Hkv;
+    const int bh = blockIdx.y, r = blockIdx.x;            // r = head-in-group * Q + token
+    const int b = bh / g.Hkv, hk = bh % g.Hkv, qh = hk * g.G + r / Q, qi = r % Q;
+    const int tile = r / BM, within = r % BM, e = threadIdx.x;
+    float M = -INFINITY;
+    for (int s = 0; s < n_split; ++s) {
+        const size_t prow = (((size_t)s * BH + bh) * n_tiles + tile) * BM + within;
+        if (part_ml[prow * 2 + 1] > 0.f) M = fmaxf(M, part_ml[prow * 2]);
+    }
+    float L = 0.f, acc = 0.f;
+    for (int s = 0; s < n_split; ++s) {
+        const size_t prow = (((size_t)s * BH + bh) * n_tiles + tile) * BM + within;
+        const float ls = part_ml[prow * 2 + 1];
+        if (ls > 0.f) {
+            const float w = __builtin_amdgcn_exp2f(part_ml[prow * 2] - M);
+            L += ls * w;
+            acc += part_o[prow * D + e] * w;
+        }
+    }
+    out[(((size_t)b * Q + qi) * g.Hq + qh) * D + e] = f32_to_bf16(acc / L);
+    if (e == 0) lse[((size_t)b * g.Hq + qh) * Q + qi] = M * 0.6931471805599453f + logf(L);
+}
+
+// Workgroups per (row block, KV head) so that a small launch still fills the chip: none for 256
+// workgroups or more.
+int attn_splits(const Geom& g, int Q)
+{
+    const char* forced = getenv("CASCADE_KV_ATTN_SPLITS");   // debug switch, read at every launch
+    constexpr int BM = kSWaves * 32;
+    const int wgs = ((g.G * Q + BM - 1) / BM) * g.B * g.Hkv;
+    int n = forced ? atoi(forced) : 256 / wgs;
+    if (n > 256 / wgs) n = 256 / wgs;       // the partial results are sized for 256 workgroups
+    if (n > kMaxAttnSplits) n = kMaxAttnSplits;
+    return n < 1 ? 1 : n;
+}
+
 void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, void* out, hipStream_t s)
 {
     const int tiles_per_bh = packed_tiles(sl);
     constexpr int BM = kSWaves * 32;
     const int tiles = (g.G * Q + BM - 1) / BM;
-    const dim3 grid(tiles * g.B * g.Hkv), block(kSWaves * 64);
+    const int n_split = attn_splits(g, Q);
+    const dim3 grid(tiles * g.B * g.Hkv * n_split), block(kSWaves * 64);
+    if (n_split > 1) {
+        float* part_o = b.attn_part;
+        float* part_ml = b.attn_part + (size_t)kAttnPartRows * g.d;
+        if (g.d == 128) {
+            hipLaunchKernelGGL((attn_stream_kernel<128, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)b.Qr,
+                               (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, n_split, part_o, part_ml);
+            hipLaunchKernelGGL(attn_merge_kernel<128>, dim3(g.G * Q, g.B * g.Hkv), dim3(128), 0, s, g, Q, tiles, n_split, BM,
+                               part_o, part_ml, (bf16_t*)out, b.lse);
+        } else {
+            hipLaunchKernelGGL((attn_stream_kernel<64, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)b.Qr,
+                               (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, n_split, part_o, part_ml);
+            hipLaunchKernelGGL(attn_merge_kernel<64>, dim3(g.G * Q, g.B * g.Hkv), dim3(64), 0, s, g, Q, tiles, n_split, BM,
+                               part_o, part_ml, (bf16_t*)out, b.lse);
+        }
+        return;
+    }
     static const char* dbg_env = getenv("CASCADE_KV_ATTN_DEBUG");
     if (dbg_env && g.d == 128) {   // phase timing of one workgroup (development aid)
         long long* dbg = (long long*)b.logits;
-        hipLaunchKernelGGL((attn_stream_kernel<128, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)b.Qr,
-                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, dbg);
+        hipLaunchKernelGGL((attn_stream_kernel<128, true, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)b.Qr,
+                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, dbg, 1, (float*)nullptr, (float*)nullptr);
         long long h[16];
         (void)hipStreamSynchronize(s);
         (void)hipMemcpy(h, dbg, sizeof(h), hipMemcpyDeviceToHost);
@@ -424,11 +535,11 @@ void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, i
         return;
     }
     if (g.d == 128)
-        hipLaunchKernelGGL((attn_stream_kernel<128, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)b.Qr,
-                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr);
+        hipLaunchKernelGGL((attn_stream_kernel<128, false, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)b.Qr,
+                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, 1, (float*)nullptr, (float*)nullptr);
     else
-        hipLaunchKernelGGL((attn_stream_kernel<64, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)b.Qr,
-                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr);
+        hipLaunchKernelGGL((attn_stream_kernel<64, false, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)b.Qr,
+                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, 1, (float*)nullptr, (float*)nullptr);
 }
 
 }  // namespace ckv

@@ -5,6 +5,10 @@
 
 namespace ckv {
 
+// A split attention launch has at most 256 workgroups of 256 rows.
+constexpr int kAttnPartRows = 256 * 256;
+constexpr int kMaxAttnSplits = 8;
+
 // Device memory of one context, carved out of the caller's workspace.
 struct DevBuffers {
     // cache
@@ -26,6 +30,7 @@ struct DevBuffers {
     void* Vt;        // [B,Hkv,vt_tiles,d,64] the same for V, every tile transposed
     float* lse;      // [B,Hq,max_chunk] log-sum-exp of every query row (natural log, scaled logits)
     float* mu_chunk; // [B,Hkv,max_chunk] scores of the chunk's tokens
+    float* attn_part;// [kAttnPartRows, d + 2] bf16 MFMA path: partial outputs, maxima and row sums of a split attention launch
     float* negt;     // [B,Hq,max_chunk+64] bf16 MFMA path: exponent offsets of the score sums (-inf: row does not contribute)
     int32_t* offers; // [B,Hkv,2,max_chunk]
     int32_t* winners;// [B,Hkv,N,max_chunk+1]

@@ -70,9 +70,23 @@ def test_tiny_f32_free_running(oracle_mod):
          sizes=[24], chunks=[10] * 8, max_chunk=10, token_selection=0),
     dict(name="f32_all_rows_in_scores", dtype=B.CASCADE_F32, d=64, Hq=2, Hkv=1, batch=1, n_sink=2,
          sizes=[16, 16], chunks=[40] * 5, max_chunk=40, beta=0.999, score_tail_eps=-1.0),
+    # the same launch shapes with the attention kept in one workgroup per row block (small
+    # launches are otherwise split over the keys), and with an odd number of splits
+    dict(name="bf16_d128_ragged_unsplit", dtype=B.CASCADE_BF16, d=128, Hq=8, Hkv=2, batch=1, n_sink=5,
+         sizes=[48, 40, 36], chunks=[1, 7, 64, 100, 33, 128, 128, 2, 90, 128, 128, 77, 128, 128, 128], max_chunk=128,
+         attn_splits=1),
+    dict(name="bf16_big_tiles_unsplit", dtype=B.CASCADE_BF16, d=128, Hq=8, Hkv=2, batch=1, n_sink=64,
+         sizes=[256, 256, 256, 256], chunks=[512] * 8, max_chunk=512, attn_splits=1),
+    dict(name="bf16_big_tiles_three_splits", dtype=B.CASCADE_BF16, d=128, Hq=8, Hkv=2, batch=1, n_sink=64,
+         sizes=[256, 256, 256, 256], chunks=[512] * 8, max_chunk=512, attn_splits=3),
+    dict(name="bf16_rising_logits_unsplit", dtype=B.CASCADE_BF16, d=64, Hq=4, Hkv=2, batch=1, n_sink=4,
+         sizes=[96, 96, 96], chunks=[256] * 6, max_chunk=256, input_scale=1.5, key_ramp=2.0, tol_out=0.1, tol_score=0.3,
+         attn_splits=1),
 ], ids=lambda c: c["name"])
-def test_prefill_one_step_ahead(oracle_mod, case):
+def test_prefill_one_step_ahead(oracle_mod, case, monkeypatch):
     from gpu_harness import ParityRun
+    if "attn_splits" in case:
+        monkeypatch.setenv("CASCADE_KV_ATTN_SPLITS", str(case["attn_splits"]))
     cfg = B.make_config(batch=case["batch"], n_q_heads=case["Hq"], n_kv_heads=case["Hkv"], head_dim=case["d"],
                         dtype=case["dtype"], n_sink=case["n_sink"], cascade_sizes=case["sizes"],
                         ema_beta=case.get("beta", 0.9), rope_base=10000.0, max_chunk=case["max_chunk"],
