@@ -672,14 +672,14 @@ __global__ __launch_bounds__(kDecThreads, 1) void decode_pv_mfma_kernel(
         for (int x = 0; x < St::kVCopies; ++x) {
             const int row = x * RPI + l / PPR;
             const int piece = (l % PPR) ^ PvSwizzle<D>::of(row);
-            async_copy_1k(vsrc, (uint32_t)((min(row, nvalid - 1) * PPR + piece) * 16),
-                          __builtin_amdgcn_readfirstlane(dst + x * 1024u));
+            async_copy_1k_stream(vsrc, (uint32_t)((min(row, nvalid - 1) * PPR + piece) * 16),
+                                 __builtin_amdgcn_readfirstlane(dst + x * 1024u));
         }
         const float* lsrc = lbase + (size_t)t.r0 * MAXG;
 #pragma unroll
         for (int x = 0; x < St::kLogitCopies; ++x)
-            async_copy_256(lsrc, (uint32_t)(min(x * 64 + l, nvalid * MAXG - 1) * 4),
-                           __builtin_amdgcn_readfirstlane(dst + St::kLgOff + x * 256u));
+            async_copy_256_stream(lsrc, (uint32_t)(min(x * 64 + l, nvalid * MAXG - 1) * 4),
+                                  __builtin_amdgcn_readfirstlane(dst + St::kLgOff + x * 256u));
         async_copy_256(mubh + phys, (uint32_t)(min(l, nvalid - 1) * 4), __builtin_amdgcn_readfirstlane(dst + St::kMuOff));
     };
 
@@ -843,8 +843,8 @@ __global__ __launch_bounds__(kDecThreads, 1) void decode_qk_stream_kernel(
         for (int x = 0; x < NC; ++x) {
             const int row = x * RPI + l / PPR;
             const int piece = (l % PPR) ^ QkSwizzle<D>::of(row);
-            async_copy_1k(ksrc, (uint32_t)((min(row, nvalid - 1) * PPR + piece) * 16),
-                          __builtin_amdgcn_readfirstlane(dst + x * 1024u));
+            async_copy_1k_stream(ksrc, (uint32_t)((min(row, nvalid - 1) * PPR + piece) * 16),
+                                 __builtin_amdgcn_readfirstlane(dst + x * 1024u));
         }
     };
 
