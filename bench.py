@@ -58,6 +58,7 @@ def prefill_bench(args, torch, B, wl):
     for c in range(W):
         cache.prefill_chunk(*chunks[c], out=out)
     torch.cuda.synchronize()
+    accepted_before = cache.read_state().accepted.copy()
     B.cascade_profile_begin(cache.ctx)
     t0 = time.perf_counter()
     for c in range(W, W + K):
@@ -70,6 +71,14 @@ def prefill_bench(args, torch, B, wl):
     Q, d = wl.chunk, wl.head_dim
     # algorithmic work of the attention kernel: one QK^T and one PV over the visible pairs
     flops = [4.0 * d * wl.n_q_heads * wl.batch * (Q * n_before[c] + Q * (Q + 1) / 2) for c in range(W, W + K)]
+    # cache update (Alg. 2 as row moves): rows that arrived at an accepting step of a cascade in the
+    # timed region (the host-visible count; a token that wins a selection moves one more row, so this
+    # is a lower bound), each read once (K, V, score, id) and written once (K, rotated K, V, score, id)
+    esz = 2 if wl.dtype == "bf16" else 4
+    moved = int((cache.read_state().accepted - accepted_before).sum()) * wl.n_kv_heads * wl.batch
+    upd_ms, upd_n = prof["update"]
+    upd_bytes = moved * ((2 * d * esz + 8) + (3 * d * esz + 8))
+    upd_rate = upd_bytes / (upd_ms / 1e3) if upd_ms > 0 else 0.0
     attn_ms, attn_n = prof["attention"]
     avg_s = attn_ms / 1e3 / max(attn_n, 1)
     achieved = (sum(flops) / K) / avg_s
@@ -81,6 +90,9 @@ def prefill_bench(args, torch, B, wl):
                      "traffic": stored_traffic("attn_stream_kernel_prefill_1m_hbm_traffic.json") if wl.name == "prefill_1m" else None,
                      "flop_per_launch": sum(flops) / K, "avg_launch_ms": avg_s * 1e3},
         "end_to_end_mfma_frac": (sum(flops) / seconds) / MFMA_BF16_PEAK,
+        "roofline_update": {"bound": "hbm", "kernel": "plan_kernel + move_kernel", "achieved": upd_rate / 1e9,
+                            "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": upd_rate / HBM_PEAK,
+                            "rows_moved_per_step": moved / max(K, 1), "avg_ms_per_step": upd_ms / max(upd_n, 1)},
     }
     return res, cache, chunks, cfg
 
@@ -207,7 +219,7 @@ def main():
                    "cascades": list(wl.cascade_sizes), "n_q_heads": wl.n_q_heads, "n_kv_heads": wl.n_kv_heads,
                    "head_dim": wl.head_dim, "ema_beta": wl.ema_beta, "timed_chunks": [args.warmup, args.warmup + args.steps]},
         "roofline": res["roofline"], "kernel_ms_per_step": res["kernel_ms_per_step"],
-        "end_to_end_mfma_frac": res["end_to_end_mfma_frac"],
+        "end_to_end_mfma_frac": res["end_to_end_mfma_frac"], "roofline_update": res["roofline_update"],
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(args, torch, B, wl, cache, cfg, chunks)
