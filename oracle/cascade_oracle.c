@@ -16,7 +16,7 @@
  *   - GQA: one decision per KV head, query heads of a group reduced by max
  *     (or mean): Appendix "Head Policy and Head Reduction".
  *
- * Readings taken where the paper is silent (each is listed in the design doc):
+ * Readings taken where the paper is silent:
  *   R1  a cascade with period f accepts when (t mod f) == 0, where t counts the
  *       tokens offered to the first cascade so far (sink insertions excluded).
  *   R2  the scores of a chunk are the exact softmax probabilities (final

@@ -18,7 +18,9 @@ from paper_2406_17808_amd.workloads import WORKLOADS, chunk_inputs, chunk_inputs
 
 pytestmark = pytest.mark.gpu
 
-TOL_OUT, TOL_SCORE = 2e-2, 6e-2     # bf16 (parity)
+# bf16: outputs to the bar of the benchmark spec; scores: same arithmetic (operand rounding of the
+# rotated q and k, 2^-9 each, over d terms) with headroom for sums of few terms
+TOL_OUT, TOL_SCORE = 2e-2, 6e-2
 
 
 def _host(x):
