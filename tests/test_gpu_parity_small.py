@@ -142,6 +142,47 @@ def test_prefill_then_decode(oracle_mod, dtype, d, hq, hkv):
     run.close()
 
 
+@pytest.mark.parametrize("seed", list(range(12)))
+def test_random_geometries(oracle_mod, seed):
+    """Seeded random geometries (heads, head_dim, sinks, cascade count and sizes, periods, chunk
+    mix, decay) through prefill and decode, one step ahead of the oracle: sizes that are not
+    multiples of any tile, partly filled cascades, chunks from 1 token to several tiles."""
+    from gpu_harness import ParityRun
+    rng = np.random.default_rng(1000 + seed)
+    d = int(rng.choice([64, 128]))
+    hkv = int(rng.choice([1, 2, 3]))
+    G = int(rng.choice([1, 2, 4, 5, 8]))
+    N = int(rng.integers(1, 6))
+    sizes = [int(rng.integers(3, 150)) for _ in range(N)]
+    periods = None
+    if rng.random() < 0.4:
+        periods = [1] + [int(rng.integers(1, 5)) for _ in range(N - 1)]
+    max_chunk = int(rng.choice([17, 64, 130, 300]))
+    cfg = B.make_config(batch=int(rng.choice([1, 2])), n_q_heads=hkv * G, n_kv_heads=hkv, head_dim=d,
+                        dtype=B.CASCADE_BF16, n_sink=int(rng.integers(0, 9)), cascade_sizes=sizes,
+                        ema_beta=float(rng.choice([0.5, 0.9, 0.99, 0.999])), rope_base=10000.0, max_chunk=max_chunk,
+                        accept_period=periods, head_reduce=int(rng.integers(0, 2)),
+                        token_selection=int(rng.random() < 0.85), keep_update_scores=1)
+    tol_out, tol_score = _tolerances(cfg)
+    run = ParityRun(cfg, one_step_ahead=True)
+    worst_out = worst_score = 0.0
+    drift = compared = 0
+    for step in range(14):
+        decode = rng.random() < 0.3
+        n = 1 if decode else int(rng.integers(1, max_chunk + 1))
+        q, k, v = _inputs(rng, cfg, n)
+        rep = run.step(q, k, v, decode=decode)
+        assert rep.replay_exact, (seed, step)
+        worst_out, worst_score = max(worst_out, rep.out_err), max(worst_score, rep.score_err)
+        drift += rep.drift
+        compared += rep.compared
+    print(f"random geometry {seed}: d={d} heads {hkv * G}/{hkv} sinks {cfg.n_sink} sizes {sizes} periods {periods} "
+          f"max_chunk {max_chunk}: out {worst_out:.3e} score {worst_score:.3e} drift {drift}/{compared}")
+    assert worst_out <= tol_out and worst_score <= tol_score
+    assert drift <= 0.02 * max(compared, 1)
+    run.close()
+
+
 def test_layers_share_scratch_without_interfering(oracle_mod):
     """Three layers over one workspace (the layer loop of Alg. 1), fed different inputs in turn,
     prefill and decode: the middle layer is compared with the oracle at every step, the outer
