@@ -426,20 +426,21 @@ extern "C" int cascade_prefill_chunk(cascade_ctx* ctx, const void* dev_q, const 
 
     SegList sl;
     build_segments(g, ctx->st, true, Q, sl);
+    // the MFMA kernels take logits directly as base-2 exponents
+    const float qscale = ctx->mfma ? g.scale * 1.4426950408889634f : 1.f;
+    const int tail = Q < ctx->tail_k ? Q : ctx->tail_k;    // rows that carry weight in the score sums
     {
         Timed t(ctx, CASCADE_K_PREP, s);
-        // the MFMA kernels take logits directly as base-2 exponents
-        const float qscale = ctx->mfma ? g.scale * 1.4426950408889634f : 1.f;
-        launch_prep(g, ctx->dtype, ctx->buf, sl, Q, qscale, dev_q, dev_k, dev_v, s);
+        // bf16: the attention kernel rotates its queries itself; only the score kernel reads rotated copies
+        launch_prep(g, ctx->dtype, ctx->buf, sl, Q, qscale, ctx->mfma ? Q - tail : 0, dev_q, dev_k, dev_v, s);
         if (ctx->mfma && !launch_kv_pack(g, ctx->buf, sl, Q, s))
             return fail(ctx, CASCADE_E_WORKSPACE_TOO_SMALL, "cascade_prefill_chunk: packed K/V buffers too small for this segment list");
     }
     {
         Timed t(ctx, CASCADE_K_ATTENTION, s);
-        if (ctx->mfma) launch_attn_stream(g, ctx->buf, sl, Q, dev_out, s);
+        if (ctx->mfma) launch_attn_stream(g, ctx->buf, sl, Q, dev_q, qscale, dev_out, s);
         else launch_attn_simple(g, ctx->dtype, ctx->buf, sl, Q, ctx->max_chunk, dev_out, s);
     }
-    const int tail = Q < ctx->tail_k ? Q : ctx->tail_k;
     const float decay = (float)pow((double)g.beta, (double)Q);
     {
         Timed t(ctx, CASCADE_K_SCORES, s);

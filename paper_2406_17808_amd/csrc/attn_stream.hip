@@ -103,9 +103,9 @@ __global__ __launch_bounds__(kPackThreads) void kv_pack_kernel(Geom g, SegList s
 // to part_o / part_ml, and attn_merge_kernel combines them.
 template <int D, bool DBG, bool SPLIT>
 __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
-    Geom g, SegList sl, int Q, int tiles_per_bh, const bf16_t* __restrict__ Qr, const bf16_t* __restrict__ Kt,
-    const bf16_t* __restrict__ Vt, bf16_t* __restrict__ out, float* __restrict__ lse, long long* dbg,
-    int n_split, float* __restrict__ part_o, float* __restrict__ part_ml)
+    Geom g, SegList sl, int Q, int tiles_per_bh, const bf16_t* __restrict__ q, const float2* __restrict__ rope, float qscale,
+    const bf16_t* __restrict__ Kt, const bf16_t* __restrict__ Vt, bf16_t* __restrict__ out, float* __restrict__ lse,
+    long long* dbg, int n_split, float* __restrict__ part_o, float* __restrict__ part_ml)
 {
     constexpr int BM = kSWaves * 32;       // query rows per workgroup
     constexpr int KS = D / 16;             // k-steps of S^T = K Q^T
@@ -181,11 +181,36 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
 #pragma unroll
     for (int g16 = 0; g16 < 4; ++g16) voff[g16] = (l32 * 8 + ((2 * g16 + half) ^ vkey)) * 8;
 
+    // The query of this lane, rotated for one segment: the stored keys are rotated to their slot
+    // index, so the query turns by (own cache index) - (cache index - slot index) of the segment,
+    // sl.qrot0[variant] + qi.  The fragment of step ks holds elements 16 ks + 8 half .. + 7, whose
+    // rotary partners (element + D/2) are the fragment of step ks + KS/2 of the same lane.  The
+    // arithmetic is that of prep_kernel (scale first, then the rotation, then one rounding), which
+    // writes the same values for the rows the score kernel reads.
     Frag qf[KS];
-    auto load_q = [&](const Seg& sg) {   // this segment's rotated copy of the queries
-        const bf16_t* qrow = Qr + ((((size_t)sg.qvar * g.B + b) * g.Hq + qh) * Q + qi) * D + half * 8;
+    auto load_q = [&](const Seg& sg) {
+        const bf16_t* qsrc = q + (((size_t)b * Q + qi) * g.Hq + qh) * D + half * 8;
+        const float2* cs = rope + (size_t)(sl.qrot0[sg.qvar] + qi) * (D / 2) + half * 8;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qf[ks].u = *reinterpret_cast<const u32x4_t*>(qrow + ks * 16);
+        for (int ks = 0; ks < KS / 2; ++ks) {
+            const u32x4_t lo = *reinterpret_cast<const u32x4_t*>(qsrc + ks * 16);
+            const u32x4_t hi = *reinterpret_cast<const u32x4_t*>(qsrc + ks * 16 + D / 2);
+            float y0[8], y1[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t wl = lo[j >> 1], wh = hi[j >> 1];
+                const float x0 = __uint_as_float((j & 1) ? (wl & 0xFFFF0000u) : (wl << 16)) * qscale;
+                const float x1 = __uint_as_float((j & 1) ? (wh & 0xFFFF0000u) : (wh << 16)) * qscale;
+                const float2 c = cs[ks * 16 + j];
+                y0[j] = x0 * c.x - x1 * c.y;
+                y1[j] = x1 * c.x + x0 * c.y;
+            }
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                qf[ks].u[x] = cvt_pk_bf16(y0[2 * x], y0[2 * x + 1]);
+                qf[ks + KS / 2].u[x] = cvt_pk_bf16(y1[2 * x], y1[2 * x + 1]);
+            }
+        }
     };
     f32x16_t s[2];   // S^T of one tile: 2 key blocks of 32 keys
     Frag pf[4];      // its probabilities, 16 keys each: [key block][half]
@@ -497,7 +522,8 @@ int attn_splits(const Geom& g, int Q)
     return n < 1 ? 1 : n;
 }
 
-void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, void* out, hipStream_t s)
+void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, const void* q, float qscale,
+                        void* out, hipStream_t s)
 {
     const int tiles_per_bh = packed_tiles(sl);
     constexpr int BM = kSWaves * 32;
@@ -508,12 +534,12 @@ void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, i
         float* part_o = b.attn_part;
         float* part_ml = b.attn_part + (size_t)kAttnPartRows * g.d;
         if (g.d == 128) {
-            hipLaunchKernelGGL((attn_stream_kernel<128, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)b.Qr,
+            hipLaunchKernelGGL((attn_stream_kernel<128, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
                                (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, n_split, part_o, part_ml);
             hipLaunchKernelGGL(attn_merge_kernel<128>, dim3(g.G * Q, g.B * g.Hkv), dim3(128), 0, s, g, Q, tiles, n_split, BM,
                                part_o, part_ml, (bf16_t*)out, b.lse);
         } else {
-            hipLaunchKernelGGL((attn_stream_kernel<64, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)b.Qr,
+            hipLaunchKernelGGL((attn_stream_kernel<64, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
                                (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, n_split, part_o, part_ml);
             hipLaunchKernelGGL(attn_merge_kernel<64>, dim3(g.G * Q, g.B * g.Hkv), dim3(64), 0, s, g, Q, tiles, n_split, BM,
                                part_o, part_ml, (bf16_t*)out, b.lse);
@@ -523,7 +549,7 @@ void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, i
     static const char* dbg_env = getenv("CASCADE_KV_ATTN_DEBUG");
     if (dbg_env && g.d == 128) {   // phase timing of one workgroup (development aid)
         long long* dbg = (long long*)b.logits;
-        hipLaunchKernelGGL((attn_stream_kernel<128, true, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)b.Qr,
+        hipLaunchKernelGGL((attn_stream_kernel<128, true, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
                            (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, dbg, 1, (float*)nullptr, (float*)nullptr);
         long long h[16];
         (void)hipStreamSynchronize(s);
@@ -535,10 +561,10 @@ void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, i
         return;
     }
     if (g.d == 128)
-        hipLaunchKernelGGL((attn_stream_kernel<128, false, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)b.Qr,
+        hipLaunchKernelGGL((attn_stream_kernel<128, false, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
                            (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, 1, (float*)nullptr, (float*)nullptr);
     else
-        hipLaunchKernelGGL((attn_stream_kernel<64, false, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)b.Qr,
+        hipLaunchKernelGGL((attn_stream_kernel<64, false, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
                            (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, 1, (float*)nullptr, (float*)nullptr);
 }
 

@@ -171,7 +171,7 @@ __device__ inline void rotate8(const float* x0, const float* x1, const float2* _
 }
 
 template <typename T>
-__global__ void prep_kernel(Geom g, SegList sl, int Q, float qscale, const float2* __restrict__ rope,
+__global__ void prep_kernel(Geom g, SegList sl, int Q, float qscale, int q_first_row, const float2* __restrict__ rope,
                             const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
                             T* __restrict__ Qr, T* __restrict__ Krc, T* __restrict__ Vch)
 {
@@ -187,6 +187,7 @@ __global__ void prep_kernel(Geom g, SegList sl, int Q, float qscale, const float
     const int i = (int)(r % Q), b = (int)(r / Q);
     float x0[8], x1[8];
     if (row < g.Hq) {
+        if (i < q_first_row) return;     // the attention kernel rotates its queries itself
         const int h = row;
         const size_t src = (((size_t)b * Q + i) * g.Hq + h) * g.d;
         Vec8<T>::load(q + src + e, x0);
@@ -217,7 +218,7 @@ __global__ void prep_kernel(Geom g, SegList sl, int Q, float qscale, const float
 
 // head dimensions that are not a multiple of 16: one thread per rotary pair
 template <typename T>
-__global__ void prep_pair_kernel(Geom g, SegList sl, int Q, float qscale, const float2* __restrict__ rope,
+__global__ void prep_pair_kernel(Geom g, SegList sl, int Q, float qscale, int q_first_row, const float2* __restrict__ rope,
                                  const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
                                  T* __restrict__ Qr, T* __restrict__ Krc, T* __restrict__ Vch)
 {
@@ -232,6 +233,7 @@ __global__ void prep_pair_kernel(Geom g, SegList sl, int Q, float qscale, const 
     r /= rows_per_tok;
     const int i = (int)(r % Q), b = (int)(r / Q);
     if (row < sl.n_qvar * g.Hq) {
+        if (i < q_first_row) return;
         const int vq = row / g.Hq, h = row % g.Hq;
         const size_t src = (((size_t)b * Q + i) * g.Hq + h) * g.d;
         const size_t dst = ((((size_t)vq * g.B + b) * g.Hq + h) * Q + i) * g.d;
@@ -256,7 +258,7 @@ __global__ void prep_pair_kernel(Geom g, SegList sl, int Q, float qscale, const 
     }
 }
 
-void launch_prep(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int Q, float qscale,
+void launch_prep(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int Q, float qscale, int q_first_row,
                  const void* q, const void* k, const void* v, hipStream_t s)
 {
     const dim3 block(256);
@@ -264,20 +266,20 @@ void launch_prep(const Geom& g, int dtype, const DevBuffers& b, const SegList& s
         const long n = (long)g.B * Q * (g.Hq + 2 * g.Hkv) * (g.d / 16);
         const dim3 grid((unsigned)((n + 255) / 256));
         if (dtype == CASCADE_F32)
-            hipLaunchKernelGGL(prep_kernel<float>, grid, block, 0, s, g, sl, Q, qscale, b.rope, (const float*)q, (const float*)k,
+            hipLaunchKernelGGL(prep_kernel<float>, grid, block, 0, s, g, sl, Q, qscale, q_first_row, b.rope, (const float*)q, (const float*)k,
                                (const float*)v, (float*)b.Qr, (float*)b.Krc, (float*)b.Vch);
         else
-            hipLaunchKernelGGL(prep_kernel<bf16_t>, grid, block, 0, s, g, sl, Q, qscale, b.rope, (const bf16_t*)q, (const bf16_t*)k,
+            hipLaunchKernelGGL(prep_kernel<bf16_t>, grid, block, 0, s, g, sl, Q, qscale, q_first_row, b.rope, (const bf16_t*)q, (const bf16_t*)k,
                                (const bf16_t*)v, (bf16_t*)b.Qr, (bf16_t*)b.Krc, (bf16_t*)b.Vch);
         return;
     }
     const long n = (long)g.B * Q * (sl.n_qvar * g.Hq + 2 * g.Hkv) * (g.d / 2);
     const dim3 grid((unsigned)((n + 255) / 256));
     if (dtype == CASCADE_F32)
-        hipLaunchKernelGGL(prep_pair_kernel<float>, grid, block, 0, s, g, sl, Q, qscale, b.rope, (const float*)q, (const float*)k,
+        hipLaunchKernelGGL(prep_pair_kernel<float>, grid, block, 0, s, g, sl, Q, qscale, q_first_row, b.rope, (const float*)q, (const float*)k,
                            (const float*)v, (float*)b.Qr, (float*)b.Krc, (float*)b.Vch);
     else
-        hipLaunchKernelGGL(prep_pair_kernel<bf16_t>, grid, block, 0, s, g, sl, Q, qscale, b.rope, (const bf16_t*)q,
+        hipLaunchKernelGGL(prep_pair_kernel<bf16_t>, grid, block, 0, s, g, sl, Q, qscale, q_first_row, b.rope, (const bf16_t*)q,
                            (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)b.Qr, (bf16_t*)b.Krc, (bf16_t*)b.Vch);
 }
 

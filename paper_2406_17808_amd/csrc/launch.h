@@ -51,7 +51,8 @@ void launch_wrow_table(float beta, float* wrow, int n, hipStream_t s);
 void launch_fill_i32(int32_t* p, size_t n, int32_t value, hipStream_t s);
 void launch_load_state(const Geom& g, int dtype, const DevBuffers& b, const void* k, const void* v,
                        const float* mu, const int32_t* ids, const int* counts, int total, hipStream_t s);
-void launch_prep(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int Q, float qscale,
+// q_first_row: the rotated query copies are written for chunk rows q_first_row .. Q-1 only
+void launch_prep(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int Q, float qscale, int q_first_row,
                  const void* q, const void* k, const void* v, hipStream_t s);
 void launch_plan(const Geom& g, const DevBuffers& b, const UpdatePlan& pl, int max_chunk, hipStream_t s);
 void launch_moves(const Geom& g, int dtype, const DevBuffers& b, const UpdatePlan& pl, int max_chunk,
@@ -65,9 +66,10 @@ void launch_score_simple(const Geom& g, int dtype, const DevBuffers& b, const Se
 
 // attention, bf16 MFMA (head_dim 64 or 128).  launch_kv_pack copies the keys and values of the
 // segment list into Kt / Vt, tile by tile (false if they do not hold that many tiles);
-// launch_attn_stream reads only those copies.
+// launch_attn_stream reads only those copies, and the caller's queries (q: [B,Q,Hq,d], rotated on the fly).
 bool launch_kv_pack(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, hipStream_t s);
-void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, void* out, hipStream_t s);
+void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, const void* q, float qscale,
+                        void* out, hipStream_t s);
 void launch_score_mfma(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, int max_chunk,
                        int tail_rows, float decay, hipStream_t s);
 
