@@ -90,7 +90,7 @@ def prefill_bench(args, torch, B, wl):
                      "traffic": stored_traffic("attn_stream_kernel_prefill_1m_hbm_traffic.json") if wl.name == "prefill_1m" else None,
                      "flop_per_launch": sum(flops) / K, "avg_launch_ms": avg_s * 1e3},
         "end_to_end_mfma_frac": (sum(flops) / seconds) / MFMA_BF16_PEAK,
-        "roofline_update": {"bound": "hbm", "kernel": "plan_kernel + move_kernel", "achieved": upd_rate / 1e9,
+        "roofline_update": {"bound": "hbm", "kernel": "plan_kernel + gather_kernel + scatter_kernel", "achieved": upd_rate / 1e9,
                             "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": upd_rate / HBM_PEAK,
                             "rows_moved_per_step": moved / max(K, 1), "avg_ms_per_step": upd_ms / max(upd_n, 1)},
     }

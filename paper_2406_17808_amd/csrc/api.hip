@@ -173,6 +173,8 @@ static WorkspaceBytes carve(const cascade_config* c, const Geom& g, char* state_
     b.attn_part = (float*)take(mfma ? (size_t)kAttnPartRows * (g.d + 2) * 4 : 0);
     b.offers = (int32_t*)take(BH * 2 * mc * 4);
     b.winners = (int32_t*)take(BH * g.N * (mc + 1) * 4);
+    const int move_stage_rows = (g.N + 1) * ((int)mc + 1);    // every cascade and the sinks: at most max_chunk + 1 entries each
+    b.move_stage = take(g.d % 16 == 0 ? BH * (size_t)move_stage_rows * (2 * g.d * elem + 8) : 0);
     b.logits = (float*)take(BH * ((size_t)g.slots + 1) * (size_t)(g.G <= 8 ? decode_logit_heads(g) : g.G) * 4);
     b.part = (float*)take(BHq * splits * 2 * 4);
     b.opart = (float*)take(BHq * splits * g.d * 4);
@@ -180,6 +182,7 @@ static WorkspaceBytes carve(const cascade_config* c, const Geom& g, char* state_
     b.rope_rows = rope_rows;
     b.dec_splits = splits;
     b.vt_tiles = vt_tiles;
+    b.move_stage_rows = move_stage_rows;
     if (out) *out = b;
     return bytes;
 }

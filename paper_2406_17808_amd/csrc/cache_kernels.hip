@@ -391,12 +391,159 @@ __global__ void move_kernel(Geom g, UpdatePlan pl, int c, int E, int extra, int 
     }
 }
 
-// Destinations of cascade c take sources from earlier cascades or from the chunk only (items
-// never move backwards), so writing the last cascade first keeps every source intact until it
-// has been read.
+// The moves of all cascades in two launches.  Every entry (cascade, index) names a destination
+// slot and a source; gather_kernel copies the sources that are cache rows (un-rotated key, value,
+// score, id: the state before the update) into a staging array, scatter_kernel then writes every
+// destination from the staging array or from the chunk's own tokens.  No launch both reads and
+// writes the cache, so the order of the cascades does not matter.
+struct MoveList {
+    int n, total;
+    int c[kMaxCascades + 1], first[kMaxCascades + 2], E[kMaxCascades + 1], extra[kMaxCascades + 1];
+};
+
+__device__ inline bool move_entry(const Geom& g, const UpdatePlan& pl, const MoveList& ml, int eg, int bh, int qstride,
+                                  const int32_t* __restrict__ winners, int* dst, int* ref)
+{
+    int i = 0;
+    while (i + 1 < ml.n && eg >= ml.first[i + 1]) ++i;
+    const int c = ml.c[i], e = eg - ml.first[i];
+    if (c < 0) {
+        *dst = pl.sink_fill0 + e;
+        *ref = g.slots + e;
+        return true;
+    }
+    const int32_t* W = winners + ((size_t)bh * pl.N + c) * (qstride + 1);
+    return final_entry(pl.c[c], e, ml.E[i], W, dst, ref);
+}
+
+// lanes = d/16 threads per row, each moving 8 elements of both halves of the head dimension
+template <typename T>
+__global__ void gather_kernel(Geom g, UpdatePlan pl, MoveList ml, int qstride, int stage_rows,
+                              const int32_t* __restrict__ winners, const T* __restrict__ Kc, const T* __restrict__ Vc,
+                              const float* __restrict__ mu, const int32_t* __restrict__ ids,
+                              T* __restrict__ stK, T* __restrict__ stV, float* __restrict__ stMu, int32_t* __restrict__ stId)
+{
+    const int lanes = g.d / 16, half = g.d / 2;
+    const int bh = blockIdx.y;
+    const int eg = blockIdx.x * (blockDim.x / lanes) + threadIdx.x / lanes;
+    const int lane = threadIdx.x % lanes;
+    if (eg >= ml.total) return;
+    int dst, ref;
+    if (!move_entry(g, pl, ml, eg, bh, qstride, winners, &dst, &ref)) return;
+    if (ref >= g.slots) return;          // a token of the chunk: read by scatter_kernel
+    const size_t srow = ((size_t)bh * g.slots + ref) * g.d, trow = ((size_t)bh * stage_rows + eg) * g.d;
+    float x[8];
+    Vec8<T>::load(Kc + srow + lane * 8, x);          Vec8<T>::store(stK + trow + lane * 8, x);
+    Vec8<T>::load(Kc + srow + half + lane * 8, x);   Vec8<T>::store(stK + trow + half + lane * 8, x);
+    Vec8<T>::load(Vc + srow + lane * 8, x);          Vec8<T>::store(stV + trow + lane * 8, x);
+    Vec8<T>::load(Vc + srow + half + lane * 8, x);   Vec8<T>::store(stV + trow + half + lane * 8, x);
+    if (lane == 0) {
+        stMu[(size_t)bh * stage_rows + eg] = mu[(size_t)bh * g.slots + ref];
+        stId[(size_t)bh * stage_rows + eg] = ids[(size_t)bh * g.slots + ref];
+    }
+}
+
+template <typename T>
+__global__ void scatter_kernel(Geom g, UpdatePlan pl, MoveList ml, int qstride, int stage_rows,
+                               const float2* __restrict__ rope, const int32_t* __restrict__ winners,
+                               const T* __restrict__ stK, const T* __restrict__ stV, const float* __restrict__ stMu,
+                               const int32_t* __restrict__ stId, const float* __restrict__ mu_chunk,
+                               const T* __restrict__ k_in, const T* __restrict__ v_in, long tok_stride, long batch_stride,
+                               T* __restrict__ Kc, T* __restrict__ Kr, T* __restrict__ Vc, float* __restrict__ mu,
+                               int32_t* __restrict__ ids)
+{
+    const int lanes = g.d / 16, half = g.d / 2;
+    const int bh = blockIdx.y;
+    const int b = bh / g.Hkv, h = bh % g.Hkv;
+    const int eg = blockIdx.x * (blockDim.x / lanes) + threadIdx.x / lanes;
+    const int lane = threadIdx.x % lanes;
+    if (eg >= ml.total) return;
+    int dst, ref;
+    if (!move_entry(g, pl, ml, eg, bh, qstride, winners, &dst, &ref)) return;
+    const T *ks, *vs;
+    float score;
+    int id;
+    if (ref < g.slots) {
+        const size_t trow = ((size_t)bh * stage_rows + eg) * g.d;
+        ks = stK + trow;
+        vs = stV + trow;
+        score = stMu[(size_t)bh * stage_rows + eg];
+        id = stId[(size_t)bh * stage_rows + eg];
+    } else {
+        const int i = ref - g.slots;
+        const size_t srow = (size_t)b * batch_stride + (size_t)i * tok_stride + (size_t)h * g.d;
+        ks = k_in + srow;
+        vs = v_in + srow;
+        score = mu_chunk[(size_t)bh * qstride + i];
+        id = pl.id0 + i;
+    }
+    const size_t drow = ((size_t)bh * g.slots + dst) * g.d;
+    const int e = lane * 8;
+    float x0[8], x1[8];
+    Vec8<T>::load(ks + e, x0);
+    Vec8<T>::load(ks + half + e, x1);
+    Vec8<T>::store(Kc + drow + e, x0);
+    Vec8<T>::store(Kc + drow + half + e, x1);
+    rotate8<T>(x0, x1, rope + (size_t)dst * half + e, Kr + drow + e, Kr + drow + half + e);
+    Vec8<T>::load(vs + e, x0);
+    Vec8<T>::load(vs + half + e, x1);
+    Vec8<T>::store(Vc + drow + e, x0);
+    Vec8<T>::store(Vc + drow + half + e, x1);
+    if (lane == 0) {
+        mu[(size_t)bh * g.slots + dst] = score;
+        ids[(size_t)bh * g.slots + dst] = id;
+    }
+}
+
+template <typename T>
+static void moves_two_phase(const Geom& g, const DevBuffers& b, const UpdatePlan& pl, const MoveList& ml, int max_chunk,
+                            const void* k, const void* v, int k_token_stride, int k_batch_stride, hipStream_t s)
+{
+    const int lanes = g.d / 16, threads = 256, rows = threads / lanes;
+    const dim3 grid((ml.total + rows - 1) / rows, g.B * g.Hkv), block(threads);
+    const size_t BH = (size_t)g.B * g.Hkv;
+    T* stK = (T*)b.move_stage;
+    T* stV = stK + BH * b.move_stage_rows * g.d;
+    float* stMu = (float*)(stV + BH * b.move_stage_rows * g.d);
+    int32_t* stId = (int32_t*)(stMu + BH * b.move_stage_rows);
+    hipLaunchKernelGGL(gather_kernel<T>, grid, block, 0, s, g, pl, ml, max_chunk, b.move_stage_rows, b.winners,
+                       (const T*)b.Kc, (const T*)b.Vc, b.mu, b.ids, stK, stV, stMu, stId);
+    hipLaunchKernelGGL(scatter_kernel<T>, grid, block, 0, s, g, pl, ml, max_chunk, b.move_stage_rows, b.rope, b.winners,
+                       (const T*)stK, (const T*)stV, stMu, stId, b.mu_chunk, (const T*)k, (const T*)v,
+                       (long)k_token_stride, (long)k_batch_stride, (T*)b.Kc, (T*)b.Kr, (T*)b.Vc, b.mu, b.ids);
+}
+
+// Head dimensions that are not a multiple of 16 take one launch per cascade: destinations of
+// cascade c take sources from earlier cascades or from the chunk only (items never move
+// backwards), so writing the last cascade first keeps every source intact until it has been read.
 void launch_moves(const Geom& g, int dtype, const DevBuffers& b, const UpdatePlan& pl, int max_chunk,
                   const void* k, const void* v, int k_token_stride, int k_batch_stride, hipStream_t s)
 {
+    if (g.d % 16 == 0 && b.move_stage) {
+        MoveList ml;
+        ml.n = 0;
+        ml.total = 0;
+        for (int c = pl.N - 1; c >= -1; --c) {
+            int E, extra = 0;
+            if (c < 0) {
+                E = pl.n_to_sink;
+            } else {
+                if (pl.c[c].M == 0) continue;
+                E = final_entries(pl.c[c], &extra);
+            }
+            if (E + extra == 0) continue;
+            ml.c[ml.n] = c; ml.first[ml.n] = ml.total; ml.E[ml.n] = E; ml.extra[ml.n] = extra;
+            ml.total += E + extra;
+            ++ml.n;
+        }
+        ml.first[ml.n] = ml.total;
+        if (ml.total == 0) return;
+        if (ml.total <= b.move_stage_rows) {
+            if (dtype == CASCADE_F32) moves_two_phase<float>(g, b, pl, ml, max_chunk, k, v, k_token_stride, k_batch_stride, s);
+            else moves_two_phase<bf16_t>(g, b, pl, ml, max_chunk, k, v, k_token_stride, k_batch_stride, s);
+            return;
+        }
+    }
     const int lanes = 32, threads = 256, rows = threads / lanes;
     for (int c = pl.N - 1; c >= -1; --c) {
         int E, extra = 0;

@@ -34,6 +34,8 @@ struct DevBuffers {
     float* negt;     // [B,Hq,max_chunk+64] bf16 MFMA path: exponent offsets of the score sums (-inf: row does not contribute)
     int32_t* offers; // [B,Hkv,2,max_chunk]
     int32_t* winners;// [B,Hkv,N,max_chunk+1]
+    void* move_stage;// [B,Hkv,move_stage_rows] x (K row, V row, score, id): sources of the update's moves, gathered before any is overwritten
+    int move_stage_rows;
     // decode scratch
     float* logits;   // [B,Hkv,slots+1,decode_logit_heads]
     float* part;     // [B,Hq,dec_splits,2] (max, sum) of every split
