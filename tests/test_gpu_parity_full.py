@@ -154,6 +154,48 @@ def test_other_experiment_geometries(oracle_mod, name, n_chunks, compare, kv_hea
     run.close()
 
 
+def test_mid_size_batch_two_mixed_prefill_and_decode(oracle_mod):
+    """Two sequences, 16 query heads on 2 KV heads (group size 8), head_dim 64, 32 sinks + 3 x 1024,
+    chunks of 512 then decode steps: whole chunks and steps compared on both sequences, free of the
+    one-step-ahead reload only between compared steps."""
+    from gpu_harness import ParityRun, to_device
+    cfg = B.make_config(batch=2, n_q_heads=16, n_kv_heads=2, head_dim=64, dtype=B.CASCADE_BF16, n_sink=32,
+                        cascade_sizes=[1024, 1024, 1024], ema_beta=0.99, rope_base=500000.0, max_chunk=512,
+                        keep_update_scores=1)
+    run = ParityRun(cfg, one_step_ahead=True)
+    rng = np.random.default_rng(77)
+    from paper_2406_17808_amd.workloads import round_to_bf16
+
+    def draw(n):
+        return tuple(round_to_bf16(rng.standard_normal((2, n, h, 64)).astype(np.float32)) for h in (16, 2, 2))
+
+    plan = [("p", 512)] * 9 + [("d", 1)] * 3 + [("p", 300)] + [("d", 1)] * 2
+    compare = {0, 3, 8, 9, 11, 12, 14}
+    worst_out = worst_score = 0.0
+    drift = compared = 0
+    for i, (kind, n) in enumerate(plan):
+        q, k, v = draw(n)
+        if i in compare:
+            if i - 1 not in compare and i > 0:
+                run.sync_oracle_from_gpu()
+            print(f"mid size: comparing step {i} ({kind}, {n} tokens)", flush=True)
+            rep = run.step(q, k, v, decode=(kind == "d"))
+            assert rep.replay_exact, i
+            worst_out, worst_score = max(worst_out, rep.out_err), max(worst_score, rep.score_err)
+            drift += rep.drift
+            compared += rep.compared
+        else:
+            dq, dk, dv = (to_device(x, cfg) for x in (q, k, v))
+            if kind == "d":
+                run.advance_gpu_only(dq[:, 0].contiguous(), dk[:, 0].contiguous(), dv[:, 0].contiguous(), decode=True)
+            else:
+                run.advance_gpu_only(dq, dk, dv)
+    print(f"mid size: out {worst_out:.3e} score {worst_score:.3e} drift {drift}/{compared}")
+    assert worst_out <= TOL_OUT and worst_score <= TOL_SCORE
+    assert drift <= 0.02 * compared
+    run.close()
+
+
 def _step_two_heads(run, q, k, v):
     """run.step, but with the oracle evaluating only the listed (non-adjacent) KV heads, each
     on its own thread."""
