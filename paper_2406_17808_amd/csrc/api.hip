@@ -167,6 +167,7 @@ static WorkspaceBytes carve(const cascade_config* c, const Geom& g, char* state_
     const int vt_tiles = mfma ? (g.slots + (int)mc) / 64 + kMaxSegments : 0;
     b.Kt = take(BH * (size_t)vt_tiles * 64 * g.d * elem);
     b.Vt = take(BH * (size_t)vt_tiles * 64 * g.d * elem);
+    b.knorm2 = (float*)take(BH * (size_t)vt_tiles * 4);
     b.lse = (float*)take(BHq * mc * 4);
     b.mu_chunk = (float*)take(BH * mc * 4);
     b.negt = (float*)take(mfma ? BHq * (mc + 64) * 4 : 0);

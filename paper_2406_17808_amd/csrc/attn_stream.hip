@@ -50,10 +50,12 @@ template <int D>
 __global__ __launch_bounds__(kPackThreads) void kv_pack_kernel(Geom g, SegList sl, int Q, int tiles_per_bh,
                                                                const bf16_t* __restrict__ Kr, const bf16_t* __restrict__ Krc,
                                                                const bf16_t* __restrict__ Vc, const bf16_t* __restrict__ Vch,
-                                                               bf16_t* __restrict__ Kt, bf16_t* __restrict__ Vt)
+                                                               bf16_t* __restrict__ Kt, bf16_t* __restrict__ Vt,
+                                                               float* __restrict__ Knorm2)
 {
     constexpr int STR = D + 8;   // LDS row stride in elements: 16-byte aligned rows
     __shared__ __attribute__((aligned(16))) bf16_t T[kBN * STR];
+    __shared__ float wave_max[kPackThreads / 64];
     const int BH = g.B * g.Hkv;
     const int bh = blockIdx.x % BH, n = blockIdx.x / BH;
     int si = 0, first = 0;
@@ -70,6 +72,7 @@ __global__ __launch_bounds__(kPackThreads) void kv_pack_kernel(Geom g, SegList s
     const bf16_t* ksrc = (sg.chunk ? Krc : Kr) + row0 * D;
     bf16_t* kdst = Kt + ((size_t)bh * tiles_per_bh + n) * (kBN * D);
     const int tid = threadIdx.x;
+    float norm2_max = 0.f;
 #pragma unroll
     for (int p = tid; p < kBN * D / 8; p += kPackThreads) {
         const int r = p / (D / 8), c = p % (D / 8);
@@ -80,8 +83,28 @@ __global__ __launch_bounds__(kPackThreads) void kv_pack_kernel(Geom g, SegList s
         }
         *reinterpret_cast<u32x4_t*>(&T[r * STR + c * 8]) = v;
         *reinterpret_cast<u32x4_t*>(kdst + (size_t)p * 8) = k;   // position c of row r holds chunk c ^ key
+        // squared norm of the key row: the D/8 threads of a row are neighbours
+        float ss = 0.f;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            const float lo = __uint_as_float(k[x] << 16), hi = __uint_as_float(k[x] & 0xFFFF0000u);
+            ss += lo * lo + hi * hi;
+        }
+#pragma unroll
+        for (int w = D / 16; w > 0; w >>= 1) ss += __shfl_xor(ss, w, D / 8);
+        norm2_max = fmaxf(norm2_max, ss);
     }
+    // the largest squared key norm of the tile (the attention kernel bounds its logits with it)
+#pragma unroll
+    for (int w = 32; w > 0; w >>= 1) norm2_max = fmaxf(norm2_max, __shfl_xor(norm2_max, w, 64));
+    if ((tid & 63) == 0) wave_max[tid >> 6] = norm2_max;
     __syncthreads();
+    if (tid == 0) {
+        float m = wave_max[0];
+#pragma unroll
+        for (int w = 1; w < kPackThreads / 64; ++w) m = fmaxf(m, wave_max[w]);
+        Knorm2[(size_t)bh * tiles_per_bh + n] = m;
+    }
     bf16_t* dst = Vt + ((size_t)bh * tiles_per_bh + n) * (kBN * D);
 #pragma unroll
     for (int p = tid; p < D * 8; p += kPackThreads) {
@@ -105,7 +128,7 @@ template <int D, bool DBG, bool SPLIT>
 __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     Geom g, SegList sl, int Q, int tiles_per_bh, const bf16_t* __restrict__ q, const float2* __restrict__ rope, float qscale,
     const bf16_t* __restrict__ Kt, const bf16_t* __restrict__ Vt, bf16_t* __restrict__ out, float* __restrict__ lse,
-    long long* dbg, int n_split, float* __restrict__ part_o, float* __restrict__ part_ml)
+    long long* dbg, int n_split, float* __restrict__ part_o, float* __restrict__ part_ml, const float* __restrict__ Knorm2)
 {
     constexpr int BM = kSWaves * 32;       // query rows per workgroup
     constexpr int KS = D / 16;             // k-steps of S^T = K Q^T
@@ -115,6 +138,7 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     constexpr int PW = CH / kSWaves;       // 1 KB copies per wave and tile (2 or 1)
     __shared__ __attribute__((aligned(1024))) bf16_t Ks[kSStages * TILE];
     __shared__ __attribute__((aligned(1024))) bf16_t Vs[kSStages * TILE];
+    __shared__ float kn_wave[kSWaves];
 
     const int BH = g.B * g.Hkv;
     // consecutive workgroups: different KV heads; row blocks that see more of the chunk (longer loops) start first
@@ -156,6 +180,7 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     for (int j = 0; j < 16; ++j) negm[j] = 0.f;
     float lsum = 0.f;   // this lane's part of the row sum
     bool seen = false;  // SPLIT: this row has seen a key
+    bool bounded = false;   // see below: the per-tile maximum is not needed
 
     // The packed tiles are LDS images: every wave copies PW consecutive KB of each
     const uint32_t lds_k = lds_address(Ks) + (uint32_t)wave * PW * 1024u;
@@ -188,7 +213,9 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     // arithmetic is that of prep_kernel (scale first, then the rotation, then one rounding), which
     // writes the same values for the rows the score kernel reads.
     Frag qf[KS];
+    float qn2 = 0.f;      // this lane's half of the squared norm of its (scaled) query, summed by the first load_q
     auto load_q = [&](const Seg& sg) {
+        qn2 = 0.f;
         const bf16_t* qsrc = q + (((size_t)b * Q + qi) * g.Hq + qh) * D + half * 8;
         const float2* cs = rope + (size_t)(sl.qrot0[sg.qvar] + qi) * (D / 2) + half * 8;
 #pragma unroll
@@ -204,6 +231,7 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
                 const float2 c = cs[ks * 16 + j];
                 y0[j] = x0 * c.x - x1 * c.y;
                 y1[j] = x1 * c.x + x0 * c.y;
+                qn2 += x0 * x0 + x1 * x1;
             }
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
@@ -244,32 +272,34 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
                 for (int j = 0; j < 16; ++j)
                     if (kb * 32 + (j >> 2) * 8 + (j & 3) > rel) s[kb][j] = -INFINITY;
         }
-        float x = -INFINITY;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) x = fmaxf(x, s[kb][j]);
-        const float mt = max_xor32(x);
-        // SPLIT: a range may start with chunk tiles some rows do not see at all, so "first" is kept
-        // per row: until a row has seen a key its m_run stays 0 and everything it holds is zero
-        const bool fresh = SPLIT ? !seen : first;
-        const bool grow = SPLIT ? (fresh ? mt > -INFINITY : mt > kRescaleLog2) : (first || mt > kRescaleLog2);
-        if (SPLIT) seen = seen || mt > -INFINITY;
-        if (__any(grow)) {
-            const float delta = grow ? mt : 0.f;   // not SPLIT: every row sees a key of the first tile, finite there
-            const float alpha = fresh ? 1.f : __builtin_amdgcn_exp2f(-delta);   // O and the row sum are still zero for a fresh row
-            m_run += delta;
-            lsum *= alpha;
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) o[db][j] *= alpha;
+        if (!bounded || first) {   // bounded: no exponent of this workgroup can exceed m_run by more than 2^kBoundLog2
+            float x = -INFINITY;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int j = 0; j < 16; ++j) s[kb][j] -= delta;
+                for (int j = 0; j < 16; ++j) x = fmaxf(x, s[kb][j]);
+            const float mt = max_xor32(x);
+            // SPLIT: a range may start with chunk tiles some rows do not see at all, so "first" is kept
+            // per row: until a row has seen a key its m_run stays 0 and everything it holds is zero
+            const bool fresh = SPLIT ? !seen : first;
+            const bool grow = SPLIT ? (fresh ? mt > -INFINITY : mt > kRescaleLog2) : (first || mt > kRescaleLog2);
+            if (SPLIT) seen = seen || mt > -INFINITY;
+            if (__any(grow)) {
+                const float delta = grow ? mt : 0.f;   // not SPLIT: every row sees a key of the first tile, finite there
+                const float alpha = fresh ? 1.f : __builtin_amdgcn_exp2f(-delta);   // O and the row sum are still zero for a fresh row
+                m_run += delta;
+                lsum *= alpha;
 #pragma unroll
-            for (int j = 0; j < 16; ++j) negm[j] = -m_run;
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) o[db][j] *= alpha;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) s[kb][j] -= delta;
+#pragma unroll
+                for (int j = 0; j < 16; ++j) negm[j] = -m_run;
+            }
         }
 #pragma unroll
         for (int qt = 0; qt < 4; ++qt) {
@@ -289,6 +319,7 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     // and of K of tile t+3 are issued.  Only the softmax needs to know which segment a tile is from.
     int NT = 0;   // tiles this workgroup visits: chunk keys after its last row are never visible
     for (int i = 0; i < sl.n; ++i) NT += ((sl.s[i].chunk ? min(sl.s[i].len, wg_imax + 1) : sl.s[i].len) + kBN - 1) / kBN;
+    int tile_first = 0;                  // SPLIT: first tile of this workgroup's range
     TileIter it1;
     it1.first(sl, wg_imax);
     if (!it1.valid(sl)) return;          // cannot happen: the chunk itself is always a segment
@@ -301,6 +332,7 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
             return;
         }
         for (int i = 0; i < tb; ++i) it1.next(sl, wg_imax);
+        tile_first = tb;
         kt_bh += (size_t)tb * TILE;
         vt_bh += (size_t)tb * TILE;
         NT = te - tb;
@@ -347,8 +379,20 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
         if (n < NT) copy_tile(vt_bh, lds_v, n, n);
     load_q(it1.sg);
     int q_seg = it1.si;
+    // the largest squared key norm among the tiles of this workgroup
+    float kn2 = 0.f;
+    {
+        const float* kn = Knorm2 + (size_t)bh * tiles_per_bh + (SPLIT ? tile_first : 0);
+        for (int i = tid; i < NT; i += kSWaves * 64) kn2 = fmaxf(kn2, kn[i]);
+#pragma unroll
+        for (int w = 32; w > 0; w >>= 1) kn2 = fmaxf(kn2, __shfl_xor(kn2, w, 64));
+        if (l == 0) kn_wave[wave] = kn2;
+    }
+    const float qnorm2 = qn2 + __shfl_xor(qn2, 32, 64);
     wait_vm<0>();
     __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kSWaves; ++w) kn2 = fmaxf(kn2, kn_wave[w]);
     qk_tile(Ks);
     if (!SPLIT || wave_active(it1)) {
         softmax_tile(it1, true);    // not SPLIT: every wave sees the first tile
@@ -360,6 +404,11 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
 #pragma unroll
         for (int j = 0; j < 16; ++j) negm[j] = 0.f;
     }
+    // By Cauchy-Schwarz no exponent of this row exceeds |q| max|k| (the rotation keeps norms; 1 % for the
+    // rounding of the rotated operands).  If that is within kBoundLog2 of the maximum of the first
+    // tile for every row of the wave, probabilities stay below 2^kBoundLog2 whatever the later
+    // tiles hold, m_run can stay where it is, and the per-tile maximum is skipped.
+    if (!SPLIT) bounded = !__any(sqrtf(qnorm2 * kn2) * 1.01f > m_run + kBoundLog2);
     it1.next(sl, wg_imax);
     __syncthreads();      // barrier 0: every wave has read K of tile 0, its buffer may be refilled
 #pragma unroll
@@ -472,10 +521,10 @@ bool launch_kv_pack(const Geom& g, const DevBuffers& b, const SegList& sl, int Q
     const dim3 grid(tiles_per_bh * g.B * g.Hkv), block(kPackThreads);
     if (g.d == 128)
         hipLaunchKernelGGL(kv_pack_kernel<128>, grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)b.Kr, (const bf16_t*)b.Krc,
-                           (const bf16_t*)b.Vc, (const bf16_t*)b.Vch, (bf16_t*)b.Kt, (bf16_t*)b.Vt);
+                           (const bf16_t*)b.Vc, (const bf16_t*)b.Vch, (bf16_t*)b.Kt, (bf16_t*)b.Vt, b.knorm2);
     else
         hipLaunchKernelGGL(kv_pack_kernel<64>, grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)b.Kr, (const bf16_t*)b.Krc,
-                           (const bf16_t*)b.Vc, (const bf16_t*)b.Vch, (bf16_t*)b.Kt, (bf16_t*)b.Vt);
+                           (const bf16_t*)b.Vc, (const bf16_t*)b.Vch, (bf16_t*)b.Kt, (bf16_t*)b.Vt, b.knorm2);
     return true;
 }
 
@@ -535,12 +584,12 @@ void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, i
         float* part_ml = b.attn_part + (size_t)kAttnPartRows * g.d;
         if (g.d == 128) {
             hipLaunchKernelGGL((attn_stream_kernel<128, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
-                               (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, n_split, part_o, part_ml);
+                               (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, n_split, part_o, part_ml, b.knorm2);
             hipLaunchKernelGGL(attn_merge_kernel<128>, dim3(g.G * Q, g.B * g.Hkv), dim3(128), 0, s, g, Q, tiles, n_split, BM,
                                part_o, part_ml, (bf16_t*)out, b.lse);
         } else {
             hipLaunchKernelGGL((attn_stream_kernel<64, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
-                               (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, n_split, part_o, part_ml);
+                               (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, n_split, part_o, part_ml, b.knorm2);
             hipLaunchKernelGGL(attn_merge_kernel<64>, dim3(g.G * Q, g.B * g.Hkv), dim3(64), 0, s, g, Q, tiles, n_split, BM,
                                part_o, part_ml, (bf16_t*)out, b.lse);
         }
@@ -550,7 +599,7 @@ void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, i
     if (dbg_env && g.d == 128) {   // phase timing of one workgroup (development aid)
         long long* dbg = (long long*)b.logits;
         hipLaunchKernelGGL((attn_stream_kernel<128, true, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
-                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, dbg, 1, (float*)nullptr, (float*)nullptr);
+                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, dbg, 1, (float*)nullptr, (float*)nullptr, b.knorm2);
         long long h[16];
         (void)hipStreamSynchronize(s);
         (void)hipMemcpy(h, dbg, sizeof(h), hipMemcpyDeviceToHost);
@@ -562,10 +611,10 @@ void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, i
     }
     if (g.d == 128)
         hipLaunchKernelGGL((attn_stream_kernel<128, false, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
-                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, 1, (float*)nullptr, (float*)nullptr);
+                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, 1, (float*)nullptr, (float*)nullptr, b.knorm2);
     else
         hipLaunchKernelGGL((attn_stream_kernel<64, false, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
-                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, 1, (float*)nullptr, (float*)nullptr);
+                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, 1, (float*)nullptr, (float*)nullptr, b.knorm2);
 }
 
 }  // namespace ckv

@@ -28,6 +28,7 @@ struct DevBuffers {
     void* Vch;       // [B,Hkv,max_chunk,d] chunk values, head-major
     void* Kt;        // [B,Hkv,vt_tiles,64,d] bf16 MFMA path: rotated keys of cache and chunk, tile by tile
     void* Vt;        // [B,Hkv,vt_tiles,d,64] the same for V, every tile transposed
+    float* knorm2;   // [B,Hkv,vt_tiles] largest squared key norm of every packed tile
     float* lse;      // [B,Hq,max_chunk] log-sum-exp of every query row (natural log, scaled logits)
     float* mu_chunk; // [B,Hkv,max_chunk] scores of the chunk's tokens
     float* attn_part;// [kAttnPartRows, d + 2] bf16 MFMA path: partial outputs, maxima and row sums of a split attention launch

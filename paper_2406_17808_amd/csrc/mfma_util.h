@@ -45,6 +45,7 @@ __device__ inline float max_xor32(float x)
 
 constexpr int kBN = 64;               // keys per tile
 constexpr float kRescaleLog2 = 8.f;   // the running maximum is only raised when it grew by 2^8
+constexpr float kBoundLog2 = 90.f;    // exponents proven to stay this close to the running maximum need no tracking (2^90 x 2^17 keys < 2^127)
 
 // Iterates over the 64-key tiles of all segments.  All fields are workgroup-uniform.
 struct TileIter {
