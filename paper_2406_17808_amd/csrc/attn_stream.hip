@@ -5,7 +5,9 @@
 // visits them.  A packed tile is the exact LDS image the attention kernel wants: K with the
 // 16-byte chunks of a row XOR-swizzled, V transposed (a row is one column of V with its 64 keys),
 // so that the A operand of O^T = V^T P^T is a plain 16-byte LDS read.  The attention kernel then
-// needs no segment logic for its loads.
+// needs no segment logic for its loads.  The kernel also leaves the largest squared key norm of
+// every tile in Knorm2: with |q| it bounds every logit of a row, and a wave whose rows are all
+// bounded close to the maximum of their first tile does not track the maximum any further.
 //
 // attn_stream_kernel: a workgroup of eight waves owns 256 query rows, 32 per wave (one lane owns
 // one query: the transposed formulation described in mfma_util.h).  Packed tiles go from global
