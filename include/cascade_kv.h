@@ -39,7 +39,8 @@ enum {
     CASCADE_E_WORKSPACE_TOO_SMALL = -3,
     CASCADE_E_UNSUPPORTED = -4,
     CASCADE_E_HIP = -5,
-    CASCADE_E_BAD_ARG = -6
+    CASCADE_E_BAD_ARG = -6,
+    CASCADE_E_INTERNAL = -7   /* a consistency check inside the library failed (a bug, not a misuse) */
 };
 
 enum { CASCADE_F32 = 0, CASCADE_BF16 = 1 };

@@ -22,6 +22,7 @@ CASCADE_E_WORKSPACE_TOO_SMALL = -3
 CASCADE_E_UNSUPPORTED = -4
 CASCADE_E_HIP = -5
 CASCADE_E_BAD_ARG = -6
+CASCADE_E_INTERNAL = -7
 CASCADE_F32 = 0
 CASCADE_BF16 = 1
 CASCADE_REDUCE_MAX = 0

@@ -26,6 +26,14 @@ struct cascade_ctx {
     int max_chunk;
     int tail_k;          // rows of a chunk (counted from its end) that enter the score sums
     bool mfma;
+    // bf16 path: Kt / Vt / Knorm2 belong to this context alone (not shared between layers), and, if
+    // packed_valid, hold every cache tile where `packed` puts it, except those named by `stale`.
+    // packed_reuse: tiles that are still valid are not packed again.
+    bool packed_own = true;
+    bool packed_reuse = true;
+    bool packed_valid = false;
+    PackedLayout packed;
+    TileRuns stale;
     bool profiling = false;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> prof[CASCADE_K_FAMILIES];
     std::string err;
@@ -260,6 +268,7 @@ static int init_context(const char* who, const cascade_config* cfg, const Geom& 
     carve(cfg, g, state_base, shared_base, &ctx->buf);
     ctx->mfma = cfg->dtype == CASCADE_BF16;
     if (const char* e = getenv("CASCADE_KV_SCALAR_ATTENTION")) if (e[0] == '1') ctx->mfma = false;
+    if (const char* e = getenv("CASCADE_KV_PACK_REUSE")) ctx->packed_reuse = e[0] != '0';   // 0: pack every tile for every chunk (A/B timing, tests)
 
     // rows of a chunk whose EMA weight beta^k has not dropped below the cut
     {
@@ -355,6 +364,7 @@ extern "C" int cascade_init_layers(const cascade_config* cfg, int32_t n_layers, 
             for (int j = 0; j < i; ++j) { cascade_destroy(out_ctxs[j]); out_ctxs[j] = nullptr; }
             return rc;
         }
+        out_ctxs[i]->packed_own = n_layers == 1;   // layers pack into one shared copy, which the next layer overwrites
     }
     return CASCADE_OK;
 }
@@ -430,6 +440,8 @@ extern "C" int cascade_prefill_chunk(cascade_ctx* ctx, const void* dev_q, const 
 
     SegList sl;
     build_segments(g, ctx->st, true, Q, sl);
+    bool packed_stable = false;   // the packed tiles of this call stay where they are for the next one
+    PackedLayout lay;
     // the MFMA kernels take logits directly as base-2 exponents
     const float qscale = ctx->mfma ? g.scale * 1.4426950408889634f : 1.f;
     const int tail = Q < ctx->tail_k ? Q : ctx->tail_k;    // rows that carry weight in the score sums
@@ -437,8 +449,27 @@ extern "C" int cascade_prefill_chunk(cascade_ctx* ctx, const void* dev_q, const 
         Timed t(ctx, CASCADE_K_PREP, s);
         // bf16: the attention kernel rotates its queries itself; only the score kernel reads rotated copies
         launch_prep(g, ctx->dtype, ctx->buf, sl, Q, qscale, ctx->mfma ? Q - tail : 0, dev_q, dev_k, dev_v, s);
-        if (ctx->mfma && !launch_kv_pack(g, ctx->buf, sl, Q, s))
-            return fail(ctx, CASCADE_E_WORKSPACE_TOO_SMALL, "cascade_prefill_chunk: packed K/V buffers too small for this segment list");
+        if (ctx->mfma) {
+            // The tiles of a full cache keep their place while the ring heads keep their offsets
+            // inside a tile: then only the tiles the last update wrote, and the chunk's own, are
+            // packed again.
+            packed_layout(g, ctx->st, lay);
+            const int chunk_tiles = (Q + 63) / 64;
+            if (lay.full && packed_tiles_of(sl) != lay.cache_tiles + chunk_tiles)
+                return fail(ctx, CASCADE_E_INTERNAL, "cascade_prefill_chunk: the segment list does not have the tiles of the packed layout");
+            TileRuns runs;
+            runs.n = 0; runs.total = 0;
+            if (ctx->packed_reuse && ctx->packed_own && lay.full && ctx->packed_valid && same_offsets(g, lay, ctx->packed)) {
+                runs = ctx->stale;
+                add_tile_run(runs, lay.cache_tiles, chunk_tiles);
+            } else {
+                add_tile_run(runs, 0, packed_tiles_of(sl));
+            }
+            ctx->packed_valid = false;   // until this call has gone through
+            if (!launch_kv_pack(g, ctx->buf, sl, runs, Q, s))
+                return fail(ctx, CASCADE_E_WORKSPACE_TOO_SMALL, "cascade_prefill_chunk: packed K/V buffers too small for this segment list");
+            packed_stable = ctx->packed_own && lay.full;
+        }
     }
     {
         Timed t(ctx, CASCADE_K_ATTENTION, s);
@@ -460,7 +491,14 @@ extern "C" int cascade_prefill_chunk(cascade_ctx* ctx, const void* dev_q, const 
         launch_plan(g, ctx->buf, pl, ctx->max_chunk, s);
         launch_moves(g, ctx->dtype, ctx->buf, pl, ctx->max_chunk, dev_k, dev_v, g.Hkv * g.d, Q * g.Hkv * g.d, s);
     }
-    return hip_check(ctx, hipGetLastError(), "cascade_prefill_chunk");
+    const int rc_launch = hip_check(ctx, hipGetLastError(), "cascade_prefill_chunk");
+    if (rc_launch == CASCADE_OK && packed_stable) {
+        ctx->packed = lay;
+        ctx->stale.n = 0; ctx->stale.total = 0;
+        add_touched_tiles(g, lay, pl, ctx->stale);
+        ctx->packed_valid = true;
+    }
+    return rc_launch;
 }
 
 // ------------------------------------------------------------------ decode step
@@ -477,6 +515,7 @@ extern "C" int cascade_decode_step(cascade_ctx* ctx, const void* dev_q, const vo
 
     SegList sl;
     build_segments(g, ctx->st, false, 1, sl);
+    ctx->packed_valid = false;   // the step writes cache rows the packed copies of the prefill path do not follow
     {
         Timed t0(ctx, CASCADE_K_DECODE_QK, s);
         launch_decode_qk(g, ctx->dtype, ctx->buf, sl, dev_q, dev_k, s);
@@ -624,6 +663,8 @@ extern "C" int cascade_simulate_structure(const cascade_config* cfg, const int32
         if (!host_scores) continue;
         const float* muc = host_scores + consumed;
         consumed += Q;
+        int run_lo[kMaxTileRuns], run_hi[kMaxTileRuns];
+        const int n_runs = touched_slot_runs(g, pl, run_lo, run_hi);   // every write below must fall inside these
         std::vector<int32_t> off_a(Q + 1), off_b(Q + 1);
         std::vector<std::vector<int32_t>> W(g.N, std::vector<int32_t>(Q + 2, -1));
         int32_t *off_in = off_a.data(), *off_out = off_b.data();
@@ -648,6 +689,9 @@ extern "C" int cascade_simulate_structure(const cascade_config* cfg, const int32
                 int dst, ref;
                 if (c < 0) { dst = pl.sink_fill0 + e; ref = g.slots + e; }
                 else if (!final_entry(pl.c[c], e, E, W[c].data(), &dst, &ref)) continue;
+                bool predicted = false;
+                for (int r = 0; r < n_runs; ++r) predicted = predicted || (dst >= run_lo[r] && dst < run_hi[r]);
+                if (!predicted) return fail(nullptr, CASCADE_E_INTERNAL, "cascade_simulate_structure: a slot was written outside the predicted runs");
                 if (ref < g.slots) { mu[dst] = mu[ref]; ids[dst] = ids[ref]; }
                 else { mu[dst] = muc[ref - g.slots]; ids[dst] = pl.id0 + (ref - g.slots); }
             }

@@ -2,7 +2,8 @@
 //
 // kv_pack_kernel, once per chunk: the keys and values the chunk attends to (cache segments, then
 // the chunk itself) are copied tile after tile (64 keys) in the order the attention kernel
-// visits them.  A packed tile is the exact LDS image the attention kernel wants: K with the
+// visits them; when the caller knows that a tile still holds what it held for the previous
+// chunk, it leaves that tile out of the launch.  A packed tile is the exact LDS image the attention kernel wants: K with the
 // 16-byte chunks of a row XOR-swizzled, V transposed (a row is one column of V with its 64 keys),
 // so that the A operand of O^T = V^T P^T is a plain 16-byte LDS read.  The attention kernel then
 // needs no segment logic for its loads.  The kernel also leaves the largest squared key norm of
@@ -49,7 +50,7 @@ constexpr int kPackThreads = 256;
 // Tile n of the packed K and V copies of one (batch, KV head): 64 rows of a segment (rows past
 // its end become zeros); K with its chunks swizzled, V transposed through LDS.
 template <int D>
-__global__ __launch_bounds__(kPackThreads) void kv_pack_kernel(Geom g, SegList sl, int Q, int tiles_per_bh,
+__global__ __launch_bounds__(kPackThreads) void kv_pack_kernel(Geom g, SegList sl, TileRuns runs, int Q, int tiles_per_bh,
                                                                const bf16_t* __restrict__ Kr, const bf16_t* __restrict__ Krc,
                                                                const bf16_t* __restrict__ Vc, const bf16_t* __restrict__ Vch,
                                                                bf16_t* __restrict__ Kt, bf16_t* __restrict__ Vt,
@@ -59,14 +60,17 @@ __global__ __launch_bounds__(kPackThreads) void kv_pack_kernel(Geom g, SegList s
     __shared__ __attribute__((aligned(16))) bf16_t T[kBN * STR];
     __shared__ float wave_max[kPackThreads / 64];
     const int BH = g.B * g.Hkv;
-    const int bh = blockIdx.x % BH, n = blockIdx.x / BH;
+    const int bh = blockIdx.x % BH, kth = blockIdx.x / BH;   // the kth tile of the runs
+    int run = 0;
+    while (run + 1 < runs.n && kth >= runs.ahead[run + 1]) ++run;
+    const int n = runs.first[run] + (kth - runs.ahead[run]);
     int si = 0, first = 0;
     for (; si < sl.n; ++si) {
         const int nt = (sl.s[si].len + kBN - 1) / kBN;
         if (n < first + nt) break;
         first += nt;
     }
-    if (si >= sl.n) return;   // cannot happen: the grid has one workgroup per tile
+    if (si >= sl.n) return;   // cannot happen: the runs name tiles of the segment list
     const Seg sg = sl.s[si];
     const int t0 = (n - first) * kBN, rows = min(kBN, sg.len - t0);
     const size_t row0 = sg.chunk ? ((size_t)bh * Q + t0) : ((size_t)bh * g.slots + sg.start + t0);
@@ -380,7 +384,7 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     for (int n = 0; n < 3; ++n)
         if (n < NT) copy_tile(vt_bh, lds_v, n, n);
     load_q(it1.sg);
-    int q_seg = it1.si;
+    int q_var = it1.sg.qvar;   // the rotation the query fragments hold (two segments may share one)
     // the largest squared key norm among the tiles of this workgroup
     float kn2 = 0.f;
     {
@@ -424,9 +428,9 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     while (true) {
         const bool has_next = n0 + 1 < NT;
         const bool act_next = has_next && wave_active(it1);
-        if (act_next && q_seg != it1.si) {
+        if (act_next && q_var != it1.sg.qvar) {
             load_q(it1.sg);
-            q_seg = it1.si;
+            q_var = it1.sg.qvar;
             wait_vm<0>();   // here, so that no wait for these loads is placed among the MFMAs (it would also wait for the copies)
         }
         // ---- matrix block.  A wave that does not see tile t holds zero probabilities; S^T of a
@@ -516,16 +520,20 @@ static int packed_tiles(const SegList& sl)
     return n;
 }
 
-bool launch_kv_pack(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, hipStream_t s)
+int packed_tiles_of(const SegList& sl) { return packed_tiles(sl); }
+
+// Tile n of a (batch, KV head) sits at tile index bh * b.vt_tiles + n of Kt, Vt and Knorm2: the
+// stride is the capacity, so that tiles keep their place from one chunk to the next.
+bool launch_kv_pack(const Geom& g, const DevBuffers& b, const SegList& sl, const TileRuns& runs, int Q, hipStream_t s)
 {
-    const int tiles_per_bh = packed_tiles(sl);
-    if (tiles_per_bh > b.vt_tiles) return false;   // the workspace was sized for every possible segment list
-    const dim3 grid(tiles_per_bh * g.B * g.Hkv), block(kPackThreads);
+    if (packed_tiles(sl) > b.vt_tiles) return false;   // the workspace was sized for every possible segment list
+    if (runs.total == 0) return true;
+    const dim3 grid(runs.total * g.B * g.Hkv), block(kPackThreads);
     if (g.d == 128)
-        hipLaunchKernelGGL(kv_pack_kernel<128>, grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)b.Kr, (const bf16_t*)b.Krc,
+        hipLaunchKernelGGL(kv_pack_kernel<128>, grid, block, 0, s, g, sl, runs, Q, b.vt_tiles, (const bf16_t*)b.Kr, (const bf16_t*)b.Krc,
                            (const bf16_t*)b.Vc, (const bf16_t*)b.Vch, (bf16_t*)b.Kt, (bf16_t*)b.Vt, b.knorm2);
     else
-        hipLaunchKernelGGL(kv_pack_kernel<64>, grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)b.Kr, (const bf16_t*)b.Krc,
+        hipLaunchKernelGGL(kv_pack_kernel<64>, grid, block, 0, s, g, sl, runs, Q, b.vt_tiles, (const bf16_t*)b.Kr, (const bf16_t*)b.Krc,
                            (const bf16_t*)b.Vc, (const bf16_t*)b.Vch, (bf16_t*)b.Kt, (bf16_t*)b.Vt, b.knorm2);
     return true;
 }
@@ -576,7 +584,7 @@ int attn_splits(const Geom& g, int Q)
 void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, const void* q, float qscale,
                         void* out, hipStream_t s)
 {
-    const int tiles_per_bh = packed_tiles(sl);
+    const int tiles_per_bh = b.vt_tiles;   // stride between the packed streams of two (batch, KV head)
     constexpr int BM = kSWaves * 32;
     const int tiles = (g.G * Q + BM - 1) / BM;
     const int n_split = attn_splits(g, Q);

@@ -785,7 +785,7 @@ template <> struct QkSwizzle<128> { __device__ static int of(int row) { return r
 template <> struct QkSwizzle<64> { __device__ static int of(int row) { return (row >> 1) & 7; } };
 
 template <int MAXG> struct QkLimits {
-    static constexpr int kRotations = 96 / MAXG < kMaxSegments ? 96 / MAXG : kMaxSegments;   // query copies held in LDS
+    static constexpr int kRotations = 96 / MAXG < kMaxQueryRotations ? 96 / MAXG : kMaxQueryRotations;   // query copies held in LDS
 };
 
 template <int D, int MAXG>
@@ -1018,7 +1018,7 @@ void launch_decode_qk(const Geom& g, int dtype, const DevBuffers& b, const SegLi
         const int ps = per_split_of(b, sl.n_cached);
         static const bool direct_only = getenv("CASCADE_KV_DECODE_QK_DIRECT") != nullptr;
         const int mg = maxg_of(g);
-        const int rotations = 96 / mg < kMaxSegments ? 96 / mg : kMaxSegments;
+        const int rotations = 96 / mg < kMaxQueryRotations ? 96 / mg : kMaxQueryRotations;
         // the streaming kernel keeps every rotation of the queries in LDS
         const bool stream = !direct_only && sl.n_qvar <= rotations;
 #define CKV_QK_MFMA(D, MG)                                                                                        \

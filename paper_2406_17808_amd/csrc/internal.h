@@ -9,7 +9,8 @@
 namespace ckv {
 
 constexpr int kMaxCascades = CASCADE_MAX_CASCADES;
-constexpr int kMaxSegments = 2 * CASCADE_MAX_CASCADES + 2;
+constexpr int kMaxQueryRotations = 2 * CASCADE_MAX_CASCADES + 2;   // sinks, two runs per ring, the chunk
+constexpr int kMaxSegments = 3 * CASCADE_MAX_CASCADES + 2;         // a run may be listed in two pieces
 
 // ------------------------------------------------------------------ element types
 typedef uint16_t bf16_t;   // raw bfloat16 bits
@@ -66,7 +67,7 @@ struct SegList {
     int n;                 // segments
     int n_qvar;            // rotated query copies
     int n_cached;          // cached rows before the chunk = positional index of chunk token 0
-    int qrot0[kMaxSegments];   // rotation index of chunk row 0 for query copy v (row i uses qrot0 + i)
+    int qrot0[kMaxQueryRotations];   // rotation index of chunk row 0 for query copy v (row i uses qrot0 + i)
     Seg s[kMaxSegments];
 };
 
@@ -93,6 +94,15 @@ struct UpdatePlan {
     int N;
     int id0;         // original index of chunk token 0
     CascStep c[kMaxCascades];
+};
+
+// A few runs of 64-row tiles (of the packed K / V copies the bf16 attention kernel reads).
+constexpr int kMaxTileRuns = 2 * CASCADE_MAX_CASCADES + 2;   // sinks, two per ring, the chunk
+struct TileRuns {
+    int n;                       // runs
+    int total;                   // tiles in all runs
+    int first[kMaxTileRuns];     // first tile of run i
+    int ahead[kMaxTileRuns];     // tiles in the runs before run i
 };
 
 // scratch index space of the update: refs < slots name a physical slot, refs >= slots a chunk token

@@ -68,9 +68,11 @@ void launch_score_simple(const Geom& g, int dtype, const DevBuffers& b, const Se
                          int max_chunk, int tail_rows, float decay, hipStream_t s);
 
 // attention, bf16 MFMA (head_dim 64 or 128).  launch_kv_pack copies the keys and values of the
-// segment list into Kt / Vt, tile by tile (false if they do not hold that many tiles);
+// segment list into Kt / Vt, tile by tile (tile n = rows 64n .. 64n+63 of the concatenated
+// segments), for the tiles named by `runs` only (false if Kt / Vt do not hold that many tiles);
 // launch_attn_stream reads only those copies, and the caller's queries (q: [B,Q,Hq,d], rotated on the fly).
-bool launch_kv_pack(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, hipStream_t s);
+int packed_tiles_of(const SegList& sl);
+bool launch_kv_pack(const Geom& g, const DevBuffers& b, const SegList& sl, const TileRuns& runs, int Q, hipStream_t s);
 void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, const void* q, float qscale,
                         void* out, hipStream_t s);
 void launch_score_mfma(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, int max_chunk,

@@ -71,7 +71,11 @@ void plan_update(const Geom& g, HostState& st, int Q, UpdatePlan& plan)
 // Cache order is sinks, last cascade oldest..newest, ..., first cascade (Section 3.1
 // "Positional Encoding": the index inside the cache).  Stored keys are rotated to their
 // physical slot index, so within a run where (cache index - slot index) is constant the
-// queries need one rotation: by (own index) - (that constant).
+// queries need one rotation: by (own index) - (that constant).  The segments are listed in
+// physical order (the wrapped part of a ring before its oldest part): attention does not care
+// in which order it meets the keys, and a full cache then always reads front to back.  The
+// wrapped part of a full ring is listed as [0, o) and [o, xi), o = xi mod 64, which fixes the
+// place of every 64-row tile of the ring (see PackedLayout).
 void build_segments(const Geom& g, const HostState& st, bool with_chunk, int Q, SegList& out)
 {
     out.n = 0;
@@ -94,12 +98,88 @@ void build_segments(const Geom& g, const HostState& st, bool with_chunk, int Q, 
         if (cnt < cap) {
             add(base, cnt, rank - base, 0);
         } else {
+            const int o = xi % 64, wrapped = rank + (cap - xi) - base;
+            add(base, o, wrapped, 0);                                 // wrapped part: ring [0, xi), in two pieces
+            add(base + o, xi - o, wrapped, 0);
             add(base + xi, cap - xi, rank - (base + xi), 0);          // oldest part: ring [xi, cap)
-            add(base, xi, rank + (cap - xi) - base, 0);               // wrapped part: ring [0, xi)
         }
         rank += cnt;
     }
     if (with_chunk) add(0, Q, n, 1);                 // chunk key i is rotated to i and sits at n + i
+}
+
+void packed_layout(const Geom& g, const HostState& st, PackedLayout& out)
+{
+    out.full = st.sink_fill == g.n_sink;
+    int tiles = (g.n_sink + 63) / 64;
+    for (int c = g.N - 1; c >= 0; --c) {             // physical order: the last cascade first
+        if (st.count[c] != g.cap[c]) out.full = false;
+        const int o = st.xi[c] % 64;
+        out.off[c] = o;
+        out.tile0[c] = tiles;
+        tiles += (o > 0 ? 1 : 0) + (g.cap[c] - o + 63) / 64;
+    }
+    out.cache_tiles = tiles;
+}
+
+bool same_offsets(const Geom& g, const PackedLayout& a, const PackedLayout& b)
+{
+    for (int c = 0; c < g.N; ++c) if (a.off[c] != b.off[c]) return false;
+    return true;
+}
+
+static int tile_of_slot(const Geom& g, const PackedLayout& lay, int slot)
+{
+    if (slot < g.n_sink) return slot / 64;
+    for (int c = 0; c < g.N; ++c) {
+        const int r = slot - g.base[c];
+        if (r < 0 || r >= g.cap[c]) continue;
+        const int o = lay.off[c];
+        return lay.tile0[c] + (r < o ? 0 : (o > 0 ? 1 : 0) + (r - o) / 64);
+    }
+    return -1;
+}
+
+int touched_slot_runs(const Geom& g, const UpdatePlan& pl, int* lo, int* hi)
+{
+    int n = 0;
+    if (pl.n_to_sink > 0) { lo[n] = pl.sink_fill0; hi[n] = pl.sink_fill0 + pl.n_to_sink; ++n; }
+    for (int c = 0; c < pl.N; ++c) {
+        const CascStep& cs = pl.c[c];
+        if (cs.M == 0) break;
+        // ring positions wpos0 .. wpos0 + J - 1 are opened; before the first push the offers
+        // compete with the item at newest0 = wpos0 - 1
+        const int len = cs.J + cs.pre;
+        if (len == 0) continue;
+        if (len >= cs.cap) { lo[n] = cs.base; hi[n] = cs.base + cs.cap; ++n; continue; }
+        const int start = cs.pre ? cs.newest0 : cs.wpos0;
+        const int end = start + len;
+        if (end <= cs.cap) { lo[n] = cs.base + start; hi[n] = cs.base + end; ++n; }
+        else {
+            lo[n] = cs.base + start; hi[n] = cs.base + cs.cap; ++n;
+            lo[n] = cs.base; hi[n] = cs.base + end - cs.cap; ++n;
+        }
+    }
+    return n;
+}
+
+void add_tile_run(TileRuns& runs, int first, int count)
+{
+    if (count <= 0) return;
+    runs.first[runs.n] = first;
+    runs.ahead[runs.n] = runs.total;
+    runs.total += count;
+    ++runs.n;
+}
+
+void add_touched_tiles(const Geom& g, const PackedLayout& layout, const UpdatePlan& pl, TileRuns& runs)
+{
+    int lo[kMaxTileRuns], hi[kMaxTileRuns];
+    const int n = touched_slot_runs(g, pl, lo, hi);
+    for (int i = 0; i < n; ++i) {                    // a run lies inside one ring: its tiles are consecutive
+        const int t0 = tile_of_slot(g, layout, lo[i]), t1 = tile_of_slot(g, layout, hi[i] - 1);
+        add_tile_run(runs, t0, t1 - t0 + 1);
+    }
 }
 
 int slot_of_rank(const Geom& g, const HostState& st, int r)

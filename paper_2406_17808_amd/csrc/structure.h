@@ -37,6 +37,28 @@ void plan_update(const Geom& g, HostState& st, int Q, UpdatePlan& plan);
 // with_chunk: append the segment of the chunk's own keys.
 void build_segments(const Geom& g, const HostState& st, bool with_chunk, int Q, SegList& out);
 
+// Where the 64-row tiles of the packed K / V copies sit when every ring is full.  build_segments
+// lists a full ring as [0, o), [o, xi), [xi, cap) with o = xi mod 64, so ring rows o + 64k ..
+// o + 64k + 63 always form tile (o > 0) + k of the ring whatever xi is: as long as no o changes,
+// a tile keeps its place and its content from chunk to chunk until one of its rows is written.
+struct PackedLayout {
+    bool full;                    // sinks and every ring are full
+    int off[kMaxCascades];        // o of every ring
+    int tile0[kMaxCascades];      // first tile of every ring
+    int cache_tiles;              // tiles of all cached rows; the chunk's tiles follow
+};
+void packed_layout(const Geom& g, const HostState& st, PackedLayout& out);
+bool same_offsets(const Geom& g, const PackedLayout& a, const PackedLayout& b);
+
+// The physical slots an update may write (ring positions opened, and the resident item the
+// first offers compete with), as runs [lo, hi) of slots inside one ring or the sinks; returns the
+// number of runs (<= 2 per cascade + 1 for the sinks).
+int touched_slot_runs(const Geom& g, const UpdatePlan& pl, int* lo, int* hi);
+
+// The same as runs of tiles of `layout`, appended to `runs`.
+void add_touched_tiles(const Geom& g, const PackedLayout& layout, const UpdatePlan& pl, TileRuns& runs);
+void add_tile_run(TileRuns& runs, int first, int count);
+
 // physical slot of the r-th entry in cache order (r < n_cached)
 int slot_of_rank(const Geom& g, const HostState& st, int r);
 

@@ -96,6 +96,14 @@ def test_tiny_f32_free_running(oracle_mod):
          sizes=[96, 96, 96], chunks=[256] * 5, max_chunk=256, logit_step="after_sinks", rope_base=1e6, attn_splits=1),
     dict(name="bf16_logit_step_chunk_tail_unsplit", dtype=B.CASCADE_BF16, d=128, Hq=4, Hkv=2, batch=1, n_sink=4,
          sizes=[96, 96, 96], chunks=[256] * 5, max_chunk=256, logit_step="chunk_tail", rope_base=1e6, attn_splits=1, compare_membership=False),
+    # rings of whole tiles, all full after a few chunks: the packed K/V tiles then keep their place
+    # from chunk to chunk and only the ones the last update wrote are packed again, as long as every
+    # ring head keeps its offset inside a tile.  Chunks of 128 and 100 change the offset of the
+    # third ring's head, and of all heads (everything is packed once, then tiles are kept again).
+    dict(name="bf16_tile_aligned_rings", dtype=B.CASCADE_BF16, d=128, Hq=4, Hkv=2, batch=1, n_sink=64,
+         sizes=[128, 128, 128], chunks=[256] * 6 + [128] + [256] * 2 + [128] + [256] * 4 + [100] + [256] * 2, max_chunk=256, pack_reuse=1),
+    dict(name="bf16_tile_aligned_rings_d64_unsplit", dtype=B.CASCADE_BF16, d=64, Hq=8, Hkv=2, batch=2, n_sink=64,
+         sizes=[256, 128], chunks=[256] * 4 + [64] * 3 + [192] + [256] * 3, max_chunk=256, attn_splits=1, pack_reuse=1),
     dict(name="bf16_logit_step_chunk_tail_d64", dtype=B.CASCADE_BF16, d=64, Hq=4, Hkv=2, batch=1, n_sink=4,
          sizes=[96, 96, 96], chunks=[256] * 5, max_chunk=256, logit_step="chunk_tail", rope_base=1e6, compare_membership=False),
 ], ids=lambda c: c["name"])
@@ -103,6 +111,8 @@ def test_prefill_one_step_ahead(oracle_mod, case, monkeypatch):
     from gpu_harness import ParityRun
     if "attn_splits" in case:
         monkeypatch.setenv("CASCADE_KV_ATTN_SPLITS", str(case["attn_splits"]))
+    if "pack_reuse" in case:   # 0: every tile is packed for every chunk
+        monkeypatch.setenv("CASCADE_KV_PACK_REUSE", str(case["pack_reuse"]))
     cfg = B.make_config(batch=case["batch"], n_q_heads=case["Hq"], n_kv_heads=case["Hkv"], head_dim=case["d"],
                         dtype=case["dtype"], n_sink=case["n_sink"], cascade_sizes=case["sizes"],
                         ema_beta=case.get("beta", 0.9), rope_base=case.get("rope_base", 10000.0), max_chunk=case["max_chunk"],
@@ -140,6 +150,28 @@ def test_prefill_one_step_ahead(oracle_mod, case, monkeypatch):
     run.close()
 
 
+def test_decode_steps_between_tile_aligned_chunks(oracle_mod, monkeypatch):
+    """Decode steps write cache rows without touching the packed K/V tiles of the prefill path, so
+    the chunk after them must not reuse any tile (rings of whole tiles, as above)."""
+    from gpu_harness import ParityRun
+    monkeypatch.setenv("CASCADE_KV_PACK_REUSE", "1")
+    cfg = B.make_config(batch=1, n_q_heads=4, n_kv_heads=2, head_dim=128, dtype=B.CASCADE_BF16, n_sink=64,
+                        cascade_sizes=[128, 128], ema_beta=0.9, rope_base=10000.0, max_chunk=256, keep_update_scores=1)
+    tol_out, tol_score = _tolerances(cfg)
+    rng = np.random.default_rng(21)
+    run = ParityRun(cfg, one_step_ahead=True)
+    plan = [("p", 256)] * 4 + [("d", 1)] * 64 + [("p", 256)] * 3 + [("d", 1)] * 7 + [("p", 256)] * 2
+    worst_out = worst_score = 0.0
+    for i, (kind, n) in enumerate(plan):
+        q, k, v = _inputs(rng, cfg, n)
+        rep = run.step(q, k, v, decode=(kind == "d"))
+        assert rep.replay_exact, i
+        worst_out, worst_score = max(worst_out, rep.out_err), max(worst_score, rep.score_err)
+    print(f"decode between aligned chunks: out {worst_out:.3e} score {worst_score:.3e}")
+    assert worst_out <= tol_out and worst_score <= tol_score
+    run.close()
+
+
 @pytest.mark.parametrize("dtype,d,hq,hkv", [(B.CASCADE_F32, 64, 8, 2), (B.CASCADE_BF16, 128, 8, 2),
                                             (B.CASCADE_BF16, 64, 8, 1), (B.CASCADE_BF16, 64, 2, 2),
                                             (B.CASCADE_BF16, 128, 4, 2), (B.CASCADE_BF16, 128, 3, 1)])
@@ -166,11 +198,13 @@ def test_prefill_then_decode(oracle_mod, dtype, d, hq, hkv):
 
 
 @pytest.mark.parametrize("seed", list(range(12)))
-def test_random_geometries(oracle_mod, seed):
+def test_random_geometries(oracle_mod, seed, monkeypatch):
     """Seeded random geometries (heads, head_dim, sinks, cascade count and sizes, periods, chunk
     mix, decay) through prefill and decode, one step ahead of the oracle: sizes that are not
-    multiples of any tile, partly filled cascades, chunks from 1 token to several tiles."""
+    multiples of any tile, partly filled cascades, chunks from 1 token to several tiles.  Even
+    seeds pack every K/V tile for every chunk, odd seeds keep the tiles no update has written."""
     from gpu_harness import ParityRun
+    monkeypatch.setenv("CASCADE_KV_PACK_REUSE", str(seed % 2))
     rng = np.random.default_rng(1000 + seed)
     d = int(rng.choice([64, 128]))
     hkv = int(rng.choice([1, 2, 3]))

@@ -203,3 +203,21 @@ def test_chunked_update_equals_token_by_token_alg2(lib, oracle_mod, seed):
         assert sim.ids[:sim.count].tolist() == st.ids.tolist(), (seed, upto)
         np.testing.assert_array_equal(sim.mu[:sim.count], st.mu.astype(np.float32))
         assert sim.swaps.tolist() == st.stats[:, 1].tolist()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_update_writes_stay_in_predicted_runs(lib, seed):
+    """The prefill path re-packs only the K/V tiles an update may have written, which it predicts
+    from the structure alone (ring positions opened, plus the resident item the first offers compete
+    with).  The host replay checks every write against that prediction and fails with
+    CASCADE_E_INTERNAL otherwise; here on tile-sized rings, chunks that wrap them, and many ties."""
+    rng = np.random.default_rng(900 + seed)
+    N = int(rng.integers(1, 5))
+    sizes = [int(x) * 64 for x in rng.integers(1, 4, size=N)]
+    n_sink = int(rng.choice([0, 3, 64]))
+    periods = None if seed % 2 == 0 else [1] + [int(x) for x in rng.integers(1, 5, size=N - 1)]
+    chunks = [int(x) for x in rng.choice([1, 5, 63, 64, 65, 128, 200, 256], size=30)]
+    scores = (rng.integers(0, 5, size=sum(chunks)) / 4.0).astype(np.float32)
+    cfg = _cfg(n_sink=n_sink, cascade_sizes=sizes, accept_period=periods, max_chunk=256, token_selection=1 - seed % 4 // 3)
+    sim = B.cascade_simulate_structure(cfg, chunks, scores)   # raises on any error code
+    assert sim.count == min(sum(chunks), n_sink + sum(sizes)) or sim.count <= n_sink + sum(sizes)
