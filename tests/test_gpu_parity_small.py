@@ -150,6 +150,31 @@ def test_prefill_one_step_ahead(oracle_mod, case, monkeypatch):
     run.close()
 
 
+def test_sixteen_cascades(oracle_mod):
+    """The largest number of sub-caches the configuration allows: once all rings are full the
+    segment list holds three pieces per ring (50 segments, 34 query rotations); a decode step then
+    has more rotations than its streaming kernel keeps in LDS and takes the register-load kernel."""
+    from gpu_harness import ParityRun
+    cfg = B.make_config(batch=1, n_q_heads=4, n_kv_heads=2, head_dim=64, dtype=B.CASCADE_BF16, n_sink=2,
+                        cascade_sizes=[70] + [9] * 15, ema_beta=0.9, rope_base=10000.0, max_chunk=96,
+                        accept_period=[1] * 16, keep_update_scores=1)
+    tol_out, tol_score = _tolerances(cfg)
+    rng = np.random.default_rng(16)
+    run = ParityRun(cfg, one_step_ahead=True)
+    plan = [("p", 96)] * 5 + [("p", 37)] + [("d", 1)] * 5 + [("p", 96)] * 2
+    worst_out = worst_score = 0.0
+    for i, (kind, n) in enumerate(plan):
+        q, k, v = _inputs(rng, cfg, n)
+        rep = run.step(q, k, v, decode=(kind == "d"))
+        assert rep.replay_exact, i
+        worst_out, worst_score = max(worst_out, rep.out_err), max(worst_score, rep.score_err)
+    st = run.gpu.read_state()
+    assert st.counts.tolist() == [2, 70] + [9] * 15      # every ring is full
+    print(f"sixteen cascades: out {worst_out:.3e} score {worst_score:.3e}")
+    assert worst_out <= tol_out and worst_score <= tol_score
+    run.close()
+
+
 def test_decode_steps_between_tile_aligned_chunks(oracle_mod, monkeypatch):
     """Decode steps write cache rows without touching the packed K/V tiles of the prefill path, so
     the chunk after them must not reuse any tile (rings of whole tiles, as above)."""
