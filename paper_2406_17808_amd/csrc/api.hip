@@ -459,10 +459,13 @@ extern "C" int cascade_prefill_chunk(cascade_ctx* ctx, const void* dev_q, const 
                 return fail(ctx, CASCADE_E_INTERNAL, "cascade_prefill_chunk: the segment list does not have the tiles of the packed layout");
             TileRuns runs;
             runs.n = 0; runs.total = 0;
-            if (ctx->packed_reuse && ctx->packed_own && lay.full && ctx->packed_valid && same_offsets(g, lay, ctx->packed)) {
+            bool partial = ctx->packed_reuse && ctx->packed_own && lay.full && ctx->packed_valid && same_offsets(g, lay, ctx->packed);
+            if (partial) {
                 runs = ctx->stale;
-                add_tile_run(runs, lay.cache_tiles, chunk_tiles);
-            } else {
+                partial = add_tile_run(runs, lay.cache_tiles, chunk_tiles);
+            }
+            if (!partial) {
+                runs.n = 0; runs.total = 0;
                 add_tile_run(runs, 0, packed_tiles_of(sl));
             }
             ctx->packed_valid = false;   // until this call has gone through
@@ -495,8 +498,7 @@ extern "C" int cascade_prefill_chunk(cascade_ctx* ctx, const void* dev_q, const 
     if (rc_launch == CASCADE_OK && packed_stable) {
         ctx->packed = lay;
         ctx->stale.n = 0; ctx->stale.total = 0;
-        add_touched_tiles(g, lay, pl, ctx->stale);
-        ctx->packed_valid = true;
+        ctx->packed_valid = add_touched_tiles(g, lay, pl, ctx->stale);
     }
     return rc_launch;
 }

@@ -163,23 +163,26 @@ int touched_slot_runs(const Geom& g, const UpdatePlan& pl, int* lo, int* hi)
     return n;
 }
 
-void add_tile_run(TileRuns& runs, int first, int count)
+bool add_tile_run(TileRuns& runs, int first, int count)
 {
-    if (count <= 0) return;
+    if (count <= 0) return true;
+    if (runs.n == kMaxTileRuns) return false;
     runs.first[runs.n] = first;
     runs.ahead[runs.n] = runs.total;
     runs.total += count;
     ++runs.n;
+    return true;
 }
 
-void add_touched_tiles(const Geom& g, const PackedLayout& layout, const UpdatePlan& pl, TileRuns& runs)
+bool add_touched_tiles(const Geom& g, const PackedLayout& layout, const UpdatePlan& pl, TileRuns& runs)
 {
     int lo[kMaxTileRuns], hi[kMaxTileRuns];
     const int n = touched_slot_runs(g, pl, lo, hi);
     for (int i = 0; i < n; ++i) {                    // a run lies inside one ring: its tiles are consecutive
         const int t0 = tile_of_slot(g, layout, lo[i]), t1 = tile_of_slot(g, layout, hi[i] - 1);
-        add_tile_run(runs, t0, t1 - t0 + 1);
+        if (t0 < 0 || t1 < t0 || !add_tile_run(runs, t0, t1 - t0 + 1)) return false;
     }
+    return true;
 }
 
 int slot_of_rank(const Geom& g, const HostState& st, int r)

@@ -55,9 +55,9 @@ bool same_offsets(const Geom& g, const PackedLayout& a, const PackedLayout& b);
 // number of runs (<= 2 per cascade + 1 for the sinks).
 int touched_slot_runs(const Geom& g, const UpdatePlan& pl, int* lo, int* hi);
 
-// The same as runs of tiles of `layout`, appended to `runs`.
-void add_touched_tiles(const Geom& g, const PackedLayout& layout, const UpdatePlan& pl, TileRuns& runs);
-void add_tile_run(TileRuns& runs, int first, int count);
+// The same as runs of tiles of `layout`, appended to `runs`; false if `runs` cannot hold them.
+bool add_touched_tiles(const Geom& g, const PackedLayout& layout, const UpdatePlan& pl, TileRuns& runs);
+bool add_tile_run(TileRuns& runs, int first, int count);
 
 // physical slot of the r-th entry in cache order (r < n_cached)
 int slot_of_rank(const Geom& g, const HostState& st, int r);
