@@ -476,7 +476,7 @@ extern "C" int cascade_prefill_chunk(cascade_ctx* ctx, const void* dev_q, const 
     }
     {
         Timed t(ctx, CASCADE_K_ATTENTION, s);
-        if (ctx->mfma) launch_attn_stream(g, ctx->buf, sl, Q, dev_q, qscale, dev_out, s);
+        if (ctx->mfma) launch_attn_stream(g, ctx->buf, sl, Q, dev_q, qscale, tail, ctx->max_chunk, dev_out, s);
         else launch_attn_simple(g, ctx->dtype, ctx->buf, sl, Q, ctx->max_chunk, dev_out, s);
     }
     const float decay = (float)pow((double)g.beta, (double)Q);

@@ -127,6 +127,23 @@ __global__ __launch_bounds__(kPackThreads) void kv_pack_kernel(Geom g, SegList s
     }
 }
 
+// What the score kernel wants to know of a finished query row i with log-sum-exp L (base 2, of the
+// scaled logits): its exponent offset negt = log2(weight of the row) - L, so that a probability
+// times the row's EMA weight is 2^(s + negt) (Section 3.1; the weights are Alg. 3's); -inf for the
+// rows before the last `tail`, which carry no weight, and for kScorePadRows rows of padding behind the chunk.
+struct ScoreOffsets {
+    const float* wrow;   // [max_chunk] weight of the row that has k rows after it
+    float* negt;         // [B,Hq,qpad]
+    int tail, qpad;
+};
+
+__device__ inline void write_score_offset(const ScoreOffsets& so, size_t head, int Q, int i, float lse2)
+{
+    float* row = so.negt + head * so.qpad;
+    row[i] = i >= Q - so.tail ? __log2f(so.wrow[Q - 1 - i]) - lse2 : -INFINITY;
+    for (int j = i + Q; j < Q + kScorePadRows; j += Q) row[j] = -INFINITY;   // the first rows between them cover the padding
+}
+
 // SPLIT: the tiles a row block visits are divided over n_split workgroups (for launches too small
 // to fill the chip otherwise); each writes its unnormalised output, running maximum and row sum
 // to part_o / part_ml, and attn_merge_kernel combines them.
@@ -134,7 +151,8 @@ template <int D, bool DBG, bool SPLIT>
 __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     Geom g, SegList sl, int Q, int tiles_per_bh, const bf16_t* __restrict__ q, const float2* __restrict__ rope, float qscale,
     const bf16_t* __restrict__ Kt, const bf16_t* __restrict__ Vt, bf16_t* __restrict__ out, float* __restrict__ lse,
-    long long* dbg, int n_split, float* __restrict__ part_o, float* __restrict__ part_ml, const float* __restrict__ Knorm2)
+    long long* dbg, int n_split, float* __restrict__ part_o, float* __restrict__ part_ml, const float* __restrict__ Knorm2,
+    ScoreOffsets so)
 {
     constexpr int BM = kSWaves * 32;       // query rows per workgroup
     constexpr int KS = D / 16;             // k-steps of S^T = K Q^T
@@ -508,7 +526,10 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
                 w.y = cvt_pk_bf16(o[db][jq * 4 + 2] * inv, o[db][jq * 4 + 3] * inv);
                 *reinterpret_cast<uint2*>(orow + db * 32 + jq * 8 + half * 4) = w;
             }
-        if (half == 0) lse[((size_t)b * g.Hq + qh) * Q + qi] = m_run * 0.6931471805599453f + logf(lt);
+        if (half == 0) {
+            lse[((size_t)b * g.Hq + qh) * Q + qi] = m_run * 0.6931471805599453f + logf(lt);
+            write_score_offset(so, (size_t)b * g.Hq + qh, Q, qi, m_run + __log2f(lt));
+        }
     }
 }
 
@@ -543,7 +564,7 @@ bool launch_kv_pack(const Geom& g, const DevBuffers& b, const SegList& sl, const
 template <int D>
 __global__ __launch_bounds__(D) void attn_merge_kernel(Geom g, int Q, int n_tiles, int n_split, int BM,
                                                        const float* __restrict__ part_o, const float* __restrict__ part_ml,
-                                                       bf16_t* __restrict__ out, float* __restrict__ lse)
+                                                       bf16_t* __restrict__ out, float* __restrict__ lse, ScoreOffsets so)
 {
     const int BH = g.B * g.Hkv;
     const int bh = blockIdx.y, r = blockIdx.x;            // r = head-in-group * Q + token
@@ -565,7 +586,10 @@ __global__ __launch_bounds__(D) void attn_merge_kernel(Geom g, int Q, int n_tile
         }
     }
     out[(((size_t)b * Q + qi) * g.Hq + qh) * D + e] = f32_to_bf16(acc / L);
-    if (e == 0) lse[((size_t)b * g.Hq + qh) * Q + qi] = M * 0.6931471805599453f + logf(L);
+    if (e == 0) {
+        lse[((size_t)b * g.Hq + qh) * Q + qi] = M * 0.6931471805599453f + logf(L);
+        write_score_offset(so, (size_t)b * g.Hq + qh, Q, qi, M + __log2f(L));
+    }
 }
 
 // Workgroups per (row block, KV head) so that a small launch still fills the chip: none for 256
@@ -582,8 +606,9 @@ int attn_splits(const Geom& g, int Q)
 }
 
 void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, const void* q, float qscale,
-                        void* out, hipStream_t s)
+                        int tail_rows, int max_chunk, void* out, hipStream_t s)
 {
+    const ScoreOffsets so = {b.wrow, b.negt, tail_rows, max_chunk + kScorePadRows};
     const int tiles_per_bh = b.vt_tiles;   // stride between the packed streams of two (batch, KV head)
     constexpr int BM = kSWaves * 32;
     const int tiles = (g.G * Q + BM - 1) / BM;
@@ -594,14 +619,14 @@ void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, i
         float* part_ml = b.attn_part + (size_t)kAttnPartRows * g.d;
         if (g.d == 128) {
             hipLaunchKernelGGL((attn_stream_kernel<128, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
-                               (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, n_split, part_o, part_ml, b.knorm2);
+                               (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, n_split, part_o, part_ml, b.knorm2, so);
             hipLaunchKernelGGL(attn_merge_kernel<128>, dim3(g.G * Q, g.B * g.Hkv), dim3(128), 0, s, g, Q, tiles, n_split, BM,
-                               part_o, part_ml, (bf16_t*)out, b.lse);
+                               part_o, part_ml, (bf16_t*)out, b.lse, so);
         } else {
             hipLaunchKernelGGL((attn_stream_kernel<64, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
-                               (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, n_split, part_o, part_ml, b.knorm2);
+                               (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, n_split, part_o, part_ml, b.knorm2, so);
             hipLaunchKernelGGL(attn_merge_kernel<64>, dim3(g.G * Q, g.B * g.Hkv), dim3(64), 0, s, g, Q, tiles, n_split, BM,
-                               part_o, part_ml, (bf16_t*)out, b.lse);
+                               part_o, part_ml, (bf16_t*)out, b.lse, so);
         }
         return;
     }
@@ -609,7 +634,7 @@ void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, i
     if (dbg_env && g.d == 128) {   // phase timing of one workgroup (development aid)
         long long* dbg = (long long*)b.logits;
         hipLaunchKernelGGL((attn_stream_kernel<128, true, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
-                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, dbg, 1, (float*)nullptr, (float*)nullptr, b.knorm2);
+                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, dbg, 1, (float*)nullptr, (float*)nullptr, b.knorm2, so);
         long long h[16];
         (void)hipStreamSynchronize(s);
         (void)hipMemcpy(h, dbg, sizeof(h), hipMemcpyDeviceToHost);
@@ -621,10 +646,10 @@ void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, i
     }
     if (g.d == 128)
         hipLaunchKernelGGL((attn_stream_kernel<128, false, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
-                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, 1, (float*)nullptr, (float*)nullptr, b.knorm2);
+                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, 1, (float*)nullptr, (float*)nullptr, b.knorm2, so);
     else
         hipLaunchKernelGGL((attn_stream_kernel<64, false, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
-                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, 1, (float*)nullptr, (float*)nullptr, b.knorm2);
+                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, 1, (float*)nullptr, (float*)nullptr, b.knorm2, so);
 }
 
 }  // namespace ckv

@@ -73,8 +73,9 @@ void launch_score_simple(const Geom& g, int dtype, const DevBuffers& b, const Se
 // launch_attn_stream reads only those copies, and the caller's queries (q: [B,Q,Hq,d], rotated on the fly).
 int packed_tiles_of(const SegList& sl);
 bool launch_kv_pack(const Geom& g, const DevBuffers& b, const SegList& sl, const TileRuns& runs, int Q, hipStream_t s);
+// It also leaves the exponent offsets of the last tail_rows rows in b.negt for launch_score_mfma.
 void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, const void* q, float qscale,
-                        void* out, hipStream_t s);
+                        int tail_rows, int max_chunk, void* out, hipStream_t s);
 void launch_score_mfma(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, int max_chunk,
                        int tail_rows, float decay, hipStream_t s);
 

@@ -44,6 +44,7 @@ __device__ inline float max_xor32(float x)
 }
 
 constexpr int kBN = 64;               // keys per tile
+constexpr int kScorePadRows = 64;     // the score kernel reads query rows in stages of this many: offsets exist for that many rows behind the chunk
 constexpr float kRescaleLog2 = 8.f;   // the running maximum is only raised when it grew by 2^8
 constexpr float kBoundLog2 = 90.f;    // exponents proven to stay this close to the running maximum need no tracking (2^90 x 2^17 keys < 2^127)
 

@@ -25,23 +25,12 @@ namespace ckv {
 // stage is used; three workgroups per CU), running on across the heads of the group, so no wave
 // waits for a staging round trip.  The exponent offsets come from a small table
 // negt[head][row] = -t (-inf for rows that do not contribute, and for the padding behind the
-// chunk), which the accumulators start from: a probability is then one v_exp_f32 of an
-// accumulator.
+// chunk), written by the attention kernel when it finishes a row; the accumulators start from
+// it: a probability is then one v_exp_f32 of an accumulator.
 constexpr int kScoreThreads = 256;
 constexpr int kScoreKeys = 256;    // keys per workgroup (4 waves x 2 blocks of 32)
 constexpr int kStStages = 3;
-constexpr int kStRows = 64;
-
-__global__ void score_offsets_kernel(int Q, int qpad, int tail, const float* __restrict__ lse,
-                                     const float* __restrict__ wrow, float* __restrict__ negt)
-{
-    const int head = blockIdx.y;
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= qpad) return;
-    float v = -INFINITY;
-    if (i < Q && i >= Q - tail) v = __log2f(wrow[Q - 1 - i]) - lse[(size_t)head * Q + i] * 1.4426950408889634f;
-    negt[(size_t)head * qpad + i] = v;
-}
+constexpr int kStRows = kScorePadRows;
 
 template <int D> struct ScoreSwz {   // permutation of the 16-byte pieces of a staged row
     __device__ static int of(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
@@ -209,9 +198,7 @@ void launch_score_mfma(const Geom& g, const DevBuffers& b, const SegList& sl, in
     int tiles = 0;
     for (int i = 0; i < sl.n; ++i) tiles += (sl.s[i].len + kScoreKeys - 1) / kScoreKeys;
     const dim3 grid(tiles * g.B * g.Hkv), block(kScoreThreads);
-    const int qpad = max_chunk + kStRows;
-    hipLaunchKernelGGL(score_offsets_kernel, dim3((qpad + 255) / 256, g.B * g.Hq), dim3(256), 0, s, Q, qpad, tail_rows,
-                       b.lse, b.wrow, b.negt);
+    const int qpad = max_chunk + kStRows;   // the attention launch left the offsets of this chunk's rows in b.negt
     if (g.d == 128)
         hipLaunchKernelGGL(score_stream_kernel<128>, grid, block, 0, s, g, sl, Q, max_chunk, tail_rows, qpad, decay,
                            (const bf16_t*)b.Qr, (const bf16_t*)b.Kr, (const bf16_t*)b.Krc, b.negt, b.mu, b.mu_chunk);
