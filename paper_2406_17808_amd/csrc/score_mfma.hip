@@ -28,7 +28,7 @@ namespace ckv {
 // chunk), written by the attention kernel when it finishes a row; the accumulators start from
 // it: a probability is then one v_exp_f32 of an accumulator.
 constexpr int kScoreThreads = 256;
-constexpr int kScoreKeys = 256;    // keys per workgroup (4 waves x 2 blocks of 32)
+constexpr int kScoreKeysPerBlock = 128;   // keys per workgroup and key block of its waves (4 waves x 32)
 constexpr int kStStages = 3;
 constexpr int kStRows = kScorePadRows;
 
@@ -36,13 +36,16 @@ template <int D> struct ScoreSwz {   // permutation of the 16-byte pieces of a s
     __device__ static int of(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
 };
 
-template <int D>
+// NKB: 32-key blocks per wave.  Two halve the LDS reads per MFMA; one gives twice as many
+// workgroups, for launches that would otherwise leave compute units without work.
+template <int D, int NKB>
 __global__ __launch_bounds__(kScoreThreads, 3) void score_stream_kernel(
     Geom g, SegList sl, int Q, int qstride, int tail, int qpad, float decay, const bf16_t* __restrict__ Qr,
     const bf16_t* __restrict__ Kr, const bf16_t* __restrict__ Krc, const float* __restrict__ negt,
     float* __restrict__ mu, float* __restrict__ mu_chunk)
 {
     constexpr int KS = D / 16;
+    constexpr int kScoreKeys = kScoreKeysPerBlock * NKB, kWaveKeys = 32 * NKB;
     constexpr int PPR = D / 8;                       // 16-byte pieces per row
     constexpr int RPI = 64 / PPR;                    // rows per copy instruction
     constexpr int kStageBytes = kStRows * D * 2;
@@ -64,13 +67,13 @@ __global__ __launch_bounds__(kScoreThreads, 3) void score_stream_kernel(
     if (si >= sl.n) return;       // uniform for the workgroup
     const Seg sg = sl.s[si];
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, l32 = l & 31, half = l >> 5;
-    const int wave_k0 = tile * kScoreKeys + wave * 64;       // first key of this wave inside the segment
+    const int wave_k0 = tile * kScoreKeys + wave * kWaveKeys;   // first key of this wave inside the segment
 
     // this wave's keys as B operands (rows past the end of the segment repeat its last row)
-    Frag kf[2][KS];
-    int kk[2];
+    Frag kf[NKB][KS];
+    int kk[NKB];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < NKB; ++kb) {
         kk[kb] = wave_k0 + kb * 32 + l32;
         const int kc = min(kk[kb], sg.len - 1);
         const bf16_t* krow = sg.chunk ? Krc + ((size_t)bh * Q + kc) * D : Kr + ((size_t)bh * g.slots + sg.start + kc) * D;
@@ -94,7 +97,7 @@ __global__ __launch_bounds__(kScoreThreads, 3) void score_stream_kernel(
     // the keys are in registers before the first copy is issued (a wait for them inside the loop
     // would also wait for every copy in flight)
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(kf[kb][ks].u));
     auto issue = [&](int s) {
@@ -115,7 +118,7 @@ __global__ __launch_bounds__(kScoreThreads, 3) void score_stream_kernel(
 
     int issued = 0;
     for (; issued < kStStages - 1 && issued < T; ++issued) issue(issued);
-    float red[2] = {0.f, 0.f}, colsum[2] = {0.f, 0.f};
+    float red[NKB] = {}, colsum[NKB] = {};
     int hh = 0, sp = 0;                                         // stage s = stage sp of head hh
     for (int s = 0; s < T; ++s) {
         const int ahead = issued - s - 1;                       // stages issued after stage s
@@ -134,27 +137,27 @@ __global__ __launch_bounds__(kScoreThreads, 3) void score_stream_kernel(
             const int i0 = i_base + rb * 32;
             if (rb * 32 >= rows) continue;
             if (sg.chunk && i0 + 31 < wave_k0) continue;        // chunk keys are seen by later rows only
-            f32x16_t acc[2];
+            f32x16_t acc[NKB];
 #pragma unroll
             for (int jq = 0; jq < 4; ++jq) {
                 const float4 t4 = *reinterpret_cast<const float4*>(&tneg[slot][wave][rb * 32 + jq * 8 + half * 4]);
                 acc[0][jq * 4 + 0] = t4.x; acc[0][jq * 4 + 1] = t4.y; acc[0][jq * 4 + 2] = t4.z; acc[0][jq * 4 + 3] = t4.w;
             }
-            acc[1] = acc[0];
+            if (NKB == 2) acc[NKB - 1] = acc[0];
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 Frag qf;
                 qf.u = *reinterpret_cast<const u32x4_t*>(qs + a_off[rb][ks]);
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
+                for (int kb = 0; kb < NKB; ++kb)
                     acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf.v, kf[kb][ks].v, acc[kb], 0, 0, 0);
             }
-            if (sg.chunk && i0 < wave_k0 + 63) {                // the diagonal crosses this block: mask
+            if (sg.chunk && i0 < wave_k0 + kWaveKeys - 1) {     // the diagonal crosses this block: mask
 #pragma unroll
                 for (int j = 0; j < 16; ++j) {
                     const int i = i0 + (j >> 2) * 8 + half * 4 + (j & 3);
 #pragma unroll
-                    for (int kb = 0; kb < 2; ++kb) {
+                    for (int kb = 0; kb < NKB; ++kb) {
                         const float p = __builtin_amdgcn_exp2f(acc[kb][j]);
                         colsum[kb] += kk[kb] <= i ? p : 0.f;
                     }
@@ -163,13 +166,13 @@ __global__ __launch_bounds__(kScoreThreads, 3) void score_stream_kernel(
 #pragma unroll
                 for (int j = 0; j < 16; ++j)
 #pragma unroll
-                    for (int kb = 0; kb < 2; ++kb) colsum[kb] += __builtin_amdgcn_exp2f(acc[kb][j]);
+                    for (int kb = 0; kb < NKB; ++kb) colsum[kb] += __builtin_amdgcn_exp2f(acc[kb][j]);
             }
         }
         if (++sp == spp) {                                      // the head is finished
             sp = 0;
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
+            for (int kb = 0; kb < NKB; ++kb) {
                 const float cs = colsum[kb] + __shfl_xor(colsum[kb], 32, 64);
                 if (g.head_reduce == CASCADE_REDUCE_MAX) red[kb] = hh == 0 ? cs : fmaxf(red[kb], cs);
                 else red[kb] += cs;
@@ -179,7 +182,7 @@ __global__ __launch_bounds__(kScoreThreads, 3) void score_stream_kernel(
         }
     }
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < NKB; ++kb) {
         float r = red[kb];
         if (g.head_reduce == CASCADE_REDUCE_MEAN) r /= (float)g.G;
         if (half == 0 && kk[kb] < sg.len) {
@@ -195,16 +198,23 @@ __global__ __launch_bounds__(kScoreThreads, 3) void score_stream_kernel(
 void launch_score_mfma(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, int max_chunk,
                        int tail_rows, float decay, hipStream_t s)
 {
-    int tiles = 0;
-    for (int i = 0; i < sl.n; ++i) tiles += (sl.s[i].len + kScoreKeys - 1) / kScoreKeys;
-    const dim3 grid(tiles * g.B * g.Hkv), block(kScoreThreads);
+    auto workgroups = [&](int keys) {
+        int tiles = 0;
+        for (int i = 0; i < sl.n; ++i) tiles += (sl.s[i].len + keys - 1) / keys;
+        return tiles * g.B * g.Hkv;
+    };
+    // 256 keys per workgroup unless that leaves a good part of the 256 x 3 workgroup slots empty
+    bool narrow = workgroups(2 * kScoreKeysPerBlock) < 600;
+    static const char* forced = getenv("CASCADE_KV_SCORE_NARROW");   // debug switch for A/B timing: 0 or 1
+    if (forced) narrow = forced[0] == '1';
+    const dim3 grid(workgroups(narrow ? kScoreKeysPerBlock : 2 * kScoreKeysPerBlock)), block(kScoreThreads);
     const int qpad = max_chunk + kStRows;   // the attention launch left the offsets of this chunk's rows in b.negt
-    if (g.d == 128)
-        hipLaunchKernelGGL(score_stream_kernel<128>, grid, block, 0, s, g, sl, Q, max_chunk, tail_rows, qpad, decay,
-                           (const bf16_t*)b.Qr, (const bf16_t*)b.Kr, (const bf16_t*)b.Krc, b.negt, b.mu, b.mu_chunk);
-    else
-        hipLaunchKernelGGL(score_stream_kernel<64>, grid, block, 0, s, g, sl, Q, max_chunk, tail_rows, qpad, decay,
-                           (const bf16_t*)b.Qr, (const bf16_t*)b.Kr, (const bf16_t*)b.Krc, b.negt, b.mu, b.mu_chunk);
+#define CKV_SCORE(D, NKB)                                                                                              \
+    hipLaunchKernelGGL((score_stream_kernel<D, NKB>), grid, block, 0, s, g, sl, Q, max_chunk, tail_rows, qpad, decay,     \
+                       (const bf16_t*)b.Qr, (const bf16_t*)b.Kr, (const bf16_t*)b.Krc, b.negt, b.mu, b.mu_chunk)
+    if (g.d == 128) { if (narrow) CKV_SCORE(128, 1); else CKV_SCORE(128, 2); }
+    else { if (narrow) CKV_SCORE(64, 1); else CKV_SCORE(64, 2); }
+#undef CKV_SCORE
 }
 
 }  // namespace ckv
