@@ -57,7 +57,7 @@ def test_tiny_f32_free_running(oracle_mod):
     dict(name="bf16_big_tiles", dtype=B.CASCADE_BF16, d=128, Hq=8, Hkv=2, batch=1, n_sink=64,
          sizes=[256, 256, 256, 256], chunks=[512] * 8, max_chunk=512),
     dict(name="bf16_all_rows_in_scores", dtype=B.CASCADE_BF16, d=128, Hq=8, Hkv=2, batch=1, n_sink=4,
-         sizes=[64, 64], chunks=[300] * 4, max_chunk=300, beta=0.99, score_tail_eps=-1.0),
+         sizes=[64, 64], chunks=[300] * 4, max_chunk=300, beta=0.99, score_tail_eps=-1.0, score_narrow=0),
     # keys grow along every chunk, so the running maximum of a row keeps rising by more than the
     # kernel's rescaling threshold.  bf16 operand rounding is relative: with logits of magnitude
     # ~20 the exponents are off by ~20 * 2^-8, hence the wider output tolerance of this case.
@@ -74,9 +74,9 @@ def test_tiny_f32_free_running(oracle_mod):
     # launches are otherwise split over the keys), and with an odd number of splits
     dict(name="bf16_d128_ragged_unsplit", dtype=B.CASCADE_BF16, d=128, Hq=8, Hkv=2, batch=1, n_sink=5,
          sizes=[48, 40, 36], chunks=[1, 7, 64, 100, 33, 128, 128, 2, 90, 128, 128, 77, 128, 128, 128], max_chunk=128,
-         attn_splits=1),
+         attn_splits=1, score_narrow=0),
     dict(name="bf16_big_tiles_unsplit", dtype=B.CASCADE_BF16, d=128, Hq=8, Hkv=2, batch=1, n_sink=64,
-         sizes=[256, 256, 256, 256], chunks=[512] * 8, max_chunk=512, attn_splits=1),
+         sizes=[256, 256, 256, 256], chunks=[512] * 8, max_chunk=512, attn_splits=1, score_narrow=0),
     dict(name="bf16_big_tiles_three_splits", dtype=B.CASCADE_BF16, d=128, Hq=8, Hkv=2, batch=1, n_sink=64,
          sizes=[256, 256, 256, 256], chunks=[512] * 8, max_chunk=512, attn_splits=3),
     dict(name="bf16_rising_logits_unsplit", dtype=B.CASCADE_BF16, d=64, Hq=4, Hkv=2, batch=1, n_sink=4,
@@ -111,6 +111,8 @@ def test_prefill_one_step_ahead(oracle_mod, case, monkeypatch):
     from gpu_harness import ParityRun
     if "attn_splits" in case:
         monkeypatch.setenv("CASCADE_KV_ATTN_SPLITS", str(case["attn_splits"]))
+    if "score_narrow" in case:   # 0: the score kernel keeps 64 keys per wave however small the launch
+        monkeypatch.setenv("CASCADE_KV_SCORE_NARROW", str(case["score_narrow"]))
     if "pack_reuse" in case:   # 0: every tile is packed for every chunk
         monkeypatch.setenv("CASCADE_KV_PACK_REUSE", str(case["pack_reuse"]))
     cfg = B.make_config(batch=case["batch"], n_q_heads=case["Hq"], n_kv_heads=case["Hkv"], head_dim=case["d"],
@@ -230,6 +232,8 @@ def test_random_geometries(oracle_mod, seed, monkeypatch):
     seeds pack every K/V tile for every chunk, odd seeds keep the tiles no update has written."""
     from gpu_harness import ParityRun
     monkeypatch.setenv("CASCADE_KV_PACK_REUSE", str(seed % 2))
+    # small launches take the score kernel with 32 keys per wave; half of the seeds force the 64-key form
+    monkeypatch.setenv("CASCADE_KV_SCORE_NARROW", str(seed // 2 % 2))
     rng = np.random.default_rng(1000 + seed)
     d = int(rng.choice([64, 128]))
     hkv = int(rng.choice([1, 2, 3]))
