@@ -536,8 +536,7 @@ extern "C" int cascade_decode_step(cascade_ctx* ctx, const void* dev_q, const vo
     plan_update(g, ctx->st, 1, pl);
     {
         Timed t3(ctx, CASCADE_K_UPDATE, s);
-        launch_plan(g, ctx->buf, pl, ctx->max_chunk, s);
-        launch_moves(g, ctx->dtype, ctx->buf, pl, ctx->max_chunk, dev_k, dev_v, g.Hkv * g.d, g.Hkv * g.d, s);
+        launch_small_update(g, ctx->dtype, ctx->buf, pl, ctx->max_chunk, dev_k, dev_v, g.Hkv * g.d, g.Hkv * g.d, s);
     }
     return hip_check(ctx, hipGetLastError(), "cascade_decode_step");
 }

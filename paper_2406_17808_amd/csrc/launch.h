@@ -58,6 +58,9 @@ void launch_load_state(const Geom& g, int dtype, const DevBuffers& b, const void
 void launch_prep(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int Q, float qscale, int q_first_row,
                  const void* q, const void* k, const void* v, hipStream_t s);
 void launch_plan(const Geom& g, const DevBuffers& b, const UpdatePlan& pl, int max_chunk, hipStream_t s);
+// launch_plan + launch_moves in one launch, one workgroup per (sequence, KV head): for updates of a few tokens
+void launch_small_update(const Geom& g, int dtype, const DevBuffers& b, const UpdatePlan& pl, int max_chunk,
+                         const void* k, const void* v, int k_token_stride, int k_batch_stride, hipStream_t s);
 void launch_moves(const Geom& g, int dtype, const DevBuffers& b, const UpdatePlan& pl, int max_chunk,
                   const void* k, const void* v, int k_token_stride, int k_batch_stride, hipStream_t s);
 
