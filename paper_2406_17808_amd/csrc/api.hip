@@ -526,17 +526,14 @@ extern "C" int cascade_decode_step(cascade_ctx* ctx, const void* dev_q, const vo
         Timed t1(ctx, CASCADE_K_DECODE_PV, s);
         launch_decode_pv(g, ctx->dtype, ctx->buf, sl, s);
     }
-    {
-        Timed t2(ctx, CASCADE_K_DECODE_FINISH, s);
-        launch_decode_finish(g, ctx->dtype, ctx->buf, sl, ctx->max_chunk, dev_v, dev_out, s);
-    }
+    // the snapshot holds the cached scores after this step's EMA update and before the insertion
     int rc = snapshot_scores(ctx, 1, s);
     if (rc) return rc;
     UpdatePlan pl;
     plan_update(g, ctx->st, 1, pl);
     {
-        Timed t3(ctx, CASCADE_K_UPDATE, s);
-        launch_small_update(g, ctx->dtype, ctx->buf, pl, ctx->max_chunk, dev_k, dev_v, g.Hkv * g.d, g.Hkv * g.d, s);
+        Timed t2(ctx, CASCADE_K_DECODE_FINISH, s);
+        launch_decode_finish(g, ctx->dtype, ctx->buf, sl, pl, ctx->max_chunk, dev_k, dev_v, dev_out, s);
     }
     return hip_check(ctx, hipGetLastError(), "cascade_decode_step");
 }

@@ -391,103 +391,6 @@ __global__ void move_kernel(Geom g, UpdatePlan pl, int c, int E, int extra, int 
     }
 }
 
-// Plan and moves of a small update (a decode step: one token) in one launch: one workgroup per
-// (sequence, KV head) takes the decisions of plan_kernel and then writes the final content of
-// every touched slot itself, the last cascade first (destinations of cascade c take their
-// sources from earlier cascades or from the new tokens only, so every source is still intact
-// when it is read), with a barrier between cascades.
-template <typename T>
-__global__ void small_update_kernel(Geom g, UpdatePlan pl, int qstride, const float2* __restrict__ rope,
-                                    int32_t* __restrict__ offers, int32_t* __restrict__ winners, int32_t* __restrict__ swaps,
-                                    T* __restrict__ Kc, T* __restrict__ Kr, T* __restrict__ Vc,
-                                    float* __restrict__ mu, int32_t* __restrict__ ids, const float* __restrict__ mu_chunk,
-                                    const T* __restrict__ k_in, const T* __restrict__ v_in, long tok_stride, long batch_stride)
-{
-    const int bh = blockIdx.x;
-    const int b = bh / g.Hkv, h = bh % g.Hkv;
-    const float* mub = mu + (size_t)bh * g.slots;
-    const float* muc = mu_chunk + (size_t)bh * qstride;
-    int32_t* off_in = offers + (size_t)bh * 2 * qstride;
-    int32_t* off_out = off_in + qstride;
-    for (int c = 0; c < pl.N; ++c) {
-        const CascStep cs = pl.c[c];
-        if (cs.M == 0) break;
-        int32_t* W = winners + ((size_t)bh * pl.N + c) * (qstride + 1);
-        const int nseg = cs.J + cs.pre;
-        int my_swaps = 0;
-        for (int sidx = threadIdx.x; sidx < nseg; sidx += blockDim.x) {
-            const int j = sidx - cs.pre;
-            int sw;
-            W[1 + j] = segment_winner(cs, c, j, g.slots, pl.n_to_sink, g.token_selection, off_in, mub, muc, &sw);
-            my_swaps += sw;
-        }
-        if (my_swaps) atomicAdd(&swaps[bh * pl.N + c], my_swaps);
-        __syncthreads();
-        for (int i = threadIdx.x; i < cs.P; i += blockDim.x) off_out[i] = evicted_ref(cs, i, W);
-        __syncthreads();
-        int32_t* tmp = off_in; off_in = off_out; off_out = tmp;
-    }
-    const int half = g.d / 2;
-    for (int c = pl.N - 1; c >= -1; --c) {
-        int E, extra = 0;
-        if (c < 0) E = pl.n_to_sink;
-        else { if (pl.c[c].M == 0) continue; E = final_entries(pl.c[c], &extra); }
-        for (int e = 0; e < E + extra; ++e) {
-            int dst, ref;
-            if (c < 0) { dst = pl.sink_fill0 + e; ref = g.slots + e; }
-            else {
-                const int32_t* W = winners + ((size_t)bh * pl.N + c) * (qstride + 1);
-                if (!final_entry(pl.c[c], e, E, W, &dst, &ref)) continue;
-            }
-            const size_t drow = ((size_t)bh * g.slots + dst) * g.d;
-            const T *ks, *vs;
-            float score;
-            int id;
-            if (ref < g.slots) {
-                const size_t srow = ((size_t)bh * g.slots + ref) * g.d;
-                ks = Kc + srow; vs = Vc + srow;
-                score = mu[(size_t)bh * g.slots + ref];
-                id = ids[(size_t)bh * g.slots + ref];
-            } else {
-                const int i = ref - g.slots;
-                const size_t srow = (size_t)b * batch_stride + (size_t)i * tok_stride + (size_t)h * g.d;
-                ks = k_in + srow; vs = v_in + srow;
-                score = mu_chunk[(size_t)bh * qstride + i];
-                id = pl.id0 + i;
-            }
-            for (int p = threadIdx.x; p < half; p += blockDim.x) {
-                const float x0 = Elem<T>::load(ks + p), x1 = Elem<T>::load(ks + p + half);
-                const float2 cs2 = rope[(size_t)dst * half + p];
-                Elem<T>::store(Kc + drow + p, x0);
-                Elem<T>::store(Kc + drow + p + half, x1);
-                Elem<T>::store(Kr + drow + p, x0 * cs2.x - x1 * cs2.y);
-                Elem<T>::store(Kr + drow + p + half, x1 * cs2.x + x0 * cs2.y);
-                Vc[drow + p] = vs[p];
-                Vc[drow + p + half] = vs[p + half];
-            }
-            if (threadIdx.x == 0) {
-                mu[(size_t)bh * g.slots + dst] = score;
-                ids[(size_t)bh * g.slots + dst] = id;
-            }
-        }
-        __syncthreads();   // the rows of this cascade are written before an earlier cascade's slots are overwritten
-    }
-}
-
-void launch_small_update(const Geom& g, int dtype, const DevBuffers& b, const UpdatePlan& pl, int max_chunk,
-                         const void* k, const void* v, int k_token_stride, int k_batch_stride, hipStream_t s)
-{
-    const dim3 grid(g.B * g.Hkv), block(64);
-    if (dtype == CASCADE_F32)
-        hipLaunchKernelGGL(small_update_kernel<float>, grid, block, 0, s, g, pl, max_chunk, b.rope, b.offers, b.winners, b.swaps,
-                           (float*)b.Kc, (float*)b.Kr, (float*)b.Vc, b.mu, b.ids, b.mu_chunk, (const float*)k, (const float*)v,
-                           (long)k_token_stride, (long)k_batch_stride);
-    else
-        hipLaunchKernelGGL(small_update_kernel<bf16_t>, grid, block, 0, s, g, pl, max_chunk, b.rope, b.offers, b.winners, b.swaps,
-                           (bf16_t*)b.Kc, (bf16_t*)b.Kr, (bf16_t*)b.Vc, b.mu, b.ids, b.mu_chunk, (const bf16_t*)k, (const bf16_t*)v,
-                           (long)k_token_stride, (long)k_batch_stride);
-}
-
 // The moves of all cascades in two launches.  Every entry (cascade, index) names a destination
 // slot and a source; gather_kernel copies the sources that are cache rows (un-rotated key, value,
 // score, id: the state before the update) into a staging array, scatter_kernel then writes every

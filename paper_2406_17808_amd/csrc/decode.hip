@@ -6,6 +6,7 @@
 
 #include "async_copy.h"
 #include "launch.h"
+#include "small_update.h"
 
 namespace ckv {
 
@@ -490,9 +491,10 @@ __global__ __launch_bounds__(kDecThreads) void decode_pv_kernel(
 }
 
 // out = sum of the split outputs + own value weighted by its probability; the new token's
-// score starts at (1-beta) * reduce_heads(p_own).
+// score starts at (1-beta) * reduce_heads(p_own).  The same workgroup then inserts the token
+// (Alg. 2 for one token: small_update.h).
 template <typename T>
-__global__ void decode_finish_kernel(Geom g, int n_cached, int n_splits, int qstride, int maxg,
+__global__ void decode_finish_kernel(Geom g, UpdatePlan pl, UpdateBuffers upd, int n_cached, int n_splits, int qstride, int maxg,
                                      const float* __restrict__ opart, const float* __restrict__ logits,
                                      const float* __restrict__ lse, const T* __restrict__ v_new,
                                      T* __restrict__ out, float* __restrict__ mu_chunk)
@@ -517,6 +519,8 @@ __global__ void decode_finish_kernel(Geom g, int n_cached, int n_splits, int qst
         if (g.head_reduce == CASCADE_REDUCE_MEAN) red /= (float)g.G;
         mu_chunk[((size_t)b * g.Hkv + hk) * qstride] = (1.f - g.beta) * red;
     }
+    __syncthreads();   // the token's score is written
+    small_update<T>(g, pl, qstride, upd, b, hk);
 }
 
 // ------------------------------------------------------------------ PV and EMA scores, bf16: MFMA fed from LDS
@@ -1062,15 +1066,17 @@ void launch_decode_pv(const Geom& g, int dtype, const DevBuffers& b, const SegLi
     CKV_DISPATCH(pv_typed, g, b, sl, s);
 }
 
-void launch_decode_finish(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int qstride, const void* v,
-                          void* out, hipStream_t s)
+void launch_decode_finish(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, const UpdatePlan& pl, int qstride,
+                          const void* k, const void* v, void* out, hipStream_t s)
 {
     const dim3 grid(g.Hkv, g.B), block(256);
+    const UpdateBuffers upd = {b.rope, b.offers, b.winners, b.swaps, b.Kc, b.Kr, b.Vc, b.mu, b.ids, b.mu_chunk,
+                               k, v, (long)g.Hkv * g.d, (long)g.Hkv * g.d};
     if (dtype == CASCADE_F32)
-        hipLaunchKernelGGL(decode_finish_kernel<float>, grid, block, 0, s, g, sl.n_cached, b.dec_splits, qstride, maxg_of(g), b.opart,
+        hipLaunchKernelGGL(decode_finish_kernel<float>, grid, block, 0, s, g, pl, upd, sl.n_cached, b.dec_splits, qstride, maxg_of(g), b.opart,
                            b.logits, b.lse, (const float*)v, (float*)out, b.mu_chunk);
     else
-        hipLaunchKernelGGL(decode_finish_kernel<bf16_t>, grid, block, 0, s, g, sl.n_cached, b.dec_splits, qstride, maxg_of(g), b.opart,
+        hipLaunchKernelGGL(decode_finish_kernel<bf16_t>, grid, block, 0, s, g, pl, upd, sl.n_cached, b.dec_splits, qstride, maxg_of(g), b.opart,
                            b.logits, b.lse, (const bf16_t*)v, (bf16_t*)out, b.mu_chunk);
 }
 

@@ -58,9 +58,6 @@ void launch_load_state(const Geom& g, int dtype, const DevBuffers& b, const void
 void launch_prep(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int Q, float qscale, int q_first_row,
                  const void* q, const void* k, const void* v, hipStream_t s);
 void launch_plan(const Geom& g, const DevBuffers& b, const UpdatePlan& pl, int max_chunk, hipStream_t s);
-// launch_plan + launch_moves in one launch, one workgroup per (sequence, KV head): for updates of a few tokens
-void launch_small_update(const Geom& g, int dtype, const DevBuffers& b, const UpdatePlan& pl, int max_chunk,
-                         const void* k, const void* v, int k_token_stride, int k_batch_stride, hipStream_t s);
 void launch_moves(const Geom& g, int dtype, const DevBuffers& b, const UpdatePlan& pl, int max_chunk,
                   const void* k, const void* v, int k_token_stride, int k_batch_stride, hipStream_t s);
 
@@ -86,8 +83,9 @@ void launch_score_mfma(const Geom& g, const DevBuffers& b, const SegList& sl, in
 void launch_decode_qk(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl,
                       const void* q, const void* k, hipStream_t s);
 void launch_decode_pv(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, hipStream_t s);
-void launch_decode_finish(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int qstride,
-                          const void* v, void* out, hipStream_t s);
+// merges the split outputs into `out`, gives the new token its score and inserts it (plan and moves of `pl`, one token)
+void launch_decode_finish(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, const UpdatePlan& pl, int qstride,
+                          const void* k, const void* v, void* out, hipStream_t s);
 bool decode_supported(const Geom& g);
 int decode_logit_heads(const Geom& g);   // heads per row of the logits buffer (group size rounded up to 1, 2, 4, 8)
 
