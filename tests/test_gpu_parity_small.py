@@ -152,6 +152,42 @@ def test_prefill_one_step_ahead(oracle_mod, case, monkeypatch):
     run.close()
 
 
+@pytest.mark.parametrize("seed", list(range(10)))
+def test_kept_tiles_random_rings(oracle_mod, seed, monkeypatch):
+    """Rings of whole tiles with random sizes, sink counts that are and are not multiples of a
+    tile, chunks that keep every ring head at its offset inside a tile, chunks that do not, and
+    decode steps in between: the packed K/V tiles are kept from chunk to chunk whenever the heads
+    allow it, and every step is compared with the oracle."""
+    from gpu_harness import ParityRun
+    monkeypatch.setenv("CASCADE_KV_PACK_REUSE", "1")
+    rng = np.random.default_rng(5000 + seed)
+    N = int(rng.integers(1, 4))
+    sizes = [int(rng.integers(1, 5)) * 64 for _ in range(N)]
+    n_sink = int(rng.choice([0, 5, 64, 70]))
+    d, hkv, G = int(rng.choice([64, 128])), int(rng.choice([1, 2])), int(rng.choice([1, 2, 4]))
+    unit = 64 * 2 ** (N - 1)      # the last cascade then receives a multiple of 64 tokens per chunk
+    cfg = B.make_config(batch=1, n_q_heads=hkv * G, n_kv_heads=hkv, head_dim=d, dtype=B.CASCADE_BF16, n_sink=n_sink,
+                        cascade_sizes=sizes, ema_beta=float(rng.choice([0.9, 0.99])), rope_base=10000.0,
+                        max_chunk=4 * unit, keep_update_scores=1)
+    tol_out, tol_score = _tolerances(cfg)
+    run = ParityRun(cfg, one_step_ahead=True)
+    plan = []
+    for _ in range(14):
+        r = rng.random()
+        if r < 0.7:
+            plan.append(("p", int(rng.integers(1, 5)) * unit))
+        elif r < 0.85:
+            plan.append(("p", int(rng.integers(1, 4 * unit + 1))))
+        else:
+            plan += [("d", 1)] * int(rng.integers(1, 4))
+    for i, (kind, n) in enumerate(plan):
+        q, k, v = _inputs(rng, cfg, n)
+        rep = run.step(q, k, v, decode=(kind == "d"))
+        assert rep.replay_exact, (seed, i, kind, n)
+        assert rep.out_err <= tol_out and rep.score_err <= tol_score, (seed, i, kind, n, rep)
+    run.close()
+
+
 def test_sixteen_cascades(oracle_mod):
     """The largest number of sub-caches the configuration allows: once all rings are full the
     segment list holds three pieces per ring (50 segments, 34 query rotations); a decode step then
