@@ -293,8 +293,12 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int j = 0; j < 16; ++j)
+                for (int j = 0; j < 16; ++j) {
                     if (kb * 32 + (j >> 2) * 8 + (j & 3) > rel) s[kb][j] = -INFINITY;
+                    // a few compares at a time: all 32 lane masks at once take 64 scalar registers, which
+                    // pushes values that live across the loop out to vector lanes
+                    if ((j & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+                }
         }
         if (!bounded || first) {   // bounded: no exponent of this workgroup can exceed m_run by more than 2^kBoundLog2
             float x = -INFINITY;
