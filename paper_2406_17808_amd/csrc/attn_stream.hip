@@ -24,6 +24,8 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include "async_copy.h"
 #include "mfma_util.h"
 
@@ -286,8 +288,8 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     // when that exceeds kRescaleLog2 (the probabilities then stay below 2^kRescaleLog2, and most
     // tiles skip the rescaling of O), and turn S^T into probabilities.  FIRST: S^T is absolute
     // and m_run not set yet (the first tile of a workgroup).
-    auto softmax_tile = [&](const TileIter& it, bool first) {
-        if ((it.t0 + kBN > it.sg.len) || (it.sg.chunk && it.t0 + kBN - 1 > wave_imin)) {
+    auto softmax_tile = [&](const TileIter& it, bool first, auto interior) {
+        if (!decltype(interior)::value && ((it.t0 + kBN > it.sg.len) || (it.sg.chunk && it.t0 + kBN - 1 > wave_imin))) {
             const int lim = it.sg.chunk ? min(it.sg.len - 1, qi) : it.sg.len - 1;   // last visible key
             const int rel = lim - it.t0 - half * 4;   // accumulator j of block kb is key t0 + 4*half + (32 kb + 8 (j/4) + j%4)
 #pragma unroll
@@ -423,7 +425,7 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     for (int w = 0; w < kSWaves; ++w) kn2 = fmaxf(kn2, kn_wave[w]);
     qk_tile(Ks);
     if (!SPLIT || wave_active(it1)) {
-        softmax_tile(it1, true);    // not SPLIT: every wave sees the first tile
+        softmax_tile(it1, true, std::false_type());    // not SPLIT: every wave sees the first tile
     } else {
 #pragma unroll
         for (int qt = 0; qt < 4; ++qt)
@@ -447,23 +449,15 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     long long tc[5] = {0, 0, 0, 0, 0}, tlast = 0;
     if (DBG) tlast = __builtin_readcyclecounter();
     auto lap = [&](int i) { if (DBG) { const long long now = __builtin_readcyclecounter(); tc[i] += now - tlast; tlast = now; } };
-    while (true) {
-        const bool has_next = n0 + 1 < NT;
-        const bool act_next = has_next && wave_active(it1);
-        if (act_next && q_var != it1.sg.qvar) {
-            load_q(it1.sg);
-            q_var = it1.sg.qvar;
-            wait_vm<0>();   // here, so that no wait for these loads is placed among the MFMAs (it would also wait for the copies)
-        }
-        // ---- matrix block.  A wave that does not see tile t holds zero probabilities; S^T of a
-        // tile this wave does not see (or that does not exist: stale buffer) is computed and
-        // dropped.  The order of MFMAs and reads is pinned step by step.
-        lap(0);
+    // ---- matrix block of iteration t.  A wave that does not see tile t holds zero probabilities;
+    // S^T of a tile this wave does not see (or that does not exist: stale buffer) is computed and
+    // dropped.  The order of MFMAs and reads is pinned step by step.
+    auto matrix_block = [&](int t) {
         __builtin_amdgcn_s_setprio(2);
         __builtin_amdgcn_sched_barrier(0);
         {
-            const bf16_t* Vtile = Vs + (n0 & 3) * TILE;
-            const bf16_t* Ktile = Ks + ((n0 + 1) & 3) * TILE;
+            const bf16_t* Vtile = Vs + (t & 3) * TILE;
+            const bf16_t* Ktile = Ks + ((t + 1) & 3) * TILE;
 #pragma unroll
             for (int i = 0; i < NF; ++i) {
                 if (i < NV) o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kAhead].v, pf[i / DB].v, o[i % DB], 0, 0, 0);
@@ -472,8 +466,46 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
+        // S^T is complete here: without this use the compiler may sink the last MFMAs (they touch no
+        // memory) past the end of the block, below the barrier and into the vector block
+        asm volatile("" : "+v"(s[0]), "+v"(s[1]));
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_setprio(0);
+    };
+    while (true) {
+        // Steady state: as long as tile t+1 is a whole tile of cached rows with another tile of the same
+        // segment behind it and both copies of the batch exist, an iteration needs none of the tests below
+        // (visibility, masks, change of rotation, which copies to issue, how many to wait for).
+        if (!it1.sg.chunk && q_var == it1.sg.qvar) {
+            int k = min((it1.len - it1.t0 - 1) / kBN, NT - 4 - n0);
+            for (; k > 0; --k) {
+                lap(0);
+                matrix_block(n0);
+                lap(1);
+                wg_barrier();
+                lap(2);
+#pragma unroll
+                for (int i = 0; i < kAhead; ++i) fr[i] = read_frag(Vs + ((n0 + 1) & 3) * TILE, Ks, i);
+                copy_tile(kt_bh, lds_k, n0 + 4, n0 & 3);
+                copy_tile(vt_bh, lds_v, n0 + 3, (n0 + 3) & 3);
+                softmax_tile(it1, false, std::true_type());
+                lap(3);
+                wait_vm<2 * PW>();
+                wg_barrier();
+                lap(4);
+                it1.t0 += kBN;
+                ++n0;
+            }
+        }
+        const bool has_next = n0 + 1 < NT;
+        const bool act_next = has_next && wave_active(it1);
+        if (act_next && q_var != it1.sg.qvar) {
+            load_q(it1.sg);
+            q_var = it1.sg.qvar;
+            wait_vm<0>();   // here, so that no wait for these loads is placed among the MFMAs (it would also wait for the copies)
+        }
+        lap(0);
+        matrix_block(n0);
         lap(1);
         if (!has_next) break;
         wg_barrier();     // barrier 2t+1 (early group), 2t+2 (late group)
@@ -484,7 +516,7 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
         const int in_flight = issue(n0);   // here: a copy instruction can hold a wave up, and this block has time to spare
         // ---- vector block
         if (act_next) {
-            softmax_tile(it1, false);
+            softmax_tile(it1, false, std::false_type());
         } else {
 #pragma unroll
             for (int qt = 0; qt < 4; ++qt)
