@@ -100,17 +100,33 @@ __global__ __launch_bounds__(kScoreThreads, 3) void score_stream_kernel(
     for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(kf[kb][ks].u));
-    auto issue = [&](int s) {
-        const int hh = s / spp, i_base = i_first + (s - hh * spp) * kStRows;
-        const int h = hk * g.G + hh, slot = s % kStStages;
-        const bf16_t* qbase = Qr + (((size_t)sg.qvar * g.B + b) * g.Hq + h) * (size_t)Q * D;
+    // what a lane copies of a stage: row x*RPI + l/PPR of the stage, one 16-byte piece (lane constants)
+    uint32_t copy_off[NCW];
 #pragma unroll
-        for (int y = 0; y < NCW; ++y) {
-            const int x = wave * NCW + y;
-            const int row = x * RPI + l / PPR;
-            const int piece = (l % PPR) ^ ScoreSwz<D>::of(row);
-            async_copy_1k(qbase, (uint32_t)((min(i_base + row, Q - 1) * PPR + piece) * 16),
-                          __builtin_amdgcn_readfirstlane(ring_lds + slot * kStageBytes + x * 1024));
+    for (int y = 0; y < NCW; ++y) {
+        const int row = (wave * NCW + y) * RPI + l / PPR;
+        copy_off[y] = (uint32_t)((row * PPR + ((l % PPR) ^ ScoreSwz<D>::of(row))) * 16);
+    }
+    int iss_hh = 0, iss_sp = 0;                                 // stage s, the next to issue, is stage iss_sp of head iss_hh
+    auto issue = [&](int s) {
+        const int i_base = i_first + iss_sp * kStRows;
+        const int h = hk * g.G + iss_hh, slot = s % kStStages;
+        if (++iss_sp == spp) { iss_sp = 0; ++iss_hh; }
+        const bf16_t* qbase = Qr + (((size_t)sg.qvar * g.B + b) * g.Hq + h) * (size_t)Q * D;
+        if (i_base + kStRows <= Q) {          // all rows of the stage exist: the lane offsets are constants
+#pragma unroll
+            for (int y = 0; y < NCW; ++y)
+                async_copy_1k(qbase + (size_t)i_base * D, copy_off[y],
+                              __builtin_amdgcn_readfirstlane(ring_lds + slot * kStageBytes + (wave * NCW + y) * 1024));
+        } else {
+#pragma unroll
+            for (int y = 0; y < NCW; ++y) {
+                const int x = wave * NCW + y;
+                const int row = x * RPI + l / PPR;
+                const int piece = (l % PPR) ^ ScoreSwz<D>::of(row);
+                async_copy_1k(qbase, (uint32_t)((min(i_base + row, Q - 1) * PPR + piece) * 16),
+                              __builtin_amdgcn_readfirstlane(ring_lds + slot * kStageBytes + x * 1024));
+            }
         }
         async_copy_256(negt + ((size_t)b * g.Hq + h) * qpad + i_base, (uint32_t)(l * 4),
                        __builtin_amdgcn_readfirstlane(tneg_lds + (uint32_t)((slot * 4 + wave) * kStRows * 4)));
