@@ -473,11 +473,14 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
         __builtin_amdgcn_s_setprio(0);
     };
     while (true) {
-        // Steady state: as long as tile t+1 is a whole tile of cached rows with another tile of the same
-        // segment behind it and both copies of the batch exist, an iteration needs none of the tests below
-        // (visibility, masks, change of rotation, which copies to issue, how many to wait for).
-        if (!it1.sg.chunk && q_var == it1.sg.qvar) {
+        // Steady state: as long as tile t+1 is a whole tile that every row of the wave sees completely,
+        // with another tile of the same segment behind it and both copies of the batch ahead, an iteration
+        // needs none of the tests below (visibility, masks, change of rotation, which copies to issue, how
+        // many to wait for).  Waves may disagree on it: both loops pass the same barriers and issue the
+        // same copies.
+        if (q_var == it1.sg.qvar) {
             int k = min((it1.len - it1.t0 - 1) / kBN, NT - 4 - n0);
+            if (it1.sg.chunk) k = min(k, (wave_imin + 1 - it1.t0) / kBN);   // chunk tiles every row of the wave sees whole
             for (; k > 0; --k) {
                 lap(0);
                 matrix_block(n0);
