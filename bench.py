@@ -3,8 +3,10 @@
 
 A step is one pass of the whole prefill hot path over one chunk of the workload: query/key
 rotation, chunk attention, exact EMA score sums and the cascade update (one call of
-cascade_prefill_chunk).  The default workload is the 1M-token / 65K-slot prefill; warm-up
-chunks are the first chunks of the stream (32 of them fill the cache), the timed chunks follow.
+cascade_prefill_chunk).  The default workload is the 1M-token / 65K-slot prefill.  Whatever
+--warmup and --steps say, the first chunks of the stream are run untimed as SETUP until every
+slot of the cache is occupied (33 chunks for that workload); the warm-up chunks and then the
+timed chunks follow, so every timed chunk attends to a full cache.
 The single JSON line also carries the decode-step latency of the batch-32 decode workload, the
 roofline figures of the dominant kernel of each, and the CPU oracle timed on a bounded sample.
 """
@@ -19,6 +21,7 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK = 2.5e15     # dense bf16 MFMA FLOP/s of one MI355X
 HBM_PEAK = 8.0e12           # bytes/s
+HEADLINE = "prefill_1m"     # the workload the metric is quoted on: its timed chunks must see a full cache
 
 
 def stored_traffic(name):
@@ -48,15 +51,29 @@ def prefill_bench(args, torch, B, wl):
     from paper_2406_17808_amd.workloads import chunk_inputs_torch
     dev = "cuda:0"
     W, K = args.warmup, args.steps
-    assert W + K <= wl.n_chunks, f"{wl.name} has only {wl.n_chunks} chunks"
     cfg = config_of(wl)
-    cache = CascadeKVCache(cfg, dev)
-    chunks = [chunk_inputs_torch(wl, args.seed, c, dev) for c in range(W + K)]
-    out = torch.empty_like(chunks[0][0])
     # cached rows before every chunk (host arithmetic; the fill does not depend on the scores)
-    n_before = [B.cascade_simulate_structure(cfg, [wl.chunk] * c).count if c else 0 for c in range(W + K)]
-    for c in range(W):
+    n_before = [B.cascade_simulate_structure(cfg, [wl.chunk] * c).count if c else 0 for c in range(wl.n_chunks + 1)]
+    # setup chunks: the stream from its start until every slot is occupied
+    F = next((c for c in range(wl.n_chunks + 1) if n_before[c] == wl.n_slots), None)
+    if F is None and wl.name != HEADLINE:
+        # a stream too short to fill its cache (Eq. 4: the span of the cascades exceeds it): time its last chunks
+        F = max(wl.n_chunks - W - K, 0)
+    if F is None or F + W + K > wl.n_chunks:
+        print(f"bench.py: {wl.name} has {wl.n_chunks} chunks; {F} fill the cache, so --warmup + --steps "
+              f"must not exceed {wl.n_chunks - (F or 0)}", file=sys.stderr)
+        sys.exit(2)
+    cache = CascadeKVCache(cfg, dev)
+    out = None
+    for c in range(F):      # untimed, generated and dropped one at a time
+        qkv = chunk_inputs_torch(wl, args.seed, c, dev)
+        out = torch.empty_like(qkv[0]) if out is None else out
+        cache.prefill_chunk(*qkv, out=out)
+    chunks = {c: chunk_inputs_torch(wl, args.seed, c, dev) for c in range(F, F + W + K)}
+    out = torch.empty_like(chunks[F][0]) if out is None else out
+    for c in range(F, F + W):
         cache.prefill_chunk(*chunks[c], out=out)
+    W += F                  # index of the first timed chunk
     torch.cuda.synchronize()
     accepted_before = cache.read_state().accepted.copy()
     B.cascade_profile_begin(cache.ctx)
@@ -82,19 +99,25 @@ def prefill_bench(args, torch, B, wl):
     attn_ms, attn_n = prof["attention"]
     avg_s = attn_ms / 1e3 / max(attn_n, 1)
     achieved = (sum(flops) / K) / avg_s
+    rows_first, rows_last = n_before[W], n_before[W + K - 1]
+    if min(rows_first, rows_last) < wl.n_slots and wl.name == HEADLINE:     # cannot happen after the setup above
+        print(f"bench.py: timed chunks saw {rows_first}..{rows_last} cached rows, below the {wl.n_slots} slots", file=sys.stderr)
+        sys.exit(3)
     res = {
+        "setup_chunks": F, "timed_chunks": [W, W + K], "cache_rows_first_timed": rows_first, "cache_rows_last_timed": rows_last,
         "tokens_per_s": tokens / seconds, "ms_per_step": seconds * 1e3 / K,
         "kernel_ms_per_step": {k: v[0] / max(v[1], 1) for k, v in prof.items() if v[1]},
         "roofline": {"bound": "mfma", "kernel": "attn_stream_kernel", "achieved": achieved / 1e12,
                      "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK,
                      "traffic": stored_traffic("attn_stream_kernel_prefill_1m_hbm_traffic.json") if wl.name == "prefill_1m" else None,
+                     "traffic_source": "profiles/attn_stream_kernel_prefill_1m_hbm_traffic.json (rocprofv3 --pmc runs, not this run)",
                      "flop_per_launch": sum(flops) / K, "avg_launch_ms": avg_s * 1e3},
         "end_to_end_mfma_frac": (sum(flops) / seconds) / MFMA_BF16_PEAK,
         "roofline_update": {"bound": "hbm", "kernel": "plan_kernel + gather_kernel + scatter_kernel", "achieved": upd_rate / 1e9,
                             "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": upd_rate / HBM_PEAK,
                             "rows_moved_per_step": moved / max(K, 1), "avg_ms_per_step": upd_ms / max(upd_n, 1)},
     }
-    return res, cache, chunks, cfg
+    return res, cache, [chunks[c] for c in sorted(chunks)], cfg
 
 
 def cpu_baseline(args, torch, B, wl, cache, cfg, chunks):
@@ -174,7 +197,8 @@ def decode_bench(args, torch, B):
         "roofline_decode": {"bound": "hbm", "kernel": "decode_qk_stream_kernel", "achieved": k_bytes / (qk_ms / 1e3 / max(qk_n, 1)) / 1e9,
                             "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                             "frac": k_bytes / (qk_ms / 1e3 / max(qk_n, 1)) / HBM_PEAK,
-                            "traffic": stored_traffic("decode_qk_stream_kernel_decode_b32_hbm_traffic.json")},
+                            "traffic": stored_traffic("decode_qk_stream_kernel_decode_b32_hbm_traffic.json"),
+                            "traffic_source": "profiles/decode_qk_stream_kernel_decode_b32_hbm_traffic.json (rocprofv3 --pmc runs, not this run)"},
     }
     cache.close()
     return res
@@ -183,8 +207,8 @@ def decode_bench(args, torch, B):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=224)
-    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="prefill_1m")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--cpu-sample-tokens", type=int, default=640)
@@ -217,7 +241,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "seq_len": wl.seq_len, "chunk": wl.chunk, "n_sink": wl.n_sink,
                    "cascades": list(wl.cascade_sizes), "n_q_heads": wl.n_q_heads, "n_kv_heads": wl.n_kv_heads,
-                   "head_dim": wl.head_dim, "ema_beta": wl.ema_beta, "timed_chunks": [args.warmup, args.warmup + args.steps]},
+                   "head_dim": wl.head_dim, "ema_beta": wl.ema_beta, "n_slots": wl.n_slots, "setup_chunks": res["setup_chunks"],
+                   "timed_chunks": res["timed_chunks"], "cache_rows_first_timed": res["cache_rows_first_timed"],
+                   "cache_rows_last_timed": res["cache_rows_last_timed"]},
         "roofline": res["roofline"], "kernel_ms_per_step": res["kernel_ms_per_step"],
         "end_to_end_mfma_frac": res["end_to_end_mfma_frac"], "roofline_update": res["roofline_update"],
     }

@@ -14,7 +14,10 @@
  *     Alg. 3 gives for the rows of a chunk are this recurrence unrolled).
  *   - the insertion of one item into sinks / cascades: Alg. 2.
  *   - GQA: one decision per KV head, query heads of a group reduced by max
- *     (or mean): Appendix "Head Policy and Head Reduction".
+ *     (or mean): Appendix "Head Policy and Head Reduction".  The same appendix's
+ *     "homogeneous heads" (one decision shared by all heads) is the switch
+ *     head_policy = 1: the head axis is reduced to ONE score per token, over all
+ *     query heads, and every KV head takes its decisions with that score.
  *
  * Readings taken where the paper is silent:
  *   R1  a cascade with period f accepts when (t mod f) == 0, where t counts the
@@ -36,7 +39,9 @@
  * sink + sliding-window special case (one cascade), the full causal attention
  * special case (nothing discarded yet), the positional-encoding example of
  * Section 3.1, a hand trace of Alg. 2, the acceptance rates and the span of
- * Eq. 4, and the row-sum identity of the EMA increments.  R1 (phase of the
+ * Eq. 4, the row-sum identity of the EMA increments, the comparison record of the
+ * hand traces, and for homogeneous heads brute force over all query heads plus the
+ * one-KV-head case where both policies coincide.  R1 (phase of the
  * acceptance schedule) and the order of head reduction in R3 are fixed by these
  * readings only: parity unpinned by the paper for those two choices.
  *
@@ -58,6 +63,7 @@ typedef struct {
     double ema_beta, rope_base, softmax_scale;
     int32_t head_reduce;      /* 0 max, 1 mean */
     int32_t token_selection;  /* 1 as in the paper, 0: never replace */
+    int32_t head_policy;      /* 0 independent KV heads (the paper's choice), 1 homogeneous */
 } oracle_config;
 
 typedef struct {
@@ -82,6 +88,11 @@ typedef struct {
     int64_t last_delta_n;
     int64_t *discard_log; /* ids in the order they were discarded */
     int64_t n_discard_log, cap_discard_log;
+    /* every token-selection comparison of Alg. 2 in the order it was taken: ids and scores of
+       the incoming item and of the newest item of the cascade (a record, not arithmetic) */
+    int64_t *select_ids;  /* [n][2] incoming, newest */
+    double *select_mu;    /* [n][2] */
+    int64_t n_select_log, cap_select_log;
 } head_t;
 
 typedef struct {
@@ -100,6 +111,20 @@ static void log_discard(head_t *H, int64_t id)
         H->discard_log = (int64_t *)realloc(H->discard_log, sizeof(int64_t) * (size_t)H->cap_discard_log);
     }
     H->discard_log[H->n_discard_log++] = id;
+}
+
+static void log_select(head_t *H, int64_t id_in, double mu_in, int64_t id_newest, double mu_newest)
+{
+    if (H->n_select_log == H->cap_select_log) {
+        H->cap_select_log = H->cap_select_log ? 2 * H->cap_select_log : 1024;
+        H->select_ids = (int64_t *)realloc(H->select_ids, sizeof(int64_t) * 2 * (size_t)H->cap_select_log);
+        H->select_mu = (double *)realloc(H->select_mu, sizeof(double) * 2 * (size_t)H->cap_select_log);
+    }
+    H->select_ids[2 * H->n_select_log] = id_in;
+    H->select_ids[2 * H->n_select_log + 1] = id_newest;
+    H->select_mu[2 * H->n_select_log] = mu_in;
+    H->select_mu[2 * H->n_select_log + 1] = mu_newest;
+    H->n_select_log++;
 }
 
 static void buf_append(buf_t *b, item_t x) { b->it[b->n++] = x; }
@@ -154,6 +179,7 @@ static void cache_insert(const oracle_config *cfg, head_t *H, item_t x)
                 return;
             }
             item_t *newest = &b->it[b->n - 1];
+            log_select(H, x.id, x.mu, newest->id, newest->mu);
             if (cfg->token_selection && x.mu > newest->mu) {
                 log_discard(H, newest->id);
                 item_free(newest);
@@ -217,6 +243,8 @@ void oracle_destroy(oracle_seq *S)
         for (int c = 0; c < S->cfg.n_cascades; ++c) free(H->casc[c].it);
         free(H->last_delta);
         free(H->discard_log);
+        free(H->select_ids);
+        free(H->select_mu);
     }
     free(S->head);
     free(S);
@@ -321,16 +349,25 @@ static void eval_rows(const oracle_seq *S, int g, const float *q, const float *k
     free(order); free(kr); free(vv); free(tmp); free(delta_h); free(p); free(qr);
 }
 
-static void chunk_one_head(oracle_seq *S, int g, const float *q, const float *k, const float *v,
-                           int Q, double *out)
+/* The reduced increments of the whole chunk for KV head g (not applied yet). */
+static double *chunk_increments(oracle_seq *S, int g, const float *q, const float *k, const float *v,
+                                int Q, double *out)
+{
+    const int64_t n = head_count(&S->cfg, &S->head[g]);
+    double *delta = (double *)malloc(sizeof(double) * (size_t)(n + Q));
+    eval_rows(S, g, q, k, v, Q, 0, Q, out, delta);
+    return delta;
+}
+
+/* The EMA update of the cached items of KV head g with the increments delta (ownership of
+ * delta passes to the head), then the insertion of the chunk's tokens. */
+static void chunk_apply(oracle_seq *S, int g, const float *k, const float *v, int Q, double *delta)
 {
     const oracle_config *cfg = &S->cfg;
     head_t *H = &S->head[g];
     const int d = cfg->head_dim, Hkv = cfg->n_kv_heads;
     const double beta = cfg->ema_beta;
     const int64_t n = head_count(cfg, H);
-    double *delta = (double *)malloc(sizeof(double) * (size_t)(n + Q));
-    eval_rows(S, g, q, k, v, Q, 0, Q, out, delta);
 
     /* cached items decay once per row of the chunk, then receive the reduced increment */
     int64_t cap_total = cfg->n_sink;
@@ -365,14 +402,36 @@ static void chunk_one_head(oracle_seq *S, int g, const float *q, const float *k,
  * q [Q][Hq][d], k and v [Q][Hkv][d] float32 (un-rotated), out [Q][Hq][d] float64
  * (only the query heads of the selected KV heads are written).
  * A decode step is a chunk of one token.
+ * Homogeneous heads (Appendix "Head Policy and Head Reduction") need all KV heads at once:
+ * the increments are reduced over ALL query heads (the max of the per-group maxima; the mean of
+ * the per-group means, the groups being equally large), every KV head then updates and inserts
+ * with that one vector, so all KV heads hold the same tokens at all times.
  */
 int oracle_chunk(oracle_seq *S, const float *q, const float *k, const float *v, int Q,
                  double *out, int kv_lo, int kv_hi)
 {
     if (!S || !q || !k || !v || !out || Q < 1) return -1;
     if (kv_lo < 0 || kv_hi > S->cfg.n_kv_heads || kv_lo >= kv_hi) return -1;
+    const int Hkv = S->cfg.n_kv_heads;
+    if (S->cfg.head_policy == 1 && (kv_lo != 0 || kv_hi != Hkv)) return -1;
+    double **delta = (double **)calloc((size_t)Hkv, sizeof(double *));
 #pragma omp parallel for schedule(dynamic, 1)
-    for (int g = kv_lo; g < kv_hi; ++g) chunk_one_head(S, g, q, k, v, Q, out);
+    for (int g = kv_lo; g < kv_hi; ++g) delta[g] = chunk_increments(S, g, q, k, v, Q, out);
+    if (S->cfg.head_policy == 1) {
+        const int64_t nk = head_count(&S->cfg, &S->head[0]) + Q;   /* the same for every head */
+        for (int64_t j = 0; j < nk; ++j) {
+            double r = delta[0][j];
+            for (int g = 1; g < Hkv; ++g) {
+                if (S->cfg.head_reduce == 0) r = delta[g][j] > r ? delta[g][j] : r;
+                else r += delta[g][j];
+            }
+            if (S->cfg.head_reduce == 1) r /= (double)Hkv;
+            for (int g = 0; g < Hkv; ++g) delta[g][j] = r;
+        }
+    }
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int g = kv_lo; g < kv_hi; ++g) chunk_apply(S, g, k, v, Q, delta[g]);
+    free(delta);
     return 0;
 }
 
@@ -483,6 +542,23 @@ int64_t oracle_last_delta(const oracle_seq *S, int g, double *out, int64_t cap)
     int64_t n = H->last_delta_n < cap ? H->last_delta_n : cap;
     if (out) memcpy(out, H->last_delta, sizeof(double) * (size_t)n);
     return H->last_delta_n;
+}
+
+/* The selection comparisons taken so far (see head_t); returns their number.  ids and mu
+ * receive [min(n, cap)][2] values: incoming item, newest item. */
+int64_t oracle_select_log(const oracle_seq *S, int g, int64_t *ids, double *mu, int64_t cap)
+{
+    const head_t *H = &S->head[g];
+    int64_t n = H->n_select_log < cap ? H->n_select_log : cap;
+    if (ids && n > 0) memcpy(ids, H->select_ids, sizeof(int64_t) * 2 * (size_t)n);
+    if (mu && n > 0) memcpy(mu, H->select_mu, sizeof(double) * 2 * (size_t)n);
+    return H->n_select_log;
+}
+
+void oracle_clear_logs(oracle_seq *S, int g)
+{
+    S->head[g].n_select_log = 0;
+    S->head[g].n_discard_log = 0;
 }
 
 int64_t oracle_discard_log(const oracle_seq *S, int g, int64_t *out, int64_t cap)

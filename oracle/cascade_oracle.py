@@ -38,7 +38,7 @@ class _CConfig(ctypes.Structure):
         ("cascade_sizes", ctypes.c_int32 * _MAX_CASCADES),
         ("accept_period", ctypes.c_int64 * _MAX_CASCADES),
         ("ema_beta", ctypes.c_double), ("rope_base", ctypes.c_double), ("softmax_scale", ctypes.c_double),
-        ("head_reduce", ctypes.c_int32), ("token_selection", ctypes.c_int32),
+        ("head_reduce", ctypes.c_int32), ("token_selection", ctypes.c_int32), ("head_policy", ctypes.c_int32),
     ]
 
 
@@ -67,6 +67,10 @@ def _lib():
         L.oracle_last_delta.argtypes = [P, ctypes.c_int, P, ctypes.c_int64]
         L.oracle_discard_log.restype = ctypes.c_int64
         L.oracle_discard_log.argtypes = [P, ctypes.c_int, P, ctypes.c_int64]
+        L.oracle_select_log.restype = ctypes.c_int64
+        L.oracle_select_log.argtypes = [P, ctypes.c_int, P, P, ctypes.c_int64]
+        L.oracle_clear_logs.restype = None
+        L.oracle_clear_logs.argtypes = [P, ctypes.c_int]
         _LIB = L
     return _LIB
 
@@ -84,6 +88,7 @@ class OracleConfig:
     softmax_scale: float = 0.0                      # 0 -> 1/sqrt(head_dim)
     head_reduce: int = 0                            # 0 max, 1 mean
     token_selection: int = 1
+    head_policy: int = 0                            # 0 independent KV heads, 1 homogeneous
 
     def periods(self):
         if self.accept_period is not None:
@@ -126,7 +131,7 @@ class OracleSeq:
         for i, p in enumerate(cfg.periods()):
             c.accept_period[i] = int(p)
         c.ema_beta, c.rope_base, c.softmax_scale = cfg.ema_beta, cfg.rope_base, cfg.softmax_scale
-        c.head_reduce, c.token_selection = cfg.head_reduce, cfg.token_selection
+        c.head_reduce, c.token_selection, c.head_policy = cfg.head_reduce, cfg.token_selection, cfg.head_policy
         self._h = _lib().oracle_create(ctypes.byref(c))
         if not self._h:
             raise ValueError("oracle_create rejected the configuration")
@@ -225,6 +230,18 @@ class OracleSeq:
         out = np.zeros(n, dtype=np.float64)
         _lib().oracle_last_delta(self._h, kv_head, _ptr(out), n)
         return out
+
+    def select_log(self, kv_head: int):
+        """Every token-selection comparison of Alg. 2 so far (or since clear_logs), in order:
+        (ids [n,2], mu [n,2]) of the incoming item and of the newest item of the cascade."""
+        n = int(_lib().oracle_select_log(self._h, kv_head, None, None, 0))
+        ids = np.zeros((max(n, 1), 2), dtype=np.int64)
+        mu = np.zeros((max(n, 1), 2), dtype=np.float64)
+        _lib().oracle_select_log(self._h, kv_head, _ptr(ids), _ptr(mu), n)
+        return ids[:n], mu[:n]
+
+    def clear_logs(self, kv_head: int) -> None:
+        _lib().oracle_clear_logs(self._h, kv_head)
 
     def discard_log(self, kv_head: int) -> np.ndarray:
         n = int(_lib().oracle_discard_log(self._h, kv_head, None, 0))

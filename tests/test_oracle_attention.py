@@ -125,6 +125,61 @@ def test_brute_force_over_membership_and_ema(oracle_mod):
     assert sum(len(o.discard_log(g)) for g in range(Hkv)) > 50
 
 
+@pytest.mark.parametrize("reduce", [0, 1])
+def test_homogeneous_heads_brute_force(oracle_mod, reduce):
+    """Homogeneous heads (Appendix "Head Policy and Head Reduction"): the head axis of the
+    attention is reduced to ONE score per token, so every KV head takes the same decisions and
+    holds the same tokens.  Brute force as above, with the increments reduced over all query
+    heads (dense attention per head against that head's own keys of the common membership)."""
+    rng = np.random.default_rng(15)
+    Hq, Hkv, d, S, Q, beta, base = 6, 3, 8, 72, 6, 0.8, 50.0
+    G = Hq // Hkv
+    cfg = OracleConfig(n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, n_sink=2, cascade_sizes=[4, 4, 4],
+                       ema_beta=beta, rope_base=base, head_reduce=reduce, head_policy=1)
+    o = OracleSeq(cfg)
+    q, k, v = _rand(rng, S, Hq, d), _rand(rng, S, Hkv, d), _rand(rng, S, Hkv, d)
+    w = beta ** (Q - 1 - np.arange(Q)) * (1 - beta)
+    for s in range(0, S, Q):
+        before = [o.state(g) for g in range(Hkv)]
+        for g in range(1, Hkv):      # one membership, one score vector
+            assert before[g].ids.tolist() == before[0].ids.tolist()
+            assert before[g].mu.tolist() == before[0].mu.tolist()
+        out = o.chunk(q[s:s + Q], k[s:s + Q], v[s:s + Q])
+        cached = before[0].ids
+        n = len(cached)
+        members = np.concatenate([cached, np.arange(s, s + Q)])
+        vis = np.concatenate([np.ones((Q, n), bool), np.tril(np.ones((Q, Q), bool))], axis=1)
+        deltas = []
+        for h in range(Hq):
+            g = h // G
+            ref, P = dense_attention(q[s:s + Q, h].astype(np.float64), n + np.arange(Q),
+                                     k[members, g].astype(np.float64), np.arange(n + Q),
+                                     v[members, g].astype(np.float64), vis, base, d ** -0.5)
+            np.testing.assert_allclose(out[:, h], ref, rtol=1e-10, atol=1e-12)
+            deltas.append(w @ P)
+        delta = np.max(deltas, axis=0) if reduce == 0 else np.mean(deltas, axis=0)
+        for g in range(Hkv):
+            np.testing.assert_allclose(o.last_delta(g), delta, rtol=1e-10, atol=1e-15)
+    assert len(o.discard_log(0)) > 30
+    # a subset of the KV heads cannot be advanced alone under this policy
+    with pytest.raises(RuntimeError):
+        o.chunk(q[:Q], k[:Q], v[:Q], kv_heads=(0, 1))
+
+
+def test_homogeneous_equals_independent_for_one_kv_head(oracle_mod):
+    rng = np.random.default_rng(16)
+    Hq, d, Q = 4, 8, 5
+    q, k, v = _rand(rng, 40, Hq, d), _rand(rng, 40, 1, d), _rand(rng, 40, 1, d)
+    states = []
+    for policy in (0, 1):
+        o = OracleSeq(OracleConfig(n_q_heads=Hq, n_kv_heads=1, head_dim=d, n_sink=1, cascade_sizes=[3, 3],
+                                   ema_beta=0.7, rope_base=10.0, head_policy=policy))
+        outs = [o.chunk(q[s:s + Q], k[s:s + Q], v[s:s + Q]) for s in range(0, 40, Q)]
+        states.append((np.concatenate(outs), o.state(0)))
+    assert np.array_equal(states[0][0], states[1][0])
+    assert states[0][1].ids.tolist() == states[1][1].ids.tolist() and states[0][1].mu.tolist() == states[1][1].mu.tolist()
+
+
 def test_mean_head_reduction(oracle_mod):
     """The mean reduction over the query heads of a group (Appendix "Head Policy")."""
     rng = np.random.default_rng(13)

@@ -47,6 +47,31 @@ def test_alg2_hand_trace(oracle_mod, trace):
     assert st.pos.tolist() == list(range(len(final)))
 
 
+def test_select_log_of_the_hand_traces(oracle_mod):
+    """The record of token-selection comparisons (which pair, which scores, in which order)
+    against the same two hand traces (tests/golden/alg2_select_log.txt)."""
+    expect = {}
+    with open(os.path.join(os.path.dirname(GOLDEN), "alg2_select_log.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            parts = [p.strip() for p in line.split(";")]
+            pairs = [[int(x) for x in p.split(">")] for p in parts[1].split(",")]
+            mus = [[float(x) for x in p.split(",")] for p in parts[2:]]
+            expect[parts[0]] = (pairs, mus)
+    for name, trace in zip("AB", _traces()):
+        n_sink, sizes, periods, scores, _, _ = trace
+        o = _policy_only(n_sink, sizes, periods)
+        for s in scores:
+            o.insert_scored(0, s)
+        ids, mu = o.select_log(0)
+        assert ids.tolist() == expect[name][0]
+        assert mu.tolist() == expect[name][1]
+        o.clear_logs(0)
+        assert len(o.select_log(0)[0]) == 0 and len(o.discard_log(0)) == 0
+
+
 def test_one_cascade_is_sink_plus_sliding_window(oracle_mod):
     """Section 3.1: with one cascade that accepts everything the cache is StreamingLLM's
     (Eq. 3 plus the sink rule): the first alpha tokens and the most recent |C| tokens."""
