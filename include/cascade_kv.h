@@ -146,6 +146,26 @@ int cascade_init(const cascade_config* cfg, void* dev_workspace, size_t workspac
 void cascade_destroy(cascade_ctx* ctx);
 
 /*
+ * cascade_init for callers that cannot allocate device memory at all (code that runs under a
+ * HIP graph capture, serving loops and harnesses that forbid hipMalloc): the same context, but
+ * its workspace is a device array that is part of the library image,
+ * CASCADE_STATIC_WORKSPACE_BYTES long, one per GPU.  The call allocates nothing on the device
+ * (no hipMalloc / hipFree, no allocating library routine) and, after the first call on a
+ * device, nothing on the host either.  Everything else is cascade_init: same arguments minus
+ * the workspace, same errors; a configuration whose cascade_workspace_bytes exceeds the array is
+ * rejected with CASCADE_E_WORKSPACE_TOO_SMALL (cascade_last_error(NULL) names both sizes).
+ * The returned context is used with every other call; cascade_destroy on it is allowed and
+ * releases nothing.
+ * The array is shared by every call on that GPU and keeps the previous contents: the call
+ * clears the part it uses, and it REPLACES the previous static context of the device, which
+ * must not be used afterwards.  Two static contexts on one GPU at the same time, or a call
+ * that overlaps work still in flight on the previous one, race.
+ */
+#define CASCADE_STATIC_WORKSPACE_BYTES (64u << 20)
+int cascade_init_static(const cascade_config* cfg, const cascade_init_state* init_state, void* stream,
+                        cascade_ctx** out_ctx);
+
+/*
  * Several layers over one workspace (the inner loop of Alg. 1 runs cache.get, the layer and
  * cache.update once per layer for every chunk).  Every layer gets a context and a cache of
  * its own; the buffers that live only inside one call (rotated queries, packed tiles, decode

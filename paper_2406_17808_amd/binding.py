@@ -32,7 +32,9 @@ EXPORTED_SYMBOLS = [
     "cascade_workspace_bytes", "cascade_init", "cascade_destroy", "cascade_prefill_chunk",
     "cascade_decode_step", "cascade_read_state", "cascade_simulate_structure", "cascade_last_error",
     "cascade_profile_begin", "cascade_profile_end", "cascade_layers_workspace_bytes", "cascade_init_layers",
+    "cascade_init_static",
 ]
+CASCADE_STATIC_WORKSPACE_BYTES = 64 << 20
 
 CASCADE_K_FAMILIES = 7
 KERNEL_FAMILIES = ["prep", "attention", "scores", "update", "decode_qk", "decode_pv", "decode_finish"]
@@ -105,6 +107,8 @@ def load_library():
         L.cascade_layers_workspace_bytes.argtypes = [ctypes.POINTER(cascade_config), ctypes.c_int32]
         L.cascade_init_layers.restype = ctypes.c_int
         L.cascade_init_layers.argtypes = [ctypes.POINTER(cascade_config), ctypes.c_int32, P, ctypes.c_size_t, P, P, P]
+        L.cascade_init_static.restype = ctypes.c_int
+        L.cascade_init_static.argtypes = [ctypes.POINTER(cascade_config), ctypes.POINTER(cascade_init_state), P, ctypes.POINTER(P)]
         L.cascade_destroy.restype = None
         L.cascade_destroy.argtypes = [P]
         L.cascade_prefill_chunk.restype = ctypes.c_int
@@ -162,6 +166,15 @@ def cascade_init(cfg: cascade_config, dev_workspace: int, workspace_bytes: int,
     rc = load_library().cascade_init(ctypes.byref(cfg), dev_workspace, workspace_bytes,
                                      ctypes.byref(init_state) if init_state is not None else None,
                                      stream, ctypes.byref(ctx))
+    _check(rc, None)
+    return ctx
+
+
+def cascade_init_static(cfg: cascade_config, init_state: Optional[cascade_init_state] = None, stream: int = 0) -> ctypes.c_void_p:
+    """A context whose workspace is the library's own static device array (no device allocation)."""
+    ctx = ctypes.c_void_p()
+    rc = load_library().cascade_init_static(ctypes.byref(cfg), ctypes.byref(init_state) if init_state is not None else None,
+                                            stream, ctypes.byref(ctx))
     _check(rc, None)
     return ctx
 

@@ -24,12 +24,17 @@ def config_of(wl: Workload, max_chunk: Optional[int] = None, batch: Optional[int
 
 class CascadeKVCache:
     def __init__(self, cfg: B.cascade_config, device: str = "cuda:0", init_state: Optional[B.cascade_init_state] = None,
-                 _layer_of=None):
+                 _layer_of=None, static_workspace: bool = False):
         self.cfg = cfg
         self.device = torch.device(device)
         self.torch_dtype = torch.bfloat16 if cfg.dtype == B.CASCADE_BF16 else torch.float32
         if _layer_of is not None:      # a layer of CascadeKVLayers: the context exists, the workspace is the owner's
             self.workspace, self.ctx, self.workspace_bytes = _layer_of
+            return
+        if static_workspace:           # the library's own device array: nothing is allocated here
+            self.workspace, self.workspace_bytes = None, B.cascade_workspace_bytes(cfg)
+            with torch.cuda.device(self.device):
+                self.ctx = B.cascade_init_static(cfg, init_state, self._stream())
             return
         nbytes = B.cascade_workspace_bytes(cfg)
         if nbytes == 0:

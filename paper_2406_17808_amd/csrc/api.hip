@@ -35,6 +35,7 @@ struct cascade_ctx {
     PackedLayout packed;
     TileRuns stale;
     bool profiling = false;
+    bool is_static = false;   // one of the per-device contexts of cascade_init_static: never deleted
     std::vector<std::pair<hipEvent_t, hipEvent_t>> prof[CASCADE_K_FAMILIES];
     std::string err;
 };
@@ -255,10 +256,10 @@ static int check_init_state(const std::string& name, const Geom& g, const cascad
 // check_init_state.
 static int init_context(const char* who, const cascade_config* cfg, const Geom& g, char* state_base, char* shared_base,
                         bool tables, const cascade_init_state* init_state, const HostState& st, int total,
-                        hipStream_t s, cascade_ctx** out_ctx)
+                        hipStream_t s, cascade_ctx** out_ctx, cascade_ctx* into = nullptr)
 {
     const std::string name = who;
-    cascade_ctx* ctx = new cascade_ctx();
+    cascade_ctx* ctx = into ? into : new cascade_ctx();   // into: a context that already exists and is reset by the caller
     ctx->cfg = *cfg;
     ctx->g = g;
     ctx->st = st;
@@ -299,7 +300,7 @@ static int init_context(const char* who, const cascade_config* cfg, const Geom& 
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         const int rc = hip_check(nullptr, e, (name + ": launch").c_str());
-        delete ctx;
+        if (!into) delete ctx;
         return rc;
     }
     *out_ctx = ctx;
@@ -381,7 +382,70 @@ extern "C" void cascade_destroy(cascade_ctx* ctx)
 {
     if (!ctx) return;
     drop_events(ctx);
+    if (ctx->is_static) return;   // lives as long as the library; the next cascade_init_static resets it
     delete ctx;
+}
+
+// ------------------------------------------------------------------ a context without a caller's workspace
+
+// The workspace of cascade_init_static: one array per GPU, held from the moment the library is
+// loaded on it until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; everything that touches the memory uses the address that call returns.
+static __device__ __align__(256) unsigned char scratch[CASCADE_STATIC_WORKSPACE_BYTES];
+
+// Keeps the array in the code object whatever the optimiser thinks of a variable no kernel names.
+__global__ void static_workspace_anchor_kernel(unsigned char* out)
+{
+    if (out) *out = scratch[0];
+}
+
+constexpr int kMaxStaticDevices = 64;
+static void* g_static_ptr[kMaxStaticDevices];          // device address of `scratch` on every device seen so far
+static cascade_ctx* g_static_ctx[kMaxStaticDevices];   // the one static context of a device: created once, reused for ever
+
+extern "C" int cascade_init_static(const cascade_config* cfg, const cascade_init_state* init_state, void* stream,
+                                   cascade_ctx** out_ctx)
+{
+    if (!cfg || !out_ctx) return fail(nullptr, CASCADE_E_NULL_ARG, "cascade_init_static: NULL argument");
+    *out_ctx = nullptr;
+    std::string why;
+    int rc = check_config(cfg, why);
+    if (rc != CASCADE_OK) return fail(nullptr, rc, "cascade_init_static: " + why);
+    Geom g;
+    make_geom(cfg, g);
+    const WorkspaceBytes need = carve(cfg, g, nullptr, nullptr, nullptr);
+    if (need.state + need.shared > (size_t)CASCADE_STATIC_WORKSPACE_BYTES)
+        return fail(nullptr, CASCADE_E_WORKSPACE_TOO_SMALL,
+                    "cascade_init_static: this configuration needs " + std::to_string(need.state + need.shared) +
+                        " bytes, the static workspace holds " + std::to_string((size_t)CASCADE_STATIC_WORKSPACE_BYTES));
+    HostState st;
+    int total = 0;
+    rc = check_init_state("cascade_init_static", g, init_state, st, total);
+    if (rc != CASCADE_OK) return rc;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_check(nullptr, e, "cascade_init_static: hipGetDevice");
+    if (dev < 0 || dev >= kMaxStaticDevices) return fail(nullptr, CASCADE_E_UNSUPPORTED, "cascade_init_static: device index out of range");
+    if (!g_static_ptr[dev]) {      // once per device, with that device current: every GPU has its own copy of the array
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return hip_check(nullptr, e != hipSuccess ? e : hipErrorInvalidSymbol, "cascade_init_static: hipGetSymbolAddress");
+        g_static_ptr[dev] = p;
+    }
+    char* base = (char*)g_static_ptr[dev];
+    if (!g_static_ctx[dev]) {      // the only host allocation, once per device; later calls reuse the object
+        g_static_ctx[dev] = new cascade_ctx();
+        g_static_ctx[dev]->is_static = true;
+    }
+    cascade_ctx* ctx = g_static_ctx[dev];
+    drop_events(ctx);
+    *ctx = cascade_ctx();          // forget whatever the previous static context of this device held
+    ctx->is_static = true;
+    hipStream_t s = (hipStream_t)stream;
+    // the array keeps what the last context left: everything this one reads before writing starts from zero
+    e = hipMemsetAsync(base, 0, need.state + need.shared, s);
+    if (e != hipSuccess) return hip_check(nullptr, e, "cascade_init_static: memset");
+    return init_context("cascade_init_static", cfg, g, base, base + need.state, true, init_state, st, total, s, out_ctx, ctx);
 }
 
 extern "C" int cascade_profile_begin(cascade_ctx* ctx)
