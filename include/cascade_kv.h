@@ -110,6 +110,9 @@ typedef struct cascade_state_view {
     int32_t* host_slot;       /* [batch, n_kv_heads, slots] physical slot that holds entry r */
     float* host_k;            /* [batch, n_kv_heads, slots, head_dim] un-rotated keys as float */
     float* host_v;            /* [batch, n_kv_heads, slots, head_dim] */
+    const int32_t* host_kv_pairs; /* NULL, or n_kv_pairs indices (sequence * n_kv_heads + KV head): host_k and
+                                 host_v are then [n_kv_pairs, slots, head_dim] and hold only those pairs,
+                                 in this order (a full copy of a large batch is tens of gigabytes) */
     int64_t* host_swaps;      /* [batch, n_kv_heads, n_cascades] selections won by the incoming token */
     float* host_pre_mu;       /* [batch, n_kv_heads, slots] needs keep_update_scores: scores of the items
                                  cached BEFORE the last prefill / decode call, after that call's EMA
@@ -126,6 +129,7 @@ typedef struct cascade_state_view {
     int64_t n_seen;
     int32_t pre_count;        /* items cached before the last call */
     int32_t last_tokens;      /* tokens of the last call (0 before any call) */
+    int32_t n_kv_pairs;       /* input: entries of host_kv_pairs */
 } cascade_state_view;
 
 /* Device bytes cascade_init needs for this configuration; 0 if the configuration is invalid. */

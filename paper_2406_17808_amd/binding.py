@@ -71,14 +71,16 @@ class cascade_init_state(ctypes.Structure):
 class cascade_state_view(ctypes.Structure):
     _fields_ = [
         ("host_ids", ctypes.c_void_p), ("host_mu", ctypes.c_void_p), ("host_slot", ctypes.c_void_p),
-        ("host_k", ctypes.c_void_p), ("host_v", ctypes.c_void_p), ("host_swaps", ctypes.c_void_p),
+        ("host_k", ctypes.c_void_p), ("host_v", ctypes.c_void_p),
+        ("host_kv_pairs", ctypes.c_void_p),
+        ("host_swaps", ctypes.c_void_p),
         ("host_pre_mu", ctypes.c_void_p), ("host_chunk_mu", ctypes.c_void_p),
         ("counts", ctypes.c_int32 * (1 + CASCADE_MAX_CASCADES)),
         ("xi", ctypes.c_int32 * CASCADE_MAX_CASCADES),
         ("accepted", ctypes.c_int64 * CASCADE_MAX_CASCADES),
         ("discards", ctypes.c_int64 * CASCADE_MAX_CASCADES),
         ("t", ctypes.c_int64), ("n_seen", ctypes.c_int64),
-        ("pre_count", ctypes.c_int32), ("last_tokens", ctypes.c_int32),
+        ("pre_count", ctypes.c_int32), ("last_tokens", ctypes.c_int32), ("n_kv_pairs", ctypes.c_int32),
     ]
 
 
@@ -238,16 +240,36 @@ class StateArrays:
         self.pre_mu = self.chunk_mu = None
 
 
-def cascade_read_state(ctx, cfg: cascade_config, with_kv: bool = False, stream: int = 0) -> StateArrays:
+class PairRows:
+    """K or V rows of selected (sequence, KV head) pairs, indexed like the full [B, Hkv, slots, d] array."""
+
+    def __init__(self, pairs, rows: np.ndarray):
+        self.index = {tuple(p): i for i, p in enumerate(pairs)}
+        self.rows = rows
+
+    def __getitem__(self, key):
+        b, g = key[0], key[1]
+        return self.rows[(self.index[(int(b), int(g))],) + tuple(key[2:])]
+
+
+def cascade_read_state(ctx, cfg: cascade_config, with_kv: bool = False, stream: int = 0, kv_pairs=None) -> StateArrays:
+    """kv_pairs: with_kv for these (sequence, KV head) pairs only (k and v are then PairRows)."""
     B, H, N, d = cfg.batch, cfg.n_kv_heads, cfg.n_cascades, cfg.head_dim
     slots = cfg.n_sink + sum(cfg.cascade_sizes[i] for i in range(N))
     ids = np.empty((B, H, slots), dtype=np.int32)
     mu = np.empty((B, H, slots), dtype=np.float32)
     slot = np.empty((B, H, slots), dtype=np.int32)
     swaps = np.empty((B, H, N), dtype=np.int64)
-    k = np.empty((B, H, slots, d), dtype=np.float32) if with_kv else None
-    v = np.empty((B, H, slots, d), dtype=np.float32) if with_kv else None
     view = cascade_state_view()
+    pair_idx = None
+    if with_kv and kv_pairs is not None:
+        pair_idx = np.ascontiguousarray([b * H + g for b, g in kv_pairs], dtype=np.int32)
+        view.host_kv_pairs, view.n_kv_pairs = pair_idx.ctypes.data, len(pair_idx)
+        k = np.empty((len(pair_idx), slots, d), dtype=np.float32)
+        v = np.empty((len(pair_idx), slots, d), dtype=np.float32)
+    else:
+        k = np.empty((B, H, slots, d), dtype=np.float32) if with_kv else None
+        v = np.empty((B, H, slots, d), dtype=np.float32) if with_kv else None
     view.host_ids, view.host_mu, view.host_slot = ids.ctypes.data, mu.ctypes.data, slot.ctypes.data
     view.host_swaps = swaps.ctypes.data
     view.host_k = k.ctypes.data if with_kv else None
@@ -258,6 +280,8 @@ def cascade_read_state(ctx, cfg: cascade_config, with_kv: bool = False, stream: 
         chunk_mu = np.zeros((B, H, cfg.max_chunk), dtype=np.float32)
         view.host_pre_mu, view.host_chunk_mu = pre_mu.ctypes.data, chunk_mu.ctypes.data
     _check(load_library().cascade_read_state(ctx, ctypes.byref(view), stream), ctx)
+    if pair_idx is not None:
+        k, v = PairRows(kv_pairs, k), PairRows(kv_pairs, v)
     out = StateArrays(view, N, ids, mu, slot, k, v, swaps)
     out.pre_mu, out.chunk_mu = pre_mu, chunk_mu
     return out

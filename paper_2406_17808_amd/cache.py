@@ -88,8 +88,8 @@ class CascadeKVCache:
         B.cascade_decode_step(self.ctx, q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), self._stream())
         return out
 
-    def read_state(self, with_kv: bool = False) -> B.StateArrays:
-        return B.cascade_read_state(self.ctx, self.cfg, with_kv, self._stream())
+    def read_state(self, with_kv: bool = False, kv_pairs=None) -> B.StateArrays:
+        return B.cascade_read_state(self.ctx, self.cfg, with_kv, self._stream(), kv_pairs)
 
 
 class CascadeKVLayers:

@@ -57,73 +57,14 @@ struct Timed {
     ~Timed() { if (stop) (void)hipEventRecord(stop, s); }
 };
 
-static thread_local std::string g_init_error;
-
 static int fail(cascade_ctx* ctx, int code, const std::string& msg)
 {
     if (ctx) ctx->err = msg;
-    else g_init_error = msg;
+    else set_init_error(msg);
     return code;
 }
 
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
-
-// ------------------------------------------------------------------ configuration
-
-static int check_config(const cascade_config* c, std::string& why)
-{
-    if (c->batch < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1) { why = "batch and head counts must be positive"; return CASCADE_E_INVALID_CONFIG; }
-    if (c->n_q_heads % c->n_kv_heads) { why = "n_q_heads must be a multiple of n_kv_heads"; return CASCADE_E_INVALID_CONFIG; }
-    if (c->dtype != CASCADE_F32 && c->dtype != CASCADE_BF16) { why = "dtype must be CASCADE_F32 or CASCADE_BF16"; return CASCADE_E_INVALID_CONFIG; }
-    if (c->head_dim < 2 || c->head_dim % 2) { why = "head_dim must be even"; return CASCADE_E_INVALID_CONFIG; }
-    if (c->n_sink < 0) { why = "n_sink must not be negative"; return CASCADE_E_INVALID_CONFIG; }
-    if (c->n_cascades < 1 || c->n_cascades > CASCADE_MAX_CASCADES) { why = "n_cascades out of range"; return CASCADE_E_INVALID_CONFIG; }
-    bool all_zero = true;
-    for (int i = 0; i < c->n_cascades; ++i) {
-        if (c->cascade_sizes[i] < 1) { why = "every cascade needs at least one slot"; return CASCADE_E_INVALID_CONFIG; }
-        if (c->accept_period[i] < 0) { why = "accept_period must not be negative"; return CASCADE_E_INVALID_CONFIG; }
-        if (c->accept_period[i] != 0) all_zero = false;
-    }
-    if (!all_zero) {
-        if (c->accept_period[0] != 1) { why = "the first cascade must accept every token (accept_period[0] == 1)"; return CASCADE_E_INVALID_CONFIG; }
-        for (int i = 0; i < c->n_cascades; ++i)
-            if (c->accept_period[i] < 1) { why = "accept_period entries must be >= 1"; return CASCADE_E_INVALID_CONFIG; }
-    }
-    if (!(c->ema_beta >= 0.f && c->ema_beta < 1.f)) { why = "ema_beta must be in [0, 1)"; return CASCADE_E_INVALID_CONFIG; }
-    if (!(c->rope_base > 0.f)) { why = "rope_base must be positive"; return CASCADE_E_INVALID_CONFIG; }
-    if (c->softmax_scale < 0.f) { why = "softmax_scale must not be negative"; return CASCADE_E_INVALID_CONFIG; }
-    if (c->max_chunk < 1) { why = "max_chunk must be >= 1"; return CASCADE_E_INVALID_CONFIG; }
-    if (c->head_reduce != CASCADE_REDUCE_MAX && c->head_reduce != CASCADE_REDUCE_MEAN) { why = "unknown head_reduce"; return CASCADE_E_INVALID_CONFIG; }
-    if (c->token_selection != 0 && c->token_selection != 1) { why = "token_selection must be 0 or 1"; return CASCADE_E_INVALID_CONFIG; }
-    long slots = c->n_sink;
-    for (int i = 0; i < c->n_cascades; ++i) slots += c->cascade_sizes[i];
-    if (slots > (1L << 28)) { why = "cache too large"; return CASCADE_E_INVALID_CONFIG; }
-    if (c->dtype == CASCADE_BF16 && c->head_dim != 64 && c->head_dim != 128) { why = "bf16 kernels cover head_dim 64 and 128"; return CASCADE_E_UNSUPPORTED; }
-    if (c->dtype == CASCADE_F32 && c->head_dim > 256) { why = "fp32 kernels cover head_dim up to 256"; return CASCADE_E_UNSUPPORTED; }
-    return CASCADE_OK;
-}
-
-static void make_geom(const cascade_config* c, Geom& g)
-{
-    memset(&g, 0, sizeof(g));
-    g.B = c->batch; g.Hq = c->n_q_heads; g.Hkv = c->n_kv_heads; g.G = g.Hq / g.Hkv; g.d = c->head_dim;
-    g.n_sink = c->n_sink; g.N = c->n_cascades;
-    bool all_zero = true;
-    for (int i = 0; i < g.N; ++i) if (c->accept_period[i] != 0) all_zero = false;
-    int slots = g.n_sink;
-    for (int i = 0; i < g.N; ++i) {
-        g.cap[i] = c->cascade_sizes[i];
-        g.period[i] = all_zero ? (1 << i) : c->accept_period[i];
-        slots += g.cap[i];
-    }
-    g.slots = slots;
-    int base = g.n_sink;                       // physical order: sinks, last cascade, ..., first cascade
-    for (int i = g.N - 1; i >= 0; --i) { g.base[i] = base; base += g.cap[i]; }
-    g.token_selection = c->token_selection;
-    g.head_reduce = c->head_reduce;
-    g.beta = c->ema_beta;
-    g.scale = c->softmax_scale > 0.f ? c->softmax_scale : (float)(1.0 / sqrt((double)g.d));
-}
 
 static int decode_splits(const Geom& g)
 {
@@ -476,7 +417,7 @@ extern "C" int cascade_profile_end(cascade_ctx* ctx, cascade_profile* out)
     return CASCADE_OK;
 }
 
-extern "C" const char* cascade_last_error(const cascade_ctx* ctx) { return ctx ? ctx->err.c_str() : g_init_error.c_str(); }
+extern "C" const char* cascade_last_error(const cascade_ctx* ctx) { return ctx ? ctx->err.c_str() : init_error(); }
 
 // Diagnostics: keep the scores the coming insertion decisions are taken with.
 static int snapshot_scores(cascade_ctx* ctx, int n_tokens, hipStream_t s)
@@ -672,17 +613,23 @@ extern "C" int cascade_read_state(cascade_ctx* ctx, cascade_state_view* view, vo
         if (rc) return rc;
         for (size_t i = 0; i < sw.size(); ++i) view->host_swaps[i] = sw[i];
     }
+    const size_t n_pairs = view->host_kv_pairs ? (size_t)(view->n_kv_pairs > 0 ? view->n_kv_pairs : 0) : BH;
+    if (view->host_kv_pairs && (view->host_k || view->host_v))
+        for (size_t i = 0; i < n_pairs; ++i)
+            if (view->host_kv_pairs[i] < 0 || (size_t)view->host_kv_pairs[i] >= BH)
+                return fail(ctx, CASCADE_E_BAD_ARG, "cascade_read_state: host_kv_pairs names a pair that does not exist");
     for (int which = 0; which < 2; ++which) {
         float* dst = which == 0 ? view->host_k : view->host_v;
         if (!dst) continue;
         const void* src = which == 0 ? ctx->buf.Kc : ctx->buf.Vc;
         std::vector<char> raw((size_t)g.slots * g.d * ctx->elem);
-        for (size_t bh = 0; bh < BH; ++bh) {
+        for (size_t pi = 0; pi < n_pairs; ++pi) {
+            const size_t bh = view->host_kv_pairs ? (size_t)view->host_kv_pairs[pi] : pi;
             rc = hip_check(ctx, hipMemcpy(raw.data(), (const char*)src + bh * raw.size(), raw.size(), hipMemcpyDeviceToHost),
                            "cascade_read_state: copy rows");
             if (rc) return rc;
             for (int r = 0; r < g.slots; ++r) {
-                float* o = dst + (bh * g.slots + r) * g.d;
+                float* o = dst + (pi * g.slots + r) * g.d;
                 if (r >= n) { memset(o, 0, sizeof(float) * g.d); continue; }
                 if (ctx->dtype == CASCADE_BF16) {
                     const bf16_t* p = (const bf16_t*)raw.data() + (size_t)slot[r] * g.d;
@@ -693,94 +640,5 @@ extern "C" int cascade_read_state(cascade_ctx* ctx, cascade_state_view* view, vo
             }
         }
     }
-    return CASCADE_OK;
-}
-
-// ------------------------------------------------------------------ host-only utility
-
-// Fill, ring heads and counters after feeding chunks of the given sizes to an empty cache; with
-// scores also the membership.  Pure host arithmetic (no device is touched).  The membership is
-// computed by the same segment / eviction routines the device kernels run (plan_core.h), one
-// "thread" at a time.
-extern "C" int cascade_simulate_structure(const cascade_config* cfg, const int32_t* chunk_sizes, int32_t n_chunks,
-                                          const float* host_scores, cascade_state_view* view)
-{
-    if (!cfg || !view || (!chunk_sizes && n_chunks > 0)) return fail(nullptr, CASCADE_E_NULL_ARG, "cascade_simulate_structure: NULL argument");
-    std::string why;
-    int rc = check_config(cfg, why);
-    if (rc != CASCADE_OK) return fail(nullptr, rc, "cascade_simulate_structure: " + why);
-    Geom g;
-    make_geom(cfg, g);
-    HostState st;
-    std::vector<float> mu;
-    std::vector<int32_t> ids;
-    std::vector<int64_t> swaps(g.N, 0);
-    if (host_scores) { mu.assign(g.slots, 0.f); ids.assign(g.slots, -1); }
-    size_t consumed = 0;
-    for (int ci = 0; ci < n_chunks; ++ci) {
-        const int Q = chunk_sizes[ci];
-        if (Q < 1) return fail(nullptr, CASCADE_E_BAD_ARG, "cascade_simulate_structure: chunk sizes must be >= 1");
-        UpdatePlan pl;
-        plan_update(g, st, Q, pl);
-        if (!host_scores) continue;
-        const float* muc = host_scores + consumed;
-        consumed += Q;
-        int run_lo[kMaxTileRuns], run_hi[kMaxTileRuns];
-        const int n_runs = touched_slot_runs(g, pl, run_lo, run_hi);   // every write below must fall inside these
-        std::vector<int32_t> off_a(Q + 1), off_b(Q + 1);
-        std::vector<std::vector<int32_t>> W(g.N, std::vector<int32_t>(Q + 2, -1));
-        int32_t *off_in = off_a.data(), *off_out = off_b.data();
-        for (int c = 0; c < g.N; ++c) {
-            const CascStep& cs = pl.c[c];
-            if (cs.M == 0) break;
-            for (int sidx = 0; sidx < cs.J + cs.pre; ++sidx) {
-                const int j = sidx - cs.pre;
-                int sw;
-                W[c][1 + j] = segment_winner(cs, c, j, g.slots, pl.n_to_sink, g.token_selection, off_in,
-                                             mu.data(), muc, &sw);
-                swaps[c] += sw;
-            }
-            for (int i = 0; i < cs.P; ++i) off_out[i] = evicted_ref(cs, i, W[c].data());
-            std::swap(off_in, off_out);
-        }
-        for (int c = g.N - 1; c >= -1; --c) {      // the last cascade first: sources are still intact
-            int E, extra = 0;
-            if (c < 0) E = pl.n_to_sink;
-            else { if (pl.c[c].M == 0) continue; E = final_entries(pl.c[c], &extra); }
-            for (int e = 0; e < E + extra; ++e) {
-                int dst, ref;
-                if (c < 0) { dst = pl.sink_fill0 + e; ref = g.slots + e; }
-                else if (!final_entry(pl.c[c], e, E, W[c].data(), &dst, &ref)) continue;
-                bool predicted = false;
-                for (int r = 0; r < n_runs; ++r) predicted = predicted || (dst >= run_lo[r] && dst < run_hi[r]);
-                if (!predicted) return fail(nullptr, CASCADE_E_INTERNAL, "cascade_simulate_structure: a slot was written outside the predicted runs");
-                if (ref < g.slots) { mu[dst] = mu[ref]; ids[dst] = ids[ref]; }
-                else { mu[dst] = muc[ref - g.slots]; ids[dst] = pl.id0 + (ref - g.slots); }
-            }
-        }
-    }
-    memset(view->counts, 0, sizeof(view->counts));
-    memset(view->xi, 0, sizeof(view->xi));
-    memset(view->accepted, 0, sizeof(view->accepted));
-    memset(view->discards, 0, sizeof(view->discards));
-    view->counts[0] = st.sink_fill;
-    for (int c = 0; c < g.N; ++c) {
-        view->counts[1 + c] = st.count[c];
-        view->xi[c] = st.xi[c];
-        view->accepted[c] = st.accepted[c];
-        view->discards[c] = st.discards[c];
-    }
-    view->t = st.t;
-    view->n_seen = st.n_seen;
-    view->pre_count = 0;
-    view->last_tokens = 0;
-    const int n = st.n_cached(g);
-    for (int r = 0; r < g.slots; ++r) {
-        const int sl = r < n ? slot_of_rank(g, st, r) : -1;
-        if (view->host_slot) view->host_slot[r] = sl;
-        if (host_scores && view->host_ids) view->host_ids[r] = sl >= 0 ? ids[sl] : -1;
-        if (host_scores && view->host_mu) view->host_mu[r] = sl >= 0 ? mu[sl] : 0.f;
-    }
-    if (host_scores && view->host_swaps) for (int c = 0; c < g.N; ++c) view->host_swaps[c] = swaps[c];
     return CASCADE_OK;
 }

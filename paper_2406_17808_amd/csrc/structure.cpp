@@ -1,9 +1,74 @@
 // Host-side structure of the cascade update and of the attention segments.
 #include "structure.h"
 
+#include <math.h>
+#include <string.h>
+
 #include <algorithm>
 
 namespace ckv {
+
+static thread_local std::string g_init_error;
+void set_init_error(const std::string& msg) { g_init_error = msg; }
+const char* init_error() { return g_init_error.c_str(); }
+
+// ------------------------------------------------------------------ configuration
+
+int check_config(const cascade_config* c, std::string& why)
+{
+    if (c->batch < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1) { why = "batch and head counts must be positive"; return CASCADE_E_INVALID_CONFIG; }
+    if (c->n_q_heads % c->n_kv_heads) { why = "n_q_heads must be a multiple of n_kv_heads"; return CASCADE_E_INVALID_CONFIG; }
+    if (c->dtype != CASCADE_F32 && c->dtype != CASCADE_BF16) { why = "dtype must be CASCADE_F32 or CASCADE_BF16"; return CASCADE_E_INVALID_CONFIG; }
+    if (c->head_dim < 2 || c->head_dim % 2) { why = "head_dim must be even"; return CASCADE_E_INVALID_CONFIG; }
+    if (c->n_sink < 0) { why = "n_sink must not be negative"; return CASCADE_E_INVALID_CONFIG; }
+    if (c->n_cascades < 1 || c->n_cascades > CASCADE_MAX_CASCADES) { why = "n_cascades out of range"; return CASCADE_E_INVALID_CONFIG; }
+    bool all_zero = true;
+    for (int i = 0; i < c->n_cascades; ++i) {
+        if (c->cascade_sizes[i] < 1) { why = "every cascade needs at least one slot"; return CASCADE_E_INVALID_CONFIG; }
+        if (c->accept_period[i] < 0) { why = "accept_period must not be negative"; return CASCADE_E_INVALID_CONFIG; }
+        if (c->accept_period[i] != 0) all_zero = false;
+    }
+    if (!all_zero) {
+        if (c->accept_period[0] != 1) { why = "the first cascade must accept every token (accept_period[0] == 1)"; return CASCADE_E_INVALID_CONFIG; }
+        for (int i = 0; i < c->n_cascades; ++i)
+            if (c->accept_period[i] < 1) { why = "accept_period entries must be >= 1"; return CASCADE_E_INVALID_CONFIG; }
+    }
+    if (!(c->ema_beta >= 0.f && c->ema_beta < 1.f)) { why = "ema_beta must be in [0, 1)"; return CASCADE_E_INVALID_CONFIG; }
+    if (!(c->rope_base > 0.f)) { why = "rope_base must be positive"; return CASCADE_E_INVALID_CONFIG; }
+    if (c->softmax_scale < 0.f) { why = "softmax_scale must not be negative"; return CASCADE_E_INVALID_CONFIG; }
+    if (c->max_chunk < 1) { why = "max_chunk must be >= 1"; return CASCADE_E_INVALID_CONFIG; }
+    if (c->head_reduce != CASCADE_REDUCE_MAX && c->head_reduce != CASCADE_REDUCE_MEAN) { why = "unknown head_reduce"; return CASCADE_E_INVALID_CONFIG; }
+    if (c->token_selection != 0 && c->token_selection != 1) { why = "token_selection must be 0 or 1"; return CASCADE_E_INVALID_CONFIG; }
+    long slots = c->n_sink;
+    for (int i = 0; i < c->n_cascades; ++i) slots += c->cascade_sizes[i];
+    if (slots > (1L << 28)) { why = "cache too large"; return CASCADE_E_INVALID_CONFIG; }
+    if (c->dtype == CASCADE_BF16 && c->head_dim != 64 && c->head_dim != 128) { why = "bf16 kernels cover head_dim 64 and 128"; return CASCADE_E_UNSUPPORTED; }
+    if (c->dtype == CASCADE_F32 && c->head_dim > 256) { why = "fp32 kernels cover head_dim up to 256"; return CASCADE_E_UNSUPPORTED; }
+    return CASCADE_OK;
+}
+
+void make_geom(const cascade_config* c, Geom& g)
+{
+    memset(&g, 0, sizeof(g));
+    g.B = c->batch; g.Hq = c->n_q_heads; g.Hkv = c->n_kv_heads; g.G = g.Hq / g.Hkv; g.d = c->head_dim;
+    g.n_sink = c->n_sink; g.N = c->n_cascades;
+    bool all_zero = true;
+    for (int i = 0; i < g.N; ++i) if (c->accept_period[i] != 0) all_zero = false;
+    int slots = g.n_sink;
+    for (int i = 0; i < g.N; ++i) {
+        g.cap[i] = c->cascade_sizes[i];
+        g.period[i] = all_zero ? (1 << i) : c->accept_period[i];
+        slots += g.cap[i];
+    }
+    g.slots = slots;
+    int base = g.n_sink;                       // physical order: sinks, last cascade, ..., first cascade
+    for (int i = g.N - 1; i >= 0; --i) { g.base[i] = base; base += g.cap[i]; }
+    g.token_selection = c->token_selection;
+    g.head_reduce = c->head_reduce;
+    g.beta = c->ema_beta;
+    g.scale = c->softmax_scale > 0.f ? c->softmax_scale : (float)(1.0 / sqrt((double)g.d));
+}
+
 
 static int64_t gcd64(int64_t a, int64_t b)
 {

@@ -9,9 +9,20 @@
 
 #include <stdint.h>
 
+#include <string>
+
 #include "internal.h"
 
 namespace ckv {
+
+// Validation of a configuration (CASCADE_OK or an error code with the reason in `why`) and the
+// geometry derived from a valid one.
+int check_config(const cascade_config* c, std::string& why);
+void make_geom(const cascade_config* c, Geom& g);
+
+// Text of the last failure of a call that has no context to keep it in (per host thread).
+void set_init_error(const std::string& msg);
+const char* init_error();
 
 struct HostState {
     int sink_fill = 0;

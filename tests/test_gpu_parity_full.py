@@ -38,7 +38,7 @@ def test_prefill_32k_whole_chunks(oracle_mod):
     run = ParityRun(cfg, one_step_ahead=True)
     compare = {0, 1, 4, 5, 17, 31}
     worst_out = worst_score = 0.0
-    drift = compared = 0
+    drift = compared = flips = 0
     for c in range(wl.n_chunks):
         q, k, v = chunk_inputs(wl, 0, c)
         if c in compare:
@@ -47,12 +47,14 @@ def test_prefill_32k_whole_chunks(oracle_mod):
             print(f"prefill_32k: comparing chunk {c}", flush=True)
             rep = run.step(q, k, v)
             assert rep.replay_exact, c
+            assert rep.flips_mismatch == 0, (c, rep)
             worst_out, worst_score = max(worst_out, rep.out_err), max(worst_score, rep.score_err)
             drift += rep.drift
             compared += rep.compared
+            flips += rep.flips_noise
         else:
             run.advance_gpu_only(to_device(q, cfg), to_device(k, cfg), to_device(v, cfg))
-    print(f"prefill_32k: out {worst_out:.3e} score {worst_score:.3e} drift {drift}/{compared}")
+    print(f"prefill_32k: out {worst_out:.3e} score {worst_score:.3e} drift {drift}/{compared} noise-level flips {flips}")
     assert worst_out <= TOL_OUT and worst_score <= TOL_SCORE
     st = run.gpu.read_state()
     assert st.n_seen == wl.seq_len and st.counts.tolist() == [64, 1024, 1024, 1024, 1024]
@@ -76,8 +78,9 @@ def test_prefill_131k_sampled_heads(oracle_mod):
             run.sync_oracle_from_gpu()
             print(f"prefill_131k: comparing chunk {c}", flush=True)
             q, k, v = _host(dq), _host(dk), _host(dv)
-            rep = _step_two_heads(run, q, k, v)
+            rep = run.step(q, k, v, threaded=True)
             assert rep.replay_exact, c
+            assert rep.flips_mismatch == 0, (c, rep)
             worst_out, worst_score = max(worst_out, rep.out_err), max(worst_score, rep.score_err)
             drift += rep.drift
             compared += rep.compared
@@ -108,11 +111,11 @@ def test_prefill_paper_16k_all_rows_in_scores(oracle_mod):
         if c == 6:
             run.sync_oracle_from_gpu()
             print("prefill_paper_16k: comparing chunk 6", flush=True)
-            rep = _step_two_heads(run, _host(dq), _host(dk), _host(dv))
+            rep = run.step(_host(dq), _host(dk), _host(dv), threaded=True)
         else:
             run.advance_gpu_only(dq, dk, dv)
     print(f"prefill_paper_16k: out {rep.out_err:.3e} score {rep.score_err:.3e} drift {rep.drift}/{rep.compared}")
-    assert rep.replay_exact
+    assert rep.replay_exact and rep.flips_mismatch == 0, rep
     assert rep.out_err <= TOL_OUT and rep.score_err <= TOL_SCORE
     st = run.gpu.read_state()
     # the last cascade takes every eighth token that leaves the first: 32768 tokens do not fill it yet
@@ -142,9 +145,9 @@ def test_other_experiment_geometries(oracle_mod, name, n_chunks, compare, kv_hea
         if c in compare:
             run.sync_oracle_from_gpu()
             print(f"{name}: comparing chunk {c} ({dq.shape[1]} tokens)", flush=True)
-            rep = _step_two_heads(run, _host(dq), _host(dk), _host(dv))
+            rep = run.step(_host(dq), _host(dk), _host(dv), threaded=True)
             print(f"{name}: chunk {c}: out {rep.out_err:.3e} score {rep.score_err:.3e} drift {rep.drift}/{rep.compared}", flush=True)
-            assert rep.replay_exact
+            assert rep.replay_exact and rep.flips_mismatch == 0, rep
             assert rep.out_err <= TOL_OUT and rep.score_err <= TOL_SCORE
         else:
             run.advance_gpu_only(dq, dk, dv)
@@ -181,6 +184,7 @@ def test_mid_size_batch_two_mixed_prefill_and_decode(oracle_mod):
             print(f"mid size: comparing step {i} ({kind}, {n} tokens)", flush=True)
             rep = run.step(q, k, v, decode=(kind == "d"))
             assert rep.replay_exact, i
+            assert rep.flips_mismatch == 0, (i, rep)
             worst_out, worst_score = max(worst_out, rep.out_err), max(worst_score, rep.score_err)
             drift += rep.drift
             compared += rep.compared
@@ -192,131 +196,203 @@ def test_mid_size_batch_two_mixed_prefill_and_decode(oracle_mod):
                 run.advance_gpu_only(dq, dk, dv)
     print(f"mid size: out {worst_out:.3e} score {worst_score:.3e} drift {drift}/{compared}")
     assert worst_out <= TOL_OUT and worst_score <= TOL_SCORE
-    assert drift <= 0.02 * compared
     run.close()
 
 
-def _step_two_heads(run, q, k, v):
-    """run.step, but with the oracle evaluating only the listed (non-adjacent) KV heads, each
-    on its own thread."""
-    from gpu_harness import StepReport, gpu_decision_scores, replay_is_exact, row_errors, to_device
+def _compare_sampled_rows_1m(run, wl, c, dq, dk, dv, heads, with_model):
+    """One compared chunk of prefill_1m: the library runs the chunk; the oracle, loaded with the
+    library's state just before, evaluates sampled rows (first 8, middle 8) and the last T rows
+    (all rows that carry EMA weight: beta^300 = 2e-14) on the given KV heads.  Returns the worst
+    output errors (ordinary rows, last 64 rows), the worst score error, the worst output and score
+    difference to the bf16 rounding model (if asked), and the library's state after the chunk."""
+    from bf16_model import chunk_reference
+    from gpu_harness import gpu_decision_scores, replay_is_exact, row_errors, StepReport
     cfg = run.cfg
-    n_tok = q.shape[1]
-    out = run.gpu.prefill_chunk(to_device(q, cfg), to_device(k, cfg), to_device(v, cfg))
-    st = run.gpu.read_state(with_kv=True)
-    out = out.float().cpu().numpy()
-    rep = StepReport()
-    beta = float(np.float32(cfg.ema_beta))
+    Q, T = wl.chunk, 300
+    run.sync_oracle_from_gpu()
+    pre = run.prev                     # the library's state before the chunk, with K / V rows of the compared heads
+    print(f"prefill_1m: comparing chunk {c} (cache rows {pre.count})", flush=True)
+    out = run.gpu.prefill_chunk(dq, dk, dv)
+    run._n_seen += Q
+    st = run.read_state()
+    run.check_rows(st)
+    out = out.float().cpu().numpy()[0]
+    q, k, v = _host(dq)[0], _host(dk)[0], _host(dv)[0]
     o = run.oracles[0]
-    pre = {g: o.state(g) for g in run.heads}
-    refs = {}
+    res = {}
 
     def work(g):
-        refs[g] = o.chunk(q[0], k[0], v[0], kv_heads=(g, g + 1))
+        head_out, _ = o.eval_rows(g, q, k, v, 0, 8)
+        mid_out, _ = o.eval_rows(g, q, k, v, Q // 2 - 4, Q // 2 + 4)
+        tail_out, tail_delta = o.eval_rows(g, q, k, v, Q - T, Q)
+        res[g] = (head_out, mid_out, tail_out, tail_delta)
 
-    threads = [threading.Thread(target=work, args=(g,)) for g in run.heads]
+    threads = [threading.Thread(target=work, args=(g,)) for g in heads]
     [t.start() for t in threads]
     [t.join() for t in threads]
-    for g in run.heads:
+    worst = dict(ordinary=0.0, last64=0.0, score=0.0, model_out=0.0, model_score=0.0, detail={})
+    rep = StepReport()
+    npre = pre.count
+    beta = float(np.float32(cfg.ema_beta))
+    for g in heads:
         hq = slice(g * run.G, (g + 1) * run.G)
-        rep.out_err = max(rep.out_err, row_errors(out[0], refs[g], hq))
-        delta = o.last_delta(g)
-        npre = len(pre[g].ids)
-        mu_ref = np.concatenate([pre[g].mu * beta ** n_tok + delta[:npre], delta[npre:]])
-        mu_gpu = gpu_decision_scores(st, 0, g, npre, n_tok)
-        rep.score_err = max(rep.score_err, float((np.abs(mu_gpu - mu_ref) / np.maximum(np.abs(mu_ref), 1e-12)).max()))
-        rep.replay_exact &= replay_is_exact(cfg, run.prev, st, 0, g, mu_gpu)
-        post = o.state(g)
-        rep.compared += st.count
-        rep.drift += int((post.ids != st.ids[0, g, :st.count]).sum())
-    run.sync_oracle_from_gpu(st)
-    return rep
+        head_out, mid_out, tail_out, tail_delta = res[g]
+        for name, ref, rows in (("first rows", head_out, slice(0, 8)), ("middle rows", mid_out, slice(Q // 2 - 4, Q // 2 + 4)),
+                                ("tail rows", tail_out, slice(Q - T, Q - 64)), ("last 64 rows", tail_out, slice(Q - 64, Q))):
+            err = row_errors(out[rows], ref[rows], hq)
+            print(f"  chunk {c} head {g} {name}: out err {err:.3e}", flush=True)
+            key = "last64" if name == "last 64 rows" else "ordinary"
+            worst[key] = max(worst[key], err)
+        # beta^4096 wipes the old scores; the tail rows give the new ones up to beta^300
+        mu_gpu = gpu_decision_scores(st, 0, g, npre, Q)
+        rel = np.abs(mu_gpu - tail_delta) / np.maximum(np.abs(tail_delta), 1e-12)
+        # rows before the tail see no key of the tail region of the chunk: their scores are below
+        # 1e-13 on both sides and carry no decision
+        big = tail_delta > 1e-9
+        worst["score"] = max(worst["score"], float(rel[big].max()))
+        # the decisions: exact replay with the library's scores (the oracle itself does not take the
+        # step here: it has only evaluated rows)
+        replayed = []
+        assert replay_is_exact(cfg, pre, st, 0, g, mu_gpu, state_out=replayed), (c, g)
+        worst["detail"][g] = dict(pre_ids=pre.ids[0, g, :npre].copy(), mu_gpu=mu_gpu, mu_ref=tail_delta, replayed=replayed[0])
+        if with_model:
+            rows = np.concatenate([np.arange(0, 8), np.arange(Q // 2 - 4, Q // 2 + 4), np.arange(Q - T, Q)])
+            mo, md = chunk_reference(q[:, hq], k[:, g], v[:, g], pre.k[0, g, :npre], pre.v[0, g, :npre], pre.slot[0, g, :npre],
+                                     rows, cfg.rope_base, ema_beta=beta)
+            num = np.linalg.norm(out[rows][:, hq] - mo, axis=-1)
+            worst["model_out"] = max(worst["model_out"], float((num / np.linalg.norm(mo, axis=-1)).max()))
+            # the model's increments (the sampled early rows weigh beta^2000 and less), reduced over the group
+            md_tail = md.max(axis=0)
+            relm = np.abs(mu_gpu - md_tail) / np.maximum(np.abs(md_tail), 1e-12)
+            worst["model_score"] = max(worst["model_score"], float(relm[md_tail > 1e-9].max()))
+    run.prev = st
+    return worst, st
 
 
-def test_prefill_1m_sampled_rows_and_planted_key(oracle_mod):
-    """prefill_1m: 256 chunks of 4096 against 64 sinks + 4 x 16384 slots.  A steady-state chunk
-    and the last chunk (whose final 64 queries are aligned with the planted key) are compared on
-    two KV heads: sampled output rows, all tail rows (the last 300, which carry all of the EMA
-    weight: beta^300 = 2e-14), every decision score, and the exact replay of the decisions."""
-    from gpu_harness import ParityRun, gpu_decision_scores, replay_is_exact, row_errors
+def _run_1m(heads):
+    from gpu_harness import ParityRun
     from paper_2406_17808_amd.cache import config_of
     wl = WORKLOADS["prefill_1m"]
     cfg = config_of(wl, keep_update_scores=1)
-    heads = [0, 3]
     run = ParityRun(cfg, one_step_ahead=True, kv_heads=heads)
-    spec = planted_key_spec(wl, 0)
-    compare = {40, wl.n_chunks - 1}
-    Q, T = wl.chunk, 300
-    worst_out = worst_score = worst_planted = 0.0
-    for c in range(wl.n_chunks):
+
+    def regenerate(c):      # the stream is too long to keep on the host: any chunk can be drawn again
+        _, dk, dv = chunk_inputs_torch(wl, 0, c, "cuda:0")
+        return _host(dk), _host(dv)
+
+    run.fed.regenerate_with(regenerate, wl.chunk)
+    return wl, cfg, run
+
+
+# Against the bf16 rounding model (bf16_model.py) what is left is the rounding of the output to
+# bf16 (relative 2^-9 per element, so at most 2^-9 in the L2 norm of a row) and of a probability
+# at another power-of-two phase than the kernel's (two independent 2^-9 roundings: sqrt(2) 2^-9),
+# together below 4.8e-3; scores involve neither (fp32 sums of fp32 probabilities).
+TOL_MODEL_OUT, TOL_MODEL_SCORE = 5e-3, 2e-3
+
+
+def test_prefill_1m_chunks_where_cascades_first_fill(oracle_mod):
+    """prefill_1m up to its first steady-state chunk: the chunks during which the first, third and
+    fourth cascade become full (4, 16, 32: pushes into the next cascade start in the middle of the
+    update) and the chunk after each, compared on three KV heads."""
+    heads = [0, 3, 6]
+    wl, cfg, run = _run_1m(heads)
+    compare = {4, 5, 16, 17, 32, 33}
+    worst_out = worst_score = 0.0
+    for c in range(34):
         dq, dk, dv = chunk_inputs_torch(wl, 0, c, "cuda:0")
         if c not in compare:
-            run.advance_gpu_only(dq, dk, dv)
+            run.advance_gpu_only(dq, dk, dv, record=False)
             continue
-        run.sync_oracle_from_gpu()
-        print(f"prefill_1m: comparing chunk {c} (cache rows {run.prev.count})", flush=True)
-        out = run.gpu.prefill_chunk(dq, dk, dv)
-        st = run.gpu.read_state()
-        out = out.float().cpu().numpy()[0]
-        q, k, v = _host(dq)[0], _host(dk)[0], _host(dv)[0]
-        o = run.oracles[0]
-        res = {}
+        worst, st = _compare_sampled_rows_1m(run, wl, c, dq, dk, dv, heads, with_model=False)
+        worst_out = max(worst_out, worst["ordinary"], worst["last64"])
+        worst_score = max(worst_score, worst["score"])
+    print(f"prefill_1m first fills: out {worst_out:.3e} score {worst_score:.3e}")
+    assert worst_out <= TOL_OUT and worst_score <= TOL_SCORE
+    final = run.gpu.read_state()
+    assert final.counts.tolist() == [64] + [16384] * 4
+    run.close()
 
-        def work(g):
-            head_out, _ = o.eval_rows(g, q, k, v, 0, 8)
-            mid_out, _ = o.eval_rows(g, q, k, v, Q // 2 - 4, Q // 2 + 4)
-            tail_out, tail_delta = o.eval_rows(g, q, k, v, Q - T, Q)
-            res[g] = (head_out, mid_out, tail_out, tail_delta)
 
-        threads = [threading.Thread(target=work, args=(g,)) for g in heads]
-        [t.start() for t in threads]
-        [t.join() for t in threads]
-        for g in heads:
-            hq = slice(g * run.G, (g + 1) * run.G)
-            head_out, mid_out, tail_out, tail_delta = res[g]
-            for name, ref, rows in (("first rows", head_out, slice(0, 8)), ("middle rows", mid_out, slice(Q // 2 - 4, Q // 2 + 4)),
-                                    ("tail rows", tail_out, slice(Q - T, Q - 64)), ("last 64 rows", tail_out, slice(Q - 64, Q))):
-                err = row_errors(out[rows], ref[rows], hq)
-                print(f"  chunk {c} head {g} {name}: out err {err:.3e}")
-                if c == wl.n_chunks - 1 and name != "last 64 rows":
-                    worst_planted = max(worst_planted, err)
-                else:
-                    worst_out = max(worst_out, err)
-            npre = run.prev.count
-            # beta^4096 wipes the old scores; the tail rows give the new ones up to beta^300
-            mu_gpu = gpu_decision_scores(st, 0, g, npre, Q)
-            rel = np.abs(mu_gpu - tail_delta) / np.maximum(np.abs(tail_delta), 1e-12)
-            # rows before the tail see no key of the tail region of the chunk: their scores are
-            # below 1e-13 on both sides and carry no decision
-            big = tail_delta > 1e-9
-            worst_score = max(worst_score, float(rel[big].max()))
-            assert replay_is_exact(cfg, run.prev, st, 0, g, mu_gpu), (c, g)
-        run.prev = st
-    print(f"prefill_1m: out {worst_out:.3e} (ordinary rows of the planted chunk {worst_planted:.3e}) score {worst_score:.3e}")
+def test_prefill_1m_sampled_rows_and_planted_key(oracle_mod):
+    """prefill_1m: 256 chunks of 4096 against 64 sinks + 4 x 16384 slots.  A steady-state chunk, the
+    chunk that brings the planted key and the last chunk (whose final 64 queries are aligned with
+    that key) are compared on three KV heads: sampled output rows, all tail rows, every decision
+    score, the exact replay of the decisions.  From the planted key's chunk to the end every
+    update is replayed (Alg. 2 with the library's scores) on those heads, and whether the key is
+    retained, its cache index (its positional-encoding index, Section 3.1) and the attention mass
+    the last queries put on it must be the replay's and the oracle's."""
+    from gpu_harness import gpu_decision_scores, replay_is_exact
+    heads = [0, 3, 6]
+    wl, cfg, run = _run_1m(heads)
+    spec = planted_key_spec(wl, 0)
+    p = spec["position"]
+    c_plant = p // wl.chunk
+    compare = {40, c_plant, wl.n_chunks - 1}
+    Q = wl.chunk
+    worst_out = worst_score = worst_planted = worst_model_out = worst_model_score = 0.0
+    last = None
+    for c in range(wl.n_chunks):
+        dq, dk, dv = chunk_inputs_torch(wl, 0, c, "cuda:0")
+        if c in compare:
+            worst, st = _compare_sampled_rows_1m(run, wl, c, dq, dk, dv, heads, with_model=(c == wl.n_chunks - 1))
+            if c == wl.n_chunks - 1:
+                worst_planted, last = worst["ordinary"], worst
+                worst_out = max(worst_out, worst["last64"])
+                worst_model_out, worst_model_score = worst["model_out"], worst["model_score"]
+            else:
+                worst_out = max(worst_out, worst["ordinary"], worst["last64"])
+            worst_score = max(worst_score, worst["score"])
+        elif c > c_plant:
+            # every update the planted key lives through: replayed with the library's own scores
+            pre = run.gpu.read_state() if run.prev.n_seen != c * Q else run.prev
+            run.advance_gpu_only(dq, dk, dv, record=False)
+            st = run.gpu.read_state()
+            for g in heads:
+                assert replay_is_exact(cfg, pre, st, 0, g, gpu_decision_scores(st, 0, g, pre.count, Q)), (c, g)
+            run.prev = st
+        else:
+            run.advance_gpu_only(dq, dk, dv, record=False)
+    print(f"prefill_1m: out {worst_out:.3e} (ordinary rows of the last chunk {worst_planted:.3e}; against the bf16 rounding "
+          f"model: out {worst_model_out:.3e} score {worst_model_score:.3e}) score {worst_score:.3e}")
     assert worst_out <= TOL_OUT and worst_score <= TOL_SCORE
     # In the last chunk the cache holds the planted key, whose norm is 4x that of every other key.
     # The rounding of the rotated bf16 operands perturbs a logit in proportion to |q||k|, so for
-    # ordinary queries that put a few percent of their mass on that key the output noise is up to
-    # 4x the usual one (a numpy model of nothing but that rounding gives up to 4e-2 over 300 rows,
-    # against 4e-3 without the planted key).  The rows this workload is about, the last 64 queries
+    # ordinary queries that put a few percent of their mass on that key the error against ideal
+    # arithmetic is up to 4x the usual one.  That this is the contract's operand rounding and nothing
+    # else is what the comparison with the rounding model shows, on the same rows, at a bound 4x
+    # tighter than the plain tolerance.  The rows this workload is about, the last 64 queries
     # aligned with the key, are held to the plain tolerance above.
     assert worst_planted <= 4 * TOL_OUT
+    assert worst_model_out <= TOL_MODEL_OUT and worst_model_score <= TOL_MODEL_SCORE
     final = run.gpu.read_state()
     assert final.n_seen == wl.seq_len and final.counts.tolist() == [64] + [16384] * 4
-    # the planted key: retained or not is reported; that the library's decision about it is the
-    # one Alg. 2 takes with the library's scores is covered by the exact replay above
-    p = spec["position"]
+    # The planted key.  Every update since its arrival was replayed exactly, so where it is (or that
+    # it is gone) is where Alg. 2 puts it with the library's scores; here the same is asserted
+    # against a policy oracle that runs free over all those updates, and the attention mass of the
+    # last queries on it (its score after the last chunk: beta^4096 has wiped everything older)
+    # against the oracle's rows.
     for g in heads:
+        det = last["detail"][g]
         where = np.nonzero(final.ids[0, g, :final.count] == p)[0]
+        where_replay = np.nonzero(det["replayed"].ids == p)[0]
+        # retained or not, and at which cache index (= positional-encoding index): the replay's answer
+        assert where.tolist() == where_replay.tolist(), (g, where, where_replay)
+        before = np.nonzero(det["pre_ids"] == p)[0]
+        if len(before):
+            # the mass the last queries of the stream put on it: the library's score against the oracle's
+            i = int(before[0])
+            m_gpu, m_ref = float(det["mu_gpu"][i]), float(det["mu_ref"][i])
+            assert abs(m_gpu - m_ref) <= TOL_SCORE * abs(m_ref), (g, m_gpu, m_ref)
         print(f"planted key {p} head {g}: " + (f"retained at cache index {int(where[0])}, score "
-              f"{final.mu[0, g, where[0]]:.3e} (median score {np.median(final.mu[0, g, :final.count]):.3e})"
-              if len(where) else "not retained"))
+              f"{final.mu[0, g, where[0]]:.3e} (oracle {det['mu_ref'][int(before[0])]:.3e}; median score "
+              f"{np.median(final.mu[0, g, :final.count]):.3e})" if len(where) else "not retained (as in the replay)"))
     run.close()
 
 
 def test_decode_b32_sampled_sequences(oracle_mod):
     """decode_b32: 32 sequences x 8 KV heads, every cache full (64 + 4 x 16384) with N(0,1) K/V
-    and U(0,1) scores; decode steps compared on sampled (sequence, KV head) pairs, free running."""
+    and U(0,1) scores; 32 decode steps compared on sampled (sequence, KV head) pairs, free running."""
     import torch
     from gpu_harness import ParityRun
     from paper_2406_17808_amd.cache import config_of
@@ -342,52 +418,27 @@ def test_decode_b32_sampled_sequences(oracle_mod):
     seqs, heads = [0, 31], [2, 7]
     run = ParityRun(cfg, one_step_ahead=False, kv_heads=heads, init_state=st0, seqs=seqs)
     counts = np.array([wl.n_sink] + list(wl.cascade_sizes))
+    init_k, init_v = {}, {}
     for b in seqs:
         for g in heads:
+            init_k[b, g], init_v[b, g] = k0[b, g].float().cpu().numpy(), v0[b, g].float().cpu().numpy()
             run.oracles[b].set_state(g, ids_row.numpy().astype(np.int64), mu0[b, g].cpu().numpy().astype(np.float64),
-                                     counts, k0[b, g].float().cpu().numpy(), v0[b, g].float().cpu().numpy(),
-                                     st0.t, st0.n_seen)
+                                     counts, init_k[b, g], init_v[b, g], st0.t, st0.n_seen)
+    run.fed.add_initial(ids_row.numpy(), init_k, init_v)
     torch.cuda.synchronize()
     del k0, v0
     worst_out = worst_score = 0.0
-    drift = 0
-    for step in range(6):
+    drift = flips = 0
+    for step in range(32):
         q = torch.randn((wl.batch, 1, wl.n_q_heads, d), generator=gen, device=dev).to(torch.bfloat16)
         k = torch.randn((wl.batch, 1, wl.n_kv_heads, d), generator=gen, device=dev).to(torch.bfloat16)
         v = torch.randn((wl.batch, 1, wl.n_kv_heads, d), generator=gen, device=dev).to(torch.bfloat16)
-        print(f"decode_b32: comparing step {step}", flush=True)
-        rep = _decode_step_two_heads(run, _host(q), _host(k), _host(v))
+        rep = run.step(_host(q), _host(k), _host(v), decode=True, threaded=True)
         assert rep.replay_exact, step
+        assert rep.flips_mismatch == 0, (step, rep)
         worst_out, worst_score = max(worst_out, rep.out_err), max(worst_score, rep.score_err)
         drift += rep.drift
-    print(f"decode_b32: out {worst_out:.3e} score {worst_score:.3e} drift {drift}")
+        flips += rep.flips_noise
+    print(f"decode_b32: out {worst_out:.3e} score {worst_score:.3e} drift {drift} noise-level flips {flips}")
     assert worst_out <= TOL_OUT and worst_score <= TOL_SCORE
     run.close()
-
-
-def _decode_step_two_heads(run, q, k, v):
-    from gpu_harness import StepReport, gpu_decision_scores, replay_is_exact, row_errors, to_device
-    cfg = run.cfg
-    dq, dk, dv = to_device(q, cfg), to_device(k, cfg), to_device(v, cfg)
-    out = run.gpu.decode_step(dq[:, 0].contiguous(), dk[:, 0].contiguous(), dv[:, 0].contiguous())[:, None]
-    st = run.gpu.read_state()
-    out = out.float().cpu().numpy()
-    rep = StepReport()
-    beta = float(np.float32(cfg.ema_beta))
-    for b, o in run.oracles.items():
-        for g in run.heads:
-            pre = o.state(g)
-            ref = o.chunk(q[b], k[b], v[b], kv_heads=(g, g + 1))
-            hq = slice(g * run.G, (g + 1) * run.G)
-            rep.out_err = max(rep.out_err, row_errors(out[b], ref, hq))
-            delta = o.last_delta(g)
-            npre = len(pre.ids)
-            mu_ref = np.concatenate([pre.mu * beta + delta[:npre], delta[npre:]])
-            mu_gpu = gpu_decision_scores(st, b, g, npre, 1)
-            rep.score_err = max(rep.score_err, float((np.abs(mu_gpu - mu_ref) / np.maximum(np.abs(mu_ref), 1e-12)).max()))
-            rep.replay_exact &= replay_is_exact(cfg, run.prev, st, b, g, mu_gpu)
-            post = o.state(g)
-            rep.compared += st.count
-            rep.drift += int((post.ids != st.ids[b, g, :st.count]).sum())
-    run.prev = st
-    return rep

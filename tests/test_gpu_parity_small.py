@@ -60,9 +60,13 @@ def test_tiny_f32_free_running(oracle_mod):
          sizes=[64, 64], chunks=[300] * 4, max_chunk=300, beta=0.99, score_tail_eps=-1.0, score_narrow=0),
     # keys grow along every chunk, so the running maximum of a row keeps rising by more than the
     # kernel's rescaling threshold.  bf16 operand rounding is relative: with logits of magnitude
-    # ~20 the exponents are off by ~20 * 2^-8, hence the wider output tolerance of this case.
+    # ~20 the exponents are off by ~20 * 2^-8, hence the wider tolerance of this case against the
+    # oracle's ideal arithmetic.  That the excess is this operand rounding and nothing else is
+    # checked against the numpy model that rounds where the bf16 contract does ("model": the bounds
+    # on outputs and scores against it).
     dict(name="bf16_rising_logits", dtype=B.CASCADE_BF16, d=64, Hq=4, Hkv=2, batch=1, n_sink=4,
-         sizes=[96, 96, 96], chunks=[256] * 6, max_chunk=256, input_scale=1.5, key_ramp=2.0, tol_out=0.1, tol_score=0.3),
+         sizes=[96, 96, 96], chunks=[256] * 6, max_chunk=256, input_scale=1.5, key_ramp=2.0, tol_out=0.1, tol_score=0.3,
+         model=(5e-3, 2e-3)),
     dict(name="f32_periods_mean", dtype=B.CASCADE_F32, d=32, Hq=4, Hkv=2, batch=2, n_sink=2,
          sizes=[9, 5, 7], chunks=[20, 3, 20, 20, 1, 20, 20, 20], max_chunk=20, periods=[1, 3, 2],
          head_reduce=B.CASCADE_REDUCE_MEAN),
@@ -81,7 +85,10 @@ def test_tiny_f32_free_running(oracle_mod):
          sizes=[256, 256, 256, 256], chunks=[512] * 8, max_chunk=512, attn_splits=3),
     dict(name="bf16_rising_logits_unsplit", dtype=B.CASCADE_BF16, d=64, Hq=4, Hkv=2, batch=1, n_sink=4,
          sizes=[96, 96, 96], chunks=[256] * 6, max_chunk=256, input_scale=1.5, key_ramp=2.0, tol_out=0.1, tol_score=0.3,
-         attn_splits=1),
+         attn_splits=1, model=(5e-3, 2e-3)),
+    # an ordinary case against the same model, for scale
+    dict(name="bf16_big_tiles_model", dtype=B.CASCADE_BF16, d=128, Hq=8, Hkv=2, batch=1, n_sink=64,
+         sizes=[256, 256, 256, 256], chunks=[512] * 4, max_chunk=512, model=(5e-3, 2e-3)),
     # one slowly rotating RoPE pair carries 32 in every query and 64 in the marked keys, which lifts
     # their logits by about 2^8 / sqrt(d) x 2^3 x log2(e) (far more than an fp32 exponent holds)
     # over the keys without it: the running maximum has to follow, whatever a launch concluded
@@ -124,9 +131,10 @@ def test_prefill_one_step_ahead(oracle_mod, case, monkeypatch):
     tol_out, tol_score = _tolerances(cfg)
     tol_out, tol_score = case.get("tol_out", tol_out), case.get("tol_score", tol_score)
     rng = np.random.default_rng(7)
-    run = ParityRun(cfg, one_step_ahead=True)
-    drift = compared = seen = 0
-    worst_out = worst_score = 0.0
+    # a comparison may flip where two scores are as close as the score tolerance of the case allows
+    run = ParityRun(cfg, one_step_ahead=True, tau=case.get("tol_score"))
+    drift = compared = seen = flips = 0
+    worst_out = worst_score = worst_model_out = worst_model_score = 0.0
     for i, n in enumerate(case["chunks"]):
         q, k, v = _inputs(rng, cfg, n, case.get("input_scale", 1.0))
         if "key_ramp" in case:
@@ -138,17 +146,25 @@ def test_prefill_one_step_ahead(oracle_mod, case, monkeypatch):
             q[..., lo], q[..., hi] = 32.0, 0.0
             k[..., lo], k[..., hi] = np.where(marked, 64.0, 0.0).astype(np.float32)[None, :, None], 0.0
         seen += n
-        rep = run.step(q, k, v)
+        rep = run.step(q, k, v, with_model="model" in case)
         assert rep.replay_exact, (case["name"], i)
+        # membership may only differ from the free oracle through comparisons whose two scores are
+        # inside float noise of each other by the oracle's own account
+        if case.get("compare_membership", True):
+            assert rep.flips_mismatch == 0, (case["name"], i, rep)
         worst_out, worst_score = max(worst_out, rep.out_err), max(worst_score, rep.score_err)
+        worst_model_out, worst_model_score = max(worst_model_out, rep.model_out_err), max(worst_model_score, rep.model_score_err)
         drift += rep.drift
         compared += rep.compared
-    print(f"{case['name']}: out {worst_out:.3e} score {worst_score:.3e} drift {drift}/{compared}")
+        flips += rep.flips_noise
+    print(f"{case['name']}: out {worst_out:.3e} score {worst_score:.3e} drift {drift}/{compared} noise-level flips {flips}"
+          + (f" model: out {worst_model_out:.3e} score {worst_model_score:.3e}" if "model" in case else ""))
     assert worst_out <= tol_out
     assert worst_score <= tol_score
-    # membership may only differ from the free oracle where score gaps are inside float noise
-    if case.get("compare_membership", True):
-        assert drift <= (0.02 * compared if cfg.dtype == B.CASCADE_BF16 else 0), (drift, compared)
+    if "model" in case:
+        assert worst_model_out <= case["model"][0] and worst_model_score <= case["model"][1]
+    if cfg.dtype == B.CASCADE_F32 and case.get("compare_membership", True):
+        assert drift == 0, (drift, compared)
     run.close()
 
 
@@ -295,13 +311,13 @@ def test_random_geometries(oracle_mod, seed, monkeypatch):
         q, k, v = _inputs(rng, cfg, n)
         rep = run.step(q, k, v, decode=decode)
         assert rep.replay_exact, (seed, step)
+        assert rep.flips_mismatch == 0, (seed, step, rep)
         worst_out, worst_score = max(worst_out, rep.out_err), max(worst_score, rep.score_err)
         drift += rep.drift
         compared += rep.compared
     print(f"random geometry {seed}: d={d} heads {hkv * G}/{hkv} sinks {cfg.n_sink} sizes {sizes} periods {periods} "
           f"max_chunk {max_chunk}: out {worst_out:.3e} score {worst_score:.3e} drift {drift}/{compared}")
     assert worst_out <= tol_out and worst_score <= tol_score
-    assert drift <= 0.02 * max(compared, 1)
     run.close()
 
 
