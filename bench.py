@@ -46,6 +46,20 @@ def calibration_copy(torch, mib):
     del a, b
 
 
+def measured_ceilings(torch, B):
+    """What this very device sustains, measured in this run (untimed leg): streaming read, copy, pure MFMA loop."""
+    nbytes = 4 << 30
+    buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    buf.fill_(1)
+    torch.cuda.synchronize()
+    c = B.cascade_measure_ceilings(buf.data_ptr(), nbytes, torch.cuda.current_stream().cuda_stream)
+    del buf
+    torch.cuda.empty_cache()
+    return {"compute_units": c["compute_units"], "core_clock_mhz": c["core_clock_mhz"], "memory_clock_mhz": c["memory_clock_mhz"],
+            "memory_bus_bits": c["memory_bus_bits"], "hbm_read_gb_s": c["read_gb_s"], "hbm_copy_gb_s_read_plus_write": c["copy_gb_s"],
+            "mfma_bf16_tflops": c["mfma_bf16_tflops"], "buffer_bytes": nbytes}
+
+
 def prefill_bench(args, torch, B, wl):
     from paper_2406_17808_amd.cache import CascadeKVCache, config_of
     from paper_2406_17808_amd.workloads import chunk_inputs_torch
@@ -214,6 +228,7 @@ def main():
     ap.add_argument("--cpu-sample-tokens", type=int, default=640)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the untimed leg that measures read / copy / MFMA ceilings")
     ap.add_argument("--only-decode", action="store_true")
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--decode-warmup", type=int, default=16)
@@ -234,6 +249,7 @@ def main():
     if args.only_decode:   # development aid: the decode section alone, not the contract line
         print(json.dumps(decode_bench(args, torch, B)))
         return
+    ceilings = None if args.no_ceilings else measured_ceilings(torch, B)
     res, cache, chunks, cfg = prefill_bench(args, torch, B, wl)
     line = {
         "metric": "prefill_tokens_per_s_per_layer", "value": res["tokens_per_s"], "unit": "tokens/s",
@@ -247,6 +263,9 @@ def main():
         "roofline": res["roofline"], "kernel_ms_per_step": res["kernel_ms_per_step"],
         "end_to_end_mfma_frac": res["end_to_end_mfma_frac"], "roofline_update": res["roofline_update"],
     }
+    if ceilings is not None:
+        line["measured_ceilings"] = ceilings
+        line["roofline"]["frac_of_measured_mfma"] = line["roofline"]["achieved"] / ceilings["mfma_bf16_tflops"]
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(args, torch, B, wl, cache, cfg, chunks)
     cache.close()
@@ -254,6 +273,9 @@ def main():
     torch.cuda.empty_cache()
     if not args.no_decode:
         line.update(decode_bench(args, torch, B))
+        if ceilings is not None:
+            line["roofline_decode"]["frac_of_measured_read"] = line["roofline_decode"]["achieved"] / ceilings["hbm_read_gb_s"]
+            line["decode_frac_of_measured_read"] = line["decode_hbm_frac"] * HBM_PEAK / 1e9 / ceilings["hbm_read_gb_s"]
     print(json.dumps(line))
 
 

@@ -45,6 +45,8 @@ enum {
 
 enum { CASCADE_F32 = 0, CASCADE_BF16 = 1 };
 enum { CASCADE_REDUCE_MAX = 0, CASCADE_REDUCE_MEAN = 1 };
+enum { CASCADE_HEADS_INDEPENDENT = 0, CASCADE_HEADS_HOMOGENEOUS = 1 };
+enum { CASCADE_SCORES_EXACT = 0, CASCADE_SCORES_SINGLE_PASS = 1 };
 
 /*
  * Geometry and hyper-parameters (Section 4 "Setup": sinks are counted in addition
@@ -77,6 +79,12 @@ typedef struct cascade_config {
                                  scores as they were when the insertion decisions were taken, for
                                  cascade_read_state (host_pre_mu, host_chunk_mu).  Costs one extra
                                  pass over the score array per call. */
+    int32_t head_policy;      /* CASCADE_HEADS_INDEPENDENT (the paper's choice: every KV head decides with its own
+                                 scores) or CASCADE_HEADS_HOMOGENEOUS (Appendix "Head Policy and Head Reduction":
+                                 the scores are reduced over ALL heads, by head_reduce, and every KV head takes
+                                 the same decisions, so all of them hold the same tokens) */
+    int32_t score_mode;       /* CASCADE_SCORES_EXACT: the scores use the final softmax probabilities (Section 3.1);
+                                 CASCADE_SCORES_SINGLE_PASS: reserved */
 } cascade_config;
 
 typedef struct cascade_ctx cascade_ctx;
@@ -256,6 +264,27 @@ typedef struct cascade_profile {
 } cascade_profile;
 int cascade_profile_begin(cascade_ctx* ctx);
 int cascade_profile_end(cascade_ctx* ctx, cascade_profile* out);
+
+/*
+ * Diagnostics: what the device this process runs on sustains, measured now, next to which the
+ * roofline fractions of the library's kernels can be read (Section 4.1 reports latencies of one
+ * GPU; the published peaks of another say little about it): number of compute units and clocks
+ * from the device properties, a streaming read of dev_buffer (GB/s), a copy of its first half
+ * onto its second (GB/s of bytes read plus bytes written), and a loop of nothing but
+ * v_mfma_f32_32x32x16_bf16 on register operands, two waves per SIMD (TFLOP/s).  dev_buffer: at least
+ * 64 MiB of device memory, 16-byte aligned; its contents are overwritten.  Blocks until done.
+ * Errors: NULL_ARG, BAD_ARG, HIP.
+ */
+typedef struct cascade_ceilings {
+    int32_t compute_units;
+    int32_t memory_bus_bits;
+    double core_clock_mhz;      /* the maximum the driver reports, not the clock a kernel runs at */
+    double memory_clock_mhz;
+    double read_gb_s;
+    double copy_gb_s;
+    double mfma_bf16_tflops;
+} cascade_ceilings;
+int cascade_measure_ceilings(void* dev_buffer, size_t bytes, void* stream, cascade_ceilings* out);
 
 /* Text of the last error of this context (or of the last failed cascade_init if ctx is NULL). */
 const char* cascade_last_error(const cascade_ctx* ctx);

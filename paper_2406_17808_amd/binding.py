@@ -27,12 +27,16 @@ CASCADE_F32 = 0
 CASCADE_BF16 = 1
 CASCADE_REDUCE_MAX = 0
 CASCADE_REDUCE_MEAN = 1
+CASCADE_HEADS_INDEPENDENT = 0
+CASCADE_HEADS_HOMOGENEOUS = 1
+CASCADE_SCORES_EXACT = 0
+CASCADE_SCORES_SINGLE_PASS = 1
 
 EXPORTED_SYMBOLS = [
     "cascade_workspace_bytes", "cascade_init", "cascade_destroy", "cascade_prefill_chunk",
     "cascade_decode_step", "cascade_read_state", "cascade_simulate_structure", "cascade_last_error",
     "cascade_profile_begin", "cascade_profile_end", "cascade_layers_workspace_bytes", "cascade_init_layers",
-    "cascade_init_static",
+    "cascade_init_static", "cascade_measure_ceilings",
 ]
 CASCADE_STATIC_WORKSPACE_BYTES = 64 << 20
 
@@ -56,6 +60,7 @@ class cascade_config(ctypes.Structure):
         ("ema_beta", ctypes.c_float), ("rope_base", ctypes.c_float), ("softmax_scale", ctypes.c_float),
         ("max_chunk", ctypes.c_int32), ("head_reduce", ctypes.c_int32), ("token_selection", ctypes.c_int32),
         ("score_tail_eps", ctypes.c_float), ("keep_update_scores", ctypes.c_int32),
+        ("head_policy", ctypes.c_int32), ("score_mode", ctypes.c_int32),
     ]
 
 
@@ -82,6 +87,12 @@ class cascade_state_view(ctypes.Structure):
         ("t", ctypes.c_int64), ("n_seen", ctypes.c_int64),
         ("pre_count", ctypes.c_int32), ("last_tokens", ctypes.c_int32), ("n_kv_pairs", ctypes.c_int32),
     ]
+
+
+class cascade_ceilings(ctypes.Structure):
+    _fields_ = [("compute_units", ctypes.c_int32), ("memory_bus_bits", ctypes.c_int32),
+                ("core_clock_mhz", ctypes.c_double), ("memory_clock_mhz", ctypes.c_double),
+                ("read_gb_s", ctypes.c_double), ("copy_gb_s", ctypes.c_double), ("mfma_bf16_tflops", ctypes.c_double)]
 
 
 class cascade_profile(ctypes.Structure):
@@ -126,6 +137,8 @@ def load_library():
         L.cascade_profile_begin.argtypes = [P]
         L.cascade_profile_end.restype = ctypes.c_int
         L.cascade_profile_end.argtypes = [P, ctypes.POINTER(cascade_profile)]
+        L.cascade_measure_ceilings.restype = ctypes.c_int
+        L.cascade_measure_ceilings.argtypes = [P, ctypes.c_size_t, P, ctypes.POINTER(cascade_ceilings)]
         L.cascade_last_error.restype = ctypes.c_char_p
         L.cascade_last_error.argtypes = [P]
         _LIB = L
@@ -136,7 +149,8 @@ def make_config(batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, dtyp
                 cascade_sizes: Sequence[int], ema_beta: float, rope_base: float, max_chunk: int,
                 accept_period: Optional[Sequence[int]] = None, softmax_scale: float = 0.0,
                 head_reduce: int = CASCADE_REDUCE_MAX, token_selection: int = 1,
-                score_tail_eps: float = 0.0, keep_update_scores: int = 0) -> cascade_config:
+                score_tail_eps: float = 0.0, keep_update_scores: int = 0,
+                head_policy: int = CASCADE_HEADS_INDEPENDENT, score_mode: int = CASCADE_SCORES_EXACT) -> cascade_config:
     c = cascade_config()
     c.batch, c.n_q_heads, c.n_kv_heads, c.head_dim, c.dtype = batch, n_q_heads, n_kv_heads, head_dim, dtype
     c.n_sink, c.n_cascades = n_sink, len(cascade_sizes)
@@ -149,6 +163,7 @@ def make_config(batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, dtyp
     c.max_chunk, c.head_reduce, c.token_selection = max_chunk, head_reduce, token_selection
     c.score_tail_eps = score_tail_eps
     c.keep_update_scores = keep_update_scores
+    c.head_policy, c.score_mode = head_policy, score_mode
     return c
 
 
@@ -223,6 +238,13 @@ def cascade_profile_end(ctx) -> dict:
     p = cascade_profile()
     _check(load_library().cascade_profile_end(ctx, ctypes.byref(p)), ctx)
     return {name: (float(p.ms[i]), int(p.intervals[i])) for i, name in enumerate(KERNEL_FAMILIES)}
+
+
+def cascade_measure_ceilings(dev_buffer: int, nbytes: int, stream: int = 0) -> dict:
+    """Measured ceilings of the current device (see include/cascade_kv.h) as a dict."""
+    c = cascade_ceilings()
+    _check(load_library().cascade_measure_ceilings(dev_buffer, nbytes, stream, ctypes.byref(c)), None)
+    return {name: getattr(c, name) for name, _ in cascade_ceilings._fields_}
 
 
 class StateArrays:

@@ -9,7 +9,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libcascade_kv.so")
 
-SOURCES = ["api.hip", "structure.cpp", "simulate.cpp", "cache_kernels.hip", "attn_simple.hip", "attn_stream.hip", "score_mfma.hip", "decode.hip"]
+SOURCES = ["api.hip", "structure.cpp", "simulate.cpp", "cache_kernels.hip", "attn_simple.hip", "attn_stream.hip", "score_mfma.hip", "decode.hip", "ceilings.hip"]
 
 # packed fp32 instructions are switched off for every device compilation of this project
 HIPCC_FLAGS = [

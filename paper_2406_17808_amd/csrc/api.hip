@@ -36,6 +36,7 @@ struct cascade_ctx {
     TileRuns stale;
     bool profiling = false;
     bool is_static = false;   // one of the per-device contexts of cascade_init_static: never deleted
+    bool poisoned = false;    // a launch of an earlier call failed: the device state is undefined
     std::vector<std::pair<hipEvent_t, hipEvent_t>> prof[CASCADE_K_FAMILIES];
     std::string err;
 };
@@ -209,8 +210,15 @@ static int init_context(const char* who, const cascade_config* cfg, const Geom& 
     ctx->max_chunk = cfg->max_chunk;
     carve(cfg, g, state_base, shared_base, &ctx->buf);
     ctx->mfma = cfg->dtype == CASCADE_BF16;
+    // development switches: the environment is read here and nowhere else
     if (const char* e = getenv("CASCADE_KV_SCALAR_ATTENTION")) if (e[0] == '1') ctx->mfma = false;
-    if (const char* e = getenv("CASCADE_KV_PACK_REUSE")) ctx->packed_reuse = e[0] != '0';   // 0: pack every tile for every chunk (A/B timing, tests)
+    if (const char* e = getenv("CASCADE_KV_PACK_REUSE")) ctx->packed_reuse = e[0] != '0';   // 0: pack every tile for every chunk
+    ctx->buf.opt_attn_splits = 0;
+    if (const char* e = getenv("CASCADE_KV_ATTN_SPLITS")) ctx->buf.opt_attn_splits = atoi(e);
+    ctx->buf.opt_score_narrow = -1;
+    if (const char* e = getenv("CASCADE_KV_SCORE_NARROW")) ctx->buf.opt_score_narrow = e[0] == '1' ? 1 : 0;
+    ctx->buf.opt_decode_qk_direct = getenv("CASCADE_KV_DECODE_QK_DIRECT") != nullptr;
+    ctx->buf.opt_decode_pv_valu = getenv("CASCADE_KV_DECODE_PV_VALU") != nullptr;
 
     // rows of a chunk whose EMA weight beta^k has not dropped below the cut
     {
@@ -439,6 +447,7 @@ extern "C" int cascade_prefill_chunk(cascade_ctx* ctx, const void* dev_q, const 
     if (!dev_q || !dev_k || !dev_v || !dev_out) return fail(ctx, CASCADE_E_NULL_ARG, "cascade_prefill_chunk: NULL argument");
     if (n_tokens < 1 || n_tokens > ctx->max_chunk) return fail(ctx, CASCADE_E_BAD_ARG, "cascade_prefill_chunk: n_tokens out of range");
     if (ctx->st.n_seen + n_tokens > 0x7FFFFFFF) return fail(ctx, CASCADE_E_BAD_ARG, "cascade_prefill_chunk: token index overflow");
+    if (ctx->poisoned) return fail(ctx, CASCADE_E_HIP, "cascade_prefill_chunk: an earlier call on this context failed to launch; the cache is undefined");
     const Geom& g = ctx->g;
     hipStream_t s = (hipStream_t)stream;
     const int Q = n_tokens;
@@ -489,23 +498,30 @@ extern "C" int cascade_prefill_chunk(cascade_ctx* ctx, const void* dev_q, const 
         Timed t(ctx, CASCADE_K_SCORES, s);
         if (ctx->mfma) launch_score_mfma(g, ctx->buf, sl, Q, ctx->max_chunk, tail, decay, s);
         else launch_score_simple(g, ctx->dtype, ctx->buf, sl, Q, ctx->max_chunk, tail, decay, s);
+        if (g.head_policy == CASCADE_HEADS_HOMOGENEOUS && g.Hkv > 1) launch_share_scores(g, ctx->buf, Q, ctx->max_chunk, s);
     }
     int rc = snapshot_scores(ctx, Q, s);
     if (rc) return rc;
     UpdatePlan pl;
-    plan_update(g, ctx->st, Q, pl);
+    HostState st_next = ctx->st;      // the host mirror moves on only once every launch has been accepted
+    plan_update(g, st_next, Q, pl);
     {
         Timed t(ctx, CASCADE_K_UPDATE, s);
         launch_plan(g, ctx->buf, pl, ctx->max_chunk, s);
         launch_moves(g, ctx->dtype, ctx->buf, pl, ctx->max_chunk, dev_k, dev_v, g.Hkv * g.d, Q * g.Hkv * g.d, s);
     }
     const int rc_launch = hip_check(ctx, hipGetLastError(), "cascade_prefill_chunk");
-    if (rc_launch == CASCADE_OK && packed_stable) {
+    if (rc_launch != CASCADE_OK) {    // some launches may have run: host and device no longer agree
+        ctx->poisoned = true;
+        return rc_launch;
+    }
+    ctx->st = st_next;
+    if (packed_stable) {
         ctx->packed = lay;
         ctx->stale.n = 0; ctx->stale.total = 0;
         ctx->packed_valid = add_touched_tiles(g, lay, pl, ctx->stale);
     }
-    return rc_launch;
+    return CASCADE_OK;
 }
 
 // ------------------------------------------------------------------ decode step
@@ -518,6 +534,7 @@ extern "C" int cascade_decode_step(cascade_ctx* ctx, const void* dev_q, const vo
     const Geom& g = ctx->g;
     if (!decode_supported(g)) return fail(ctx, CASCADE_E_UNSUPPORTED, "cascade_decode_step: needs head_dim 64 or 128 and at most 8 query heads per KV head");
     if (ctx->st.n_seen + 1 > 0x7FFFFFFF) return fail(ctx, CASCADE_E_BAD_ARG, "cascade_decode_step: token index overflow");
+    if (ctx->poisoned) return fail(ctx, CASCADE_E_HIP, "cascade_decode_step: an earlier call on this context failed to launch; the cache is undefined");
     hipStream_t s = (hipStream_t)stream;
 
     SegList sl;
@@ -530,17 +547,23 @@ extern "C" int cascade_decode_step(cascade_ctx* ctx, const void* dev_q, const vo
     {
         Timed t1(ctx, CASCADE_K_DECODE_PV, s);
         launch_decode_pv(g, ctx->dtype, ctx->buf, sl, s);
+        // homogeneous heads: the cached scores are shared here, the new token's inside decode_finish
+        if (g.head_policy == CASCADE_HEADS_HOMOGENEOUS && g.Hkv > 1) launch_share_scores(g, ctx->buf, 0, ctx->max_chunk, s);
     }
     // the snapshot holds the cached scores after this step's EMA update and before the insertion
     int rc = snapshot_scores(ctx, 1, s);
     if (rc) return rc;
     UpdatePlan pl;
-    plan_update(g, ctx->st, 1, pl);
+    HostState st_next = ctx->st;
+    plan_update(g, st_next, 1, pl);
     {
         Timed t2(ctx, CASCADE_K_DECODE_FINISH, s);
         launch_decode_finish(g, ctx->dtype, ctx->buf, sl, pl, ctx->max_chunk, dev_k, dev_v, dev_out, s);
     }
-    return hip_check(ctx, hipGetLastError(), "cascade_decode_step");
+    rc = hip_check(ctx, hipGetLastError(), "cascade_decode_step");
+    if (rc != CASCADE_OK) { ctx->poisoned = true; return rc; }
+    ctx->st = st_next;
+    return CASCADE_OK;
 }
 
 // ------------------------------------------------------------------ read state

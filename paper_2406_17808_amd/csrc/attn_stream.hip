@@ -255,8 +255,8 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
                 const float x0 = __uint_as_float((j & 1) ? (wl & 0xFFFF0000u) : (wl << 16)) * qscale;
                 const float x1 = __uint_as_float((j & 1) ? (wh & 0xFFFF0000u) : (wh << 16)) * qscale;
                 const float2 c = cs[ks * 16 + j];
-                y0[j] = x0 * c.x - x1 * c.y;
-                y1[j] = x1 * c.x + x0 * c.y;
+                y0[j] = rot_lo(x0, x1, c.x, c.y);
+                y1[j] = rot_hi(x0, x1, c.x, c.y);
                 qn2 += x0 * x0 + x1 * x1;
             }
 #pragma unroll
@@ -635,12 +635,11 @@ __global__ __launch_bounds__(D) void attn_merge_kernel(Geom g, int Q, int n_tile
 
 // Workgroups per (row block, KV head) so that a small launch still fills the chip: none for 256
 // workgroups or more.
-int attn_splits(const Geom& g, int Q)
+int attn_splits(const Geom& g, int Q, int forced)
 {
-    const char* forced = getenv("CASCADE_KV_ATTN_SPLITS");   // debug switch, read at every launch
     constexpr int BM = kSWaves * 32;
     const int wgs = ((g.G * Q + BM - 1) / BM) * g.B * g.Hkv;
-    int n = forced ? atoi(forced) : 256 / wgs;
+    int n = forced > 0 ? forced : 256 / wgs;
     if (n > 256 / wgs) n = 256 / wgs;       // the partial results are sized for 256 workgroups
     if (n > kMaxAttnSplits) n = kMaxAttnSplits;
     return n < 1 ? 1 : n;
@@ -653,7 +652,7 @@ void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, i
     const int tiles_per_bh = b.vt_tiles;   // stride between the packed streams of two (batch, KV head)
     constexpr int BM = kSWaves * 32;
     const int tiles = (g.G * Q + BM - 1) / BM;
-    const int n_split = attn_splits(g, Q);
+    const int n_split = attn_splits(g, Q, b.opt_attn_splits);
     const dim3 grid(tiles * g.B * g.Hkv * n_split), block(kSWaves * 64);
     if (n_split > 1) {
         float* part_o = b.attn_part;
@@ -671,8 +670,8 @@ void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, i
         }
         return;
     }
-    static const char* dbg_env = getenv("CASCADE_KV_ATTN_DEBUG");
-    if (dbg_env && g.d == 128) {   // phase timing of one workgroup (development aid)
+#ifdef CASCADE_KV_ATTN_PHASE_TIMING   // development builds only: per-phase cycle counts of one workgroup
+    if (g.d == 128) {
         long long* dbg = (long long*)b.logits;
         hipLaunchKernelGGL((attn_stream_kernel<128, true, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
                            (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, dbg, 1, (float*)nullptr, (float*)nullptr, b.knorm2, so);
@@ -685,6 +684,7 @@ void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, i
                        h[w * 8 + 1] / h[w * 8 + 5], h[w * 8 + 2] / h[w * 8 + 5], h[w * 8 + 3] / h[w * 8 + 5], h[w * 8 + 4] / h[w * 8 + 5]);
         return;
     }
+#endif
     if (g.d == 128)
         hipLaunchKernelGGL((attn_stream_kernel<128, false, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
                            (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, 1, (float*)nullptr, (float*)nullptr, b.knorm2, so);

@@ -91,8 +91,8 @@ __global__ void load_state_kernel(Geom g, FillCounts fc, int total, T* __restric
     const float2 cs = rope[(size_t)slot * half + e];
     Elem<T>::store(Kc + dst + e, x0);
     Elem<T>::store(Kc + dst + e + half, x1);
-    Elem<T>::store(Kr + dst + e, x0 * cs.x - x1 * cs.y);
-    Elem<T>::store(Kr + dst + e + half, x1 * cs.x + x0 * cs.y);
+    Elem<T>::store(Kr + dst + e, rot_lo(x0, x1, cs.x, cs.y));
+    Elem<T>::store(Kr + dst + e + half, rot_hi(x0, x1, cs.x, cs.y));
     Vc[dst + e] = v_in[src + e];
     Vc[dst + e + half] = v_in[src + e + half];
     if (e == 0) {
@@ -163,8 +163,8 @@ __device__ inline void rotate8(const float* x0, const float* x1, const float2* _
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const float2 c = cs[i];
-        y0[i] = x0[i] * c.x - x1[i] * c.y;
-        y1[i] = x1[i] * c.x + x0[i] * c.y;
+        y0[i] = rot_lo(x0[i], x1[i], c.x, c.y);
+        y1[i] = rot_hi(x0[i], x1[i], c.x, c.y);
     }
     Vec8<T>::store(d0, y0);
     Vec8<T>::store(d1, y1);
@@ -239,8 +239,8 @@ __global__ void prep_pair_kernel(Geom g, SegList sl, int Q, float qscale, int q_
         const size_t dst = ((((size_t)vq * g.B + b) * g.Hq + h) * Q + i) * g.d;
         const float x0 = qscale * Elem<T>::load(q + src + e), x1 = qscale * Elem<T>::load(q + src + e + half);
         const float2 cs = rope[(size_t)(sl.qrot0[vq] + i) * half + e];
-        Elem<T>::store(Qr + dst + e, x0 * cs.x - x1 * cs.y);
-        Elem<T>::store(Qr + dst + e + half, x1 * cs.x + x0 * cs.y);
+        Elem<T>::store(Qr + dst + e, rot_lo(x0, x1, cs.x, cs.y));
+        Elem<T>::store(Qr + dst + e + half, rot_hi(x0, x1, cs.x, cs.y));
     } else {
         const int rr = row - sl.n_qvar * g.Hq;
         const int h = rr % g.Hkv;
@@ -249,8 +249,8 @@ __global__ void prep_pair_kernel(Geom g, SegList sl, int Q, float qscale, int q_
         if (rr < g.Hkv) {
             const float x0 = Elem<T>::load(k + src + e), x1 = Elem<T>::load(k + src + e + half);
             const float2 cs = rope[(size_t)i * half + e];
-            Elem<T>::store(Krc + dst + e, x0 * cs.x - x1 * cs.y);
-            Elem<T>::store(Krc + dst + e + half, x1 * cs.x + x0 * cs.y);
+            Elem<T>::store(Krc + dst + e, rot_lo(x0, x1, cs.x, cs.y));
+            Elem<T>::store(Krc + dst + e + half, rot_hi(x0, x1, cs.x, cs.y));
         } else {
             Vch[dst + e] = v[src + e];
             Vch[dst + e + half] = v[src + e + half];
@@ -281,6 +281,34 @@ void launch_prep(const Geom& g, int dtype, const DevBuffers& b, const SegList& s
     else
         hipLaunchKernelGGL(prep_pair_kernel<bf16_t>, grid, block, 0, s, g, sl, Q, qscale, q_first_row, b.rope, (const bf16_t*)q,
                            (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)b.Qr, (bf16_t*)b.Krc, (bf16_t*)b.Vch);
+}
+
+// ------------------------------------------------------------------ homogeneous heads
+
+// Appendix "Head Policy and Head Reduction", homogeneous heads: one score per token for all heads.
+// The score kernels have reduced the query heads of every KV head; here the KV heads are reduced
+// in turn (max of maxima; mean of means, the groups being equally large) and every KV head gets
+// the result.  All KV heads then hold the same tokens in the same slots, so the reduction runs
+// slot by slot.  For the cached rows the reduction of the updated scores is the update with the
+// reduced increments: before the call the scores of a slot are equal in all heads.
+__global__ void share_scores_kernel(Geom g, int n_new, int qstride, float* __restrict__ mu, float* __restrict__ mu_chunk)
+{
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long per_b = (long)g.slots + n_new;
+    if (idx >= per_b * g.B) return;
+    const int b = (int)(idx / per_b), j = (int)(idx % per_b);
+    float* p = j < g.slots ? mu + (size_t)b * g.Hkv * g.slots + j : mu_chunk + (size_t)b * g.Hkv * qstride + (j - g.slots);
+    const size_t stride = j < g.slots ? (size_t)g.slots : (size_t)qstride;
+    float r = p[0];
+    for (int h = 1; h < g.Hkv; ++h) r = g.head_reduce == CASCADE_REDUCE_MAX ? fmaxf(r, p[h * stride]) : r + p[h * stride];
+    if (g.head_reduce == CASCADE_REDUCE_MEAN) r /= (float)g.Hkv;
+    for (int h = 0; h < g.Hkv; ++h) p[h * stride] = r;
+}
+
+void launch_share_scores(const Geom& g, const DevBuffers& b, int n_new, int max_chunk, hipStream_t s)
+{
+    const long n = ((long)g.slots + n_new) * g.B;
+    hipLaunchKernelGGL(share_scores_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, g, n_new, max_chunk, b.mu, b.mu_chunk);
 }
 
 // ------------------------------------------------------------------ cascade update: who ends up where
@@ -380,8 +408,8 @@ __global__ void move_kernel(Geom g, UpdatePlan pl, int c, int E, int extra, int 
         const float2 cs2 = rope[(size_t)dst * half + p];
         Elem<T>::store(Kc + drow + p, x0);
         Elem<T>::store(Kc + drow + p + half, x1);
-        Elem<T>::store(Kr + drow + p, x0 * cs2.x - x1 * cs2.y);
-        Elem<T>::store(Kr + drow + p + half, x1 * cs2.x + x0 * cs2.y);
+        Elem<T>::store(Kr + drow + p, rot_lo(x0, x1, cs2.x, cs2.y));
+        Elem<T>::store(Kr + drow + p + half, rot_hi(x0, x1, cs2.x, cs2.y));
         Vc[drow + p] = vs[p];
         Vc[drow + p + half] = vs[p + half];
     }

@@ -510,14 +510,22 @@ __global__ void decode_finish_kernel(Geom g, UpdatePlan pl, UpdateBuffers upd, i
         Elem<T>::store(out + ((size_t)b * g.Hq + h) * g.d + e, s);
     }
     if (threadIdx.x == 0) {
-        float red = 0.f;
-        for (int hh = 0; hh < g.G; ++hh) {
-            const int h = hk * g.G + hh;
-            const float p = __expf(logits[logit_index(g, maxg, lrows, b, hk, n_cached, hh)] - lse[(size_t)b * g.Hq + h]);
-            red = (g.head_reduce == CASCADE_REDUCE_MAX) ? fmaxf(red, p) : red + p;
+        // independent heads: the query heads of this KV head; homogeneous heads: all query heads (every
+        // workgroup of the sequence computes the same value, group by group in the same order)
+        const bool all = g.head_policy == CASCADE_HEADS_HOMOGENEOUS;
+        float total = 0.f;
+        for (int k2 = all ? 0 : hk; k2 < (all ? g.Hkv : hk + 1); ++k2) {
+            float red = 0.f;
+            for (int hh = 0; hh < g.G; ++hh) {
+                const int h = k2 * g.G + hh;
+                const float p = __expf(logits[logit_index(g, maxg, lrows, b, k2, n_cached, hh)] - lse[(size_t)b * g.Hq + h]);
+                red = (g.head_reduce == CASCADE_REDUCE_MAX) ? fmaxf(red, p) : red + p;
+            }
+            if (g.head_reduce == CASCADE_REDUCE_MEAN) red /= (float)g.G;
+            total = (g.head_reduce == CASCADE_REDUCE_MAX) ? fmaxf(total, red) : total + red;
         }
-        if (g.head_reduce == CASCADE_REDUCE_MEAN) red /= (float)g.G;
-        mu_chunk[((size_t)b * g.Hkv + hk) * qstride] = (1.f - g.beta) * red;
+        if (all && g.head_reduce == CASCADE_REDUCE_MEAN) total /= (float)g.Hkv;
+        mu_chunk[((size_t)b * g.Hkv + hk) * qstride] = (1.f - g.beta) * total;
     }
     __syncthreads();   // the token's score is written
     small_update<T>(g, pl, qstride, upd, b, hk);
@@ -1020,7 +1028,7 @@ void launch_decode_qk(const Geom& g, int dtype, const DevBuffers& b, const SegLi
     if (dtype == CASCADE_BF16) {
         const dim3 grid(b.dec_splits, g.Hkv, g.B), block(kDecThreads);
         const int ps = per_split_of(b, sl.n_cached);
-        static const bool direct_only = getenv("CASCADE_KV_DECODE_QK_DIRECT") != nullptr;
+        const bool direct_only = b.opt_decode_qk_direct != 0;
         const int mg = maxg_of(g);
         const int rotations = 96 / mg < kMaxQueryRotations ? 96 / mg : kMaxQueryRotations;
         // the streaming kernel keeps every rotation of the queries in LDS
@@ -1047,7 +1055,7 @@ void launch_decode_qk(const Geom& g, int dtype, const DevBuffers& b, const SegLi
 
 void launch_decode_pv(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, hipStream_t s)
 {
-    static const bool valu_only = getenv("CASCADE_KV_DECODE_PV_VALU") != nullptr;
+    const bool valu_only = b.opt_decode_pv_valu != 0;
     if (dtype == CASCADE_BF16 && !valu_only) {
         const dim3 grid(b.dec_splits, g.Hkv, g.B), block(kDecThreads);
         const int ps = per_split_of(b, sl.n_cached);

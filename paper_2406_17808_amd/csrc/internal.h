@@ -31,6 +31,14 @@ __host__ __device__ inline bf16_t f32_to_bf16(float f)   // round to nearest eve
     return (bf16_t)(c.u >> 16);
 }
 
+// One rotary pair (x0, x1) turned by the angle whose cosine and sine are c and s, with the
+// roundings spelled out: one rounded product, then one fused multiply-add.  Every kernel that
+// rotates a key or a query that will be rounded to bf16 goes through here, so that all of them, and
+// a reference that wants to reproduce those bf16 values bit for bit, round alike whatever the
+// compiler would have contracted.
+__host__ __device__ inline float rot_lo(float x0, float x1, float c, float s) { return __builtin_fmaf(x0, c, -(x1 * s)); }
+__host__ __device__ inline float rot_hi(float x0, float x1, float c, float s) { return __builtin_fmaf(x1, c, x0 * s); }
+
 template <typename T> struct Elem;
 template <> struct Elem<float> {
     __host__ __device__ static float load(const float* p) { return *p; }
@@ -49,7 +57,7 @@ struct Geom {
     int cap[kMaxCascades];     // cascade c (0-based; 0 = first cascade)
     int base[kMaxCascades];    // first physical slot of cascade c
     int period[kMaxCascades];
-    int token_selection, head_reduce;
+    int token_selection, head_reduce, head_policy;
     float beta, scale;
 };
 

@@ -44,6 +44,12 @@ struct DevBuffers {
     int rope_rows;
     int dec_splits;
     int vt_tiles;    // capacity of Kt and Vt per (batch, KV head)
+    // development switches (tests, A/B timing), read from the environment ONCE, when the context is
+    // created; no launch looks at the environment
+    int opt_attn_splits;       // CASCADE_KV_ATTN_SPLITS: workgroups per row block of a small attention launch; 0 = automatic
+    int opt_score_narrow;      // CASCADE_KV_SCORE_NARROW: 0 / 1 force the 64- / 32-key form of the score kernel; -1 = automatic
+    int opt_decode_qk_direct;  // CASCADE_KV_DECODE_QK_DIRECT: bf16 decode logits by the register-load kernel
+    int opt_decode_pv_valu;    // CASCADE_KV_DECODE_PV_VALU: bf16 decode outputs by the VALU kernel
 };
 
 // tables
@@ -57,6 +63,8 @@ void launch_load_state(const Geom& g, int dtype, const DevBuffers& b, const void
 // q_first_row: the rotated query copies are written for chunk rows q_first_row .. Q-1 only
 void launch_prep(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int Q, float qscale, int q_first_row,
                  const void* q, const void* k, const void* v, hipStream_t s);
+// homogeneous heads: the scores of the cached rows (and of n_new new tokens) reduced over the KV heads and shared
+void launch_share_scores(const Geom& g, const DevBuffers& b, int n_new, int max_chunk, hipStream_t s);
 void launch_plan(const Geom& g, const DevBuffers& b, const UpdatePlan& pl, int max_chunk, hipStream_t s);
 void launch_moves(const Geom& g, int dtype, const DevBuffers& b, const UpdatePlan& pl, int max_chunk,
                   const void* k, const void* v, int k_token_stride, int k_batch_stride, hipStream_t s);

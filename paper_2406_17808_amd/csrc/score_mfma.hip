@@ -221,8 +221,7 @@ void launch_score_mfma(const Geom& g, const DevBuffers& b, const SegList& sl, in
     };
     // 256 keys per workgroup unless that leaves a good part of the 256 x 3 workgroup slots empty
     bool narrow = workgroups(2 * kScoreKeysPerBlock) < 600;
-    const char* forced = getenv("CASCADE_KV_SCORE_NARROW");   // debug switch (tests, A/B timing), read at every launch: 0 or 1
-    if (forced) narrow = forced[0] == '1';
+    if (b.opt_score_narrow >= 0) narrow = b.opt_score_narrow == 1;
     const dim3 grid(workgroups(narrow ? kScoreKeysPerBlock : 2 * kScoreKeysPerBlock)), block(kScoreThreads);
     const int qpad = max_chunk + kStRows;   // the attention launch left the offsets of this chunk's rows in b.negt
 #define CKV_SCORE(D, NKB)                                                                                              \

@@ -89,8 +89,8 @@ __device__ inline void small_update(const Geom& g, const UpdatePlan& pl, int qst
                 const float2 cs2 = rope[(size_t)dst * half + p];
                 Elem<T>::store(Kc + drow + p, x0);
                 Elem<T>::store(Kc + drow + p + half, x1);
-                Elem<T>::store(Kr + drow + p, x0 * cs2.x - x1 * cs2.y);
-                Elem<T>::store(Kr + drow + p + half, x1 * cs2.x + x0 * cs2.y);
+                Elem<T>::store(Kr + drow + p, rot_lo(x0, x1, cs2.x, cs2.y));
+                Elem<T>::store(Kr + drow + p + half, rot_hi(x0, x1, cs2.x, cs2.y));
                 Vc[drow + p] = vs[p];
                 Vc[drow + p + half] = vs[p + half];
             }

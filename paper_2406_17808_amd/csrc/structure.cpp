@@ -39,6 +39,9 @@ int check_config(const cascade_config* c, std::string& why)
     if (c->max_chunk < 1) { why = "max_chunk must be >= 1"; return CASCADE_E_INVALID_CONFIG; }
     if (c->head_reduce != CASCADE_REDUCE_MAX && c->head_reduce != CASCADE_REDUCE_MEAN) { why = "unknown head_reduce"; return CASCADE_E_INVALID_CONFIG; }
     if (c->token_selection != 0 && c->token_selection != 1) { why = "token_selection must be 0 or 1"; return CASCADE_E_INVALID_CONFIG; }
+    if (c->head_policy != CASCADE_HEADS_INDEPENDENT && c->head_policy != CASCADE_HEADS_HOMOGENEOUS) { why = "unknown head_policy"; return CASCADE_E_INVALID_CONFIG; }
+    if (c->score_mode != CASCADE_SCORES_EXACT && c->score_mode != CASCADE_SCORES_SINGLE_PASS) { why = "unknown score_mode"; return CASCADE_E_INVALID_CONFIG; }
+    if (c->score_mode == CASCADE_SCORES_SINGLE_PASS) { why = "score_mode CASCADE_SCORES_SINGLE_PASS is not available"; return CASCADE_E_UNSUPPORTED; }
     long slots = c->n_sink;
     for (int i = 0; i < c->n_cascades; ++i) slots += c->cascade_sizes[i];
     if (slots > (1L << 28)) { why = "cache too large"; return CASCADE_E_INVALID_CONFIG; }
@@ -65,6 +68,7 @@ void make_geom(const cascade_config* c, Geom& g)
     for (int i = g.N - 1; i >= 0; --i) { g.base[i] = base; base += g.cap[i]; }
     g.token_selection = c->token_selection;
     g.head_reduce = c->head_reduce;
+    g.head_policy = c->head_policy;
     g.beta = c->ema_beta;
     g.scale = c->softmax_scale > 0.f ? c->softmax_scale : (float)(1.0 / sqrt((double)g.d));
 }

@@ -40,12 +40,20 @@ def _table(index, d, base):
 
 
 def _rotate_f32(x, index, d, base):
-    """Pairs (x_i, x_{i+d/2}) rotated by index * theta_i, in float32 arithmetic."""
+    """Pairs (x_i, x_{i+d/2}) rotated by index * theta_i in float32 arithmetic with the roundings of
+    the bf16 contract: lo = fma(x0, c, -(x1 * s)), hi = fma(x1, c, x0 * s): one product rounded to
+    float32, then a fused multiply-add (the exact product of two float32 values fits a float64; the
+    sum is rounded to float64 and then to float32, which differs from a single rounding only in
+    ties of probability 2^-29)."""
     half = d // 2
     c, s = _table(index, d, base)
     x = np.asarray(x, dtype=np.float32)
     x0, x1 = x[..., :half], x[..., half:]
-    return np.concatenate([x0 * c - x1 * s, x1 * c + x0 * s], axis=-1).astype(np.float32)
+    t_lo = (x1 * s).astype(np.float32).astype(np.float64)
+    t_hi = (x0 * s).astype(np.float32).astype(np.float64)
+    lo = (x0.astype(np.float64) * c.astype(np.float64) - t_lo).astype(np.float32)
+    hi = (x1.astype(np.float64) * c.astype(np.float64) + t_hi).astype(np.float32)
+    return np.concatenate([lo, hi], axis=-1)
 
 
 def chunk_reference(q, k_chunk, v_chunk, k_cache, v_cache, slot, rows, rope_base, softmax_scale=0.0,

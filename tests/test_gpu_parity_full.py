@@ -230,7 +230,7 @@ def _compare_sampled_rows_1m(run, wl, c, dq, dk, dv, heads, with_model):
     threads = [threading.Thread(target=work, args=(g,)) for g in heads]
     [t.start() for t in threads]
     [t.join() for t in threads]
-    worst = dict(ordinary=0.0, last64=0.0, score=0.0, model_out=0.0, model_score=0.0, detail={})
+    worst = dict(early=0.0, tail=0.0, last64=0.0, score=0.0, model_out=0.0, model_score=0.0, detail={})
     rep = StepReport()
     npre = pre.count
     beta = float(np.float32(cfg.ema_beta))
@@ -241,7 +241,7 @@ def _compare_sampled_rows_1m(run, wl, c, dq, dk, dv, heads, with_model):
                                 ("tail rows", tail_out, slice(Q - T, Q - 64)), ("last 64 rows", tail_out, slice(Q - 64, Q))):
             err = row_errors(out[rows], ref[rows], hq)
             print(f"  chunk {c} head {g} {name}: out err {err:.3e}", flush=True)
-            key = "last64" if name == "last 64 rows" else "ordinary"
+            key = {"last 64 rows": "last64", "tail rows": "tail"}.get(name, "early")
             worst[key] = max(worst[key], err)
         # beta^4096 wipes the old scores; the tail rows give the new ones up to beta^300
         mu_gpu = gpu_decision_scores(st, 0, g, npre, Q)
@@ -284,11 +284,14 @@ def _run_1m(heads):
     return wl, cfg, run
 
 
-# Against the bf16 rounding model (bf16_model.py) what is left is the rounding of the output to
-# bf16 (relative 2^-9 per element, so at most 2^-9 in the L2 norm of a row) and of a probability
-# at another power-of-two phase than the kernel's (two independent 2^-9 roundings: sqrt(2) 2^-9),
-# together below 4.8e-3; scores involve neither (fp32 sums of fp32 probabilities).
-TOL_MODEL_OUT, TOL_MODEL_SCORE = 5e-3, 2e-3
+# Against the bf16 rounding model (bf16_model.py) what is left in an output row is its own rounding
+# to bf16 (relative 2^-9 per element) and the rounding of every probability at another
+# power-of-two phase than the kernel's (two independent roundings of 2^-9 each); as relative L2
+# errors of a row these are about 1.1e-3 and 1.6e-3 on average, and the largest of some thousand
+# rows of 64 to 128 elements stays below 2^-7.  Scores involve neither rounding (fp32 sums of fp32
+# probabilities of the same bf16 operands): they agree to fp32 accuracy, 2^-12 with room for the
+# sums of up to 70000 keys behind every normaliser.
+TOL_MODEL_OUT, TOL_MODEL_SCORE = 2.0 ** -7, 2.0 ** -12
 
 
 def test_prefill_1m_chunks_where_cascades_first_fill(oracle_mod):
@@ -305,7 +308,7 @@ def test_prefill_1m_chunks_where_cascades_first_fill(oracle_mod):
             run.advance_gpu_only(dq, dk, dv, record=False)
             continue
         worst, st = _compare_sampled_rows_1m(run, wl, c, dq, dk, dv, heads, with_model=False)
-        worst_out = max(worst_out, worst["ordinary"], worst["last64"])
+        worst_out = max(worst_out, worst["early"], worst["tail"], worst["last64"])
         worst_score = max(worst_score, worst["score"])
     print(f"prefill_1m first fills: out {worst_out:.3e} score {worst_score:.3e}")
     assert worst_out <= TOL_OUT and worst_score <= TOL_SCORE
@@ -330,18 +333,22 @@ def test_prefill_1m_sampled_rows_and_planted_key(oracle_mod):
     c_plant = p // wl.chunk
     compare = {40, c_plant, wl.n_chunks - 1}
     Q = wl.chunk
+    assert p % Q < Q - 300      # the sampled tail rows of its chunk all come after the planted key
     worst_out = worst_score = worst_planted = worst_model_out = worst_model_score = 0.0
     last = None
     for c in range(wl.n_chunks):
         dq, dk, dv = chunk_inputs_torch(wl, 0, c, "cuda:0")
         if c in compare:
-            worst, st = _compare_sampled_rows_1m(run, wl, c, dq, dk, dv, heads, with_model=(c == wl.n_chunks - 1))
-            if c == wl.n_chunks - 1:
-                worst_planted, last = worst["ordinary"], worst
+            worst, st = _compare_sampled_rows_1m(run, wl, c, dq, dk, dv, heads, with_model=(c in (c_plant, wl.n_chunks - 1)))
+            if c == wl.n_chunks - 1:       # ordinary rows see the planted key in the cache; the last 64 are aligned with it
+                worst_planted, last = max(worst_planted, worst["early"], worst["tail"]), worst
                 worst_out = max(worst_out, worst["last64"])
-                worst_model_out, worst_model_score = worst["model_out"], worst["model_score"]
+            elif c == c_plant:             # the rows behind the planted key see it in their own chunk
+                worst_planted = max(worst_planted, worst["tail"], worst["last64"])
+                worst_out = max(worst_out, worst["early"])
             else:
-                worst_out = max(worst_out, worst["ordinary"], worst["last64"])
+                worst_out = max(worst_out, worst["early"], worst["tail"], worst["last64"])
+            worst_model_out, worst_model_score = max(worst_model_out, worst["model_out"]), max(worst_model_score, worst["model_score"])
             worst_score = max(worst_score, worst["score"])
         elif c > c_plant:
             # every update the planted key lives through: replayed with the library's own scores
@@ -353,16 +360,16 @@ def test_prefill_1m_sampled_rows_and_planted_key(oracle_mod):
             run.prev = st
         else:
             run.advance_gpu_only(dq, dk, dv, record=False)
-    print(f"prefill_1m: out {worst_out:.3e} (ordinary rows of the last chunk {worst_planted:.3e}; against the bf16 rounding "
+    print(f"prefill_1m: out {worst_out:.3e} (ordinary rows that see the planted key {worst_planted:.3e}; against the bf16 rounding "
           f"model: out {worst_model_out:.3e} score {worst_model_score:.3e}) score {worst_score:.3e}")
     assert worst_out <= TOL_OUT and worst_score <= TOL_SCORE
-    # In the last chunk the cache holds the planted key, whose norm is 4x that of every other key.
-    # The rounding of the rotated bf16 operands perturbs a logit in proportion to |q||k|, so for
-    # ordinary queries that put a few percent of their mass on that key the error against ideal
-    # arithmetic is up to 4x the usual one.  That this is the contract's operand rounding and nothing
-    # else is what the comparison with the rounding model shows, on the same rows, at a bound 4x
-    # tighter than the plain tolerance.  The rows this workload is about, the last 64 queries
-    # aligned with the key, are held to the plain tolerance above.
+    # The planted key has 4x the norm of every other key.  The rounding of the rotated bf16 operands
+    # perturbs a logit in proportion to |q||k|, so for ordinary queries that see that key (the rows
+    # behind it in its own chunk; every row of the last chunk, where it is in the cache) and put a
+    # few percent of their mass on it the error against ideal arithmetic is up to 4x the usual one.
+    # That this is the contract's operand rounding and nothing else is what the comparison with the
+    # rounding model shows, on the same rows, at the bound derived above.  The rows this workload is
+    # about, the last 64 queries aligned with the key, are held to the plain tolerance.
     assert worst_planted <= 4 * TOL_OUT
     assert worst_model_out <= TOL_MODEL_OUT and worst_model_score <= TOL_MODEL_SCORE
     final = run.gpu.read_state()
