@@ -263,6 +263,10 @@ typedef struct cascade_profile {
     int64_t intervals[CASCADE_K_FAMILIES];
 } cascade_profile;
 int cascade_profile_begin(cascade_ctx* ctx);
+/* The same for the families whose bit (1 << CASCADE_K_*) is set in family_mask only: two events on the
+ * stream between two kernels cost about ten microseconds of idle time, which a timed run should
+ * not pay for families it does not report. */
+int cascade_profile_begin_families(cascade_ctx* ctx, uint32_t family_mask);
 int cascade_profile_end(cascade_ctx* ctx, cascade_profile* out);
 
 /*

@@ -36,7 +36,7 @@ EXPORTED_SYMBOLS = [
     "cascade_workspace_bytes", "cascade_init", "cascade_destroy", "cascade_prefill_chunk",
     "cascade_decode_step", "cascade_read_state", "cascade_simulate_structure", "cascade_last_error",
     "cascade_profile_begin", "cascade_profile_end", "cascade_layers_workspace_bytes", "cascade_init_layers",
-    "cascade_init_static", "cascade_measure_ceilings",
+    "cascade_init_static", "cascade_measure_ceilings", "cascade_profile_begin_families",
 ]
 CASCADE_STATIC_WORKSPACE_BYTES = 64 << 20
 
@@ -135,6 +135,8 @@ def load_library():
                                                  ctypes.POINTER(cascade_state_view)]
         L.cascade_profile_begin.restype = ctypes.c_int
         L.cascade_profile_begin.argtypes = [P]
+        L.cascade_profile_begin_families.restype = ctypes.c_int
+        L.cascade_profile_begin_families.argtypes = [P, ctypes.c_uint32]
         L.cascade_profile_end.restype = ctypes.c_int
         L.cascade_profile_end.argtypes = [P, ctypes.POINTER(cascade_profile)]
         L.cascade_measure_ceilings.restype = ctypes.c_int
@@ -229,8 +231,13 @@ def cascade_decode_step(ctx, dev_q: int, dev_k: int, dev_v: int, dev_out: int, s
     _check(load_library().cascade_decode_step(ctx, dev_q, dev_k, dev_v, dev_out, stream), ctx)
 
 
-def cascade_profile_begin(ctx) -> None:
-    _check(load_library().cascade_profile_begin(ctx), ctx)
+def cascade_profile_begin(ctx, families=None) -> None:
+    """families: names from KERNEL_FAMILIES to put events around (None: all of them)."""
+    if families is None:
+        _check(load_library().cascade_profile_begin(ctx), ctx)
+    else:
+        mask = sum(1 << KERNEL_FAMILIES.index(f) for f in families)
+        _check(load_library().cascade_profile_begin_families(ctx, mask), ctx)
 
 
 def cascade_profile_end(ctx) -> dict:

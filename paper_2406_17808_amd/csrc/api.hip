@@ -35,6 +35,7 @@ struct cascade_ctx {
     PackedLayout packed;
     TileRuns stale;
     bool profiling = false;
+    uint32_t prof_mask = ~0u;   // kernel families that get events while profiling
     bool is_static = false;   // one of the per-device contexts of cascade_init_static: never deleted
     bool poisoned = false;    // a launch of an earlier call failed: the device state is undefined
     std::vector<std::pair<hipEvent_t, hipEvent_t>> prof[CASCADE_K_FAMILIES];
@@ -49,7 +50,7 @@ struct Timed {
     hipEvent_t stop = nullptr;
     Timed(cascade_ctx* c, int f, hipStream_t st) : ctx(c), fam(f), s(st)
     {
-        if (!ctx->profiling) return;
+        if (!ctx->profiling || !(ctx->prof_mask >> fam & 1u)) return;
         hipEvent_t start;
         if (hipEventCreate(&start) != hipSuccess || hipEventCreate(&stop) != hipSuccess) { stop = nullptr; return; }
         (void)hipEventRecord(start, s);
@@ -219,6 +220,7 @@ static int init_context(const char* who, const cascade_config* cfg, const Geom& 
     if (const char* e = getenv("CASCADE_KV_SCORE_NARROW")) ctx->buf.opt_score_narrow = e[0] == '1' ? 1 : 0;
     ctx->buf.opt_decode_qk_direct = getenv("CASCADE_KV_DECODE_QK_DIRECT") != nullptr;
     ctx->buf.opt_decode_pv_valu = getenv("CASCADE_KV_DECODE_PV_VALU") != nullptr;
+    ctx->buf.opt_update_staged = getenv("CASCADE_KV_UPDATE_STAGED") != nullptr;
 
     // rows of a chunk whose EMA weight beta^k has not dropped below the cut
     {
@@ -397,13 +399,16 @@ extern "C" int cascade_init_static(const cascade_config* cfg, const cascade_init
     return init_context("cascade_init_static", cfg, g, base, base + need.state, true, init_state, st, total, s, out_ctx, ctx);
 }
 
-extern "C" int cascade_profile_begin(cascade_ctx* ctx)
+extern "C" int cascade_profile_begin_families(cascade_ctx* ctx, uint32_t family_mask)
 {
     if (!ctx) return CASCADE_E_NULL_ARG;
     drop_events(ctx);
     ctx->profiling = true;
+    ctx->prof_mask = family_mask;
     return CASCADE_OK;
 }
+
+extern "C" int cascade_profile_begin(cascade_ctx* ctx) { return cascade_profile_begin_families(ctx, ~0u); }
 
 extern "C" int cascade_profile_end(cascade_ctx* ctx, cascade_profile* out)
 {
@@ -507,8 +512,9 @@ extern "C" int cascade_prefill_chunk(cascade_ctx* ctx, const void* dev_q, const 
     plan_update(g, st_next, Q, pl);
     {
         Timed t(ctx, CASCADE_K_UPDATE, s);
-        launch_plan(g, ctx->buf, pl, ctx->max_chunk, s);
-        launch_moves(g, ctx->dtype, ctx->buf, pl, ctx->max_chunk, dev_k, dev_v, g.Hkv * g.d, Q * g.Hkv * g.d, s);
+        const bool direct = update_is_direct(g, ctx->buf, pl);
+        if (!direct) launch_plan(g, ctx->buf, pl, ctx->max_chunk, s);
+        launch_moves(g, ctx->dtype, ctx->buf, pl, ctx->max_chunk, dev_k, dev_v, g.Hkv * g.d, Q * g.Hkv * g.d, direct, s);
     }
     const int rc_launch = hip_check(ctx, hipGetLastError(), "cascade_prefill_chunk");
     if (rc_launch != CASCADE_OK) {    // some launches may have run: host and device no longer agree

@@ -429,8 +429,10 @@ struct MoveList {
     int c[kMaxCascades + 1], first[kMaxCascades + 2], E[kMaxCascades + 1], extra[kMaxCascades + 1];
 };
 
+// direct: the plan is direct (plan_is_direct) and nobody has written the winners of the FIRST
+// cascade: every token is accepted there (period 1), so a slot it opens takes the offer that opens it
 __device__ inline bool move_entry(const Geom& g, const UpdatePlan& pl, const MoveList& ml, int eg, int bh, int qstride,
-                                  const int32_t* __restrict__ winners, int* dst, int* ref)
+                                  const int32_t* __restrict__ winners, int* dst, int* ref, bool direct = false)
 {
     int i = 0;
     while (i + 1 < ml.n && eg >= ml.first[i + 1]) ++i;
@@ -438,6 +440,12 @@ __device__ inline bool move_entry(const Geom& g, const UpdatePlan& pl, const Mov
     if (c < 0) {
         *dst = pl.sink_fill0 + e;
         *ref = g.slots + e;
+        return true;
+    }
+    if (direct && c == 0) {              // J < cap: entry e is slot j = e; no offer competes in the first cascade
+        const CascStep& cs = pl.c[0];
+        *dst = cs.base + (cs.wpos0 + e) % cs.cap;
+        *ref = offer_ref_direct(pl, 0, e < cs.A ? e : cs.kp0 + (e - cs.A) * cs.pstride, g.slots);
         return true;
     }
     const int32_t* W = winners + ((size_t)bh * pl.N + c) * (qstride + 1);
@@ -478,7 +486,7 @@ __global__ void scatter_kernel(Geom g, UpdatePlan pl, MoveList ml, int qstride, 
                                const int32_t* __restrict__ stId, const float* __restrict__ mu_chunk,
                                const T* __restrict__ k_in, const T* __restrict__ v_in, long tok_stride, long batch_stride,
                                T* __restrict__ Kc, T* __restrict__ Kr, T* __restrict__ Vc, float* __restrict__ mu,
-                               int32_t* __restrict__ ids)
+                               int32_t* __restrict__ ids, bool direct)
 {
     const int lanes = g.d / 16, half = g.d / 2;
     const int bh = blockIdx.y;
@@ -487,7 +495,7 @@ __global__ void scatter_kernel(Geom g, UpdatePlan pl, MoveList ml, int qstride, 
     const int lane = threadIdx.x % lanes;
     if (eg >= ml.total) return;
     int dst, ref;
-    if (!move_entry(g, pl, ml, eg, bh, qstride, winners, &dst, &ref)) return;
+    if (!move_entry(g, pl, ml, eg, bh, qstride, winners, &dst, &ref, direct)) return;
     const T *ks, *vs;
     float score;
     int id;
@@ -523,9 +531,120 @@ __global__ void scatter_kernel(Geom g, UpdatePlan pl, MoveList ml, int qstride, 
     }
 }
 
+// gather_kernel for updates whose plan is direct (plan_is_direct): the thread group of an entry
+// decides its segment itself (the offers are named from the structure alone), leaves the winner
+// in `winners` for scatter_kernel, counts the replacements, and stages the winner if it is a cache
+// row.  No plan_kernel launch, no cascade-by-cascade dependency.  Only the cascades beyond the
+// first have anything to decide or to stage (the first takes the chunk's tokens as they come):
+// the launch covers their entries only, n_entries of them.
+template <typename T>
+__global__ void gather_direct_kernel(Geom g, UpdatePlan pl, MoveList ml, int n_entries, int qstride, int stage_rows,
+                                     int32_t* __restrict__ winners, int32_t* __restrict__ swaps,
+                                     const float* __restrict__ mu_chunk, const T* __restrict__ Kc, const T* __restrict__ Vc,
+                                     const float* __restrict__ mu, const int32_t* __restrict__ ids,
+                                     T* __restrict__ stK, T* __restrict__ stV, float* __restrict__ stMu, int32_t* __restrict__ stId)
+{
+    __shared__ int wg_swaps[kMaxCascades];   // replacements counted by this workgroup, per cascade
+    const int lanes = g.d / 16, half = g.d / 2;
+    const int bh = blockIdx.y;
+    const int eg = blockIdx.x * (blockDim.x / lanes) + threadIdx.x / lanes;
+    const int lane = threadIdx.x % lanes;
+    if (threadIdx.x < kMaxCascades) wg_swaps[threadIdx.x] = 0;
+    __syncthreads();
+    int c = -1, j = 0, ref = 0, dst = 0;
+    bool move = false;
+    if (eg < n_entries) {                // the entries of the cascades beyond the first come first in the list
+        int i = 0;
+        while (i + 1 < ml.n && eg >= ml.first[i + 1]) ++i;
+        c = ml.c[i];
+        {
+            const CascStep& cs = pl.c[c];
+            // entry e < E is slot j = e of the J < cap slots opened (final_entry); entry E is the segment of
+            // the item that was newest before the update
+            const int e = eg - ml.first[i];
+            j = e < ml.E[i] ? e : -1;
+            dst = j < 0 ? cs.base + cs.newest0 : cs.base + (cs.wpos0 + j) % cs.cap;
+        }
+    }
+    // The segment of every entry, decided by the `lanes` threads of its group together: the same
+    // first-maximum rule as segment_winner (a later offer replaces the holder only on a strictly
+    // higher score), with the scores of `lanes` offers loaded at a time instead of one after the other.
+    {
+        const int lead = (threadIdx.x & 63) - lane;          // first lane of this group inside the wave
+        int kb = 0, ke = 0, sw = 0;
+        float bs = 0.f;
+        const float* mub = mu + (size_t)bh * g.slots;
+        const float* muc = mu_chunk + (size_t)bh * qstride;
+        if (c >= 0) {
+            const CascStep& cs = pl.c[c];
+            if (j < 0) {
+                ref = cs.base + cs.newest0;
+                kb = 0;
+                ke = cs.kp0 < cs.M ? cs.kp0 : cs.M;
+            } else {
+                const int kh = j < cs.A ? j : cs.kp0 + (j - cs.A) * cs.pstride;
+                ref = offer_ref_direct(pl, c, kh, g.slots);
+                kb = kh + 1;
+                if (j + 1 < cs.A) ke = kb;
+                else if (j + 1 == cs.A) ke = cs.kp0 < cs.M ? cs.kp0 : cs.M;
+                else ke = kh + cs.pstride < cs.M ? kh + cs.pstride : cs.M;
+            }
+            if (!g.token_selection) ke = kb;
+            if (ke > kb) bs = ref_score(ref, g.slots, mub, muc);
+        }
+        // rounds of `lanes` offers; groups of one wave may need different numbers of rounds
+        int rounds = c >= 0 && ke > kb ? (ke - kb + lanes - 1) / lanes : 0;
+        int max_rounds = rounds;
+        for (int w = lanes; w < 64; w <<= 1) max_rounds = max(max_rounds, __shfl_xor(max_rounds, w, 64));
+        for (int r = 0; r < max_rounds; ++r) {
+            const int k = kb + r * lanes + lane;
+            const bool valid = r < rounds && k < ke;
+            int rk = 0;
+            float s = -INFINITY;
+            if (valid) {
+                rk = offer_ref_direct(pl, c, k, g.slots);
+                s = ref_score(rk, g.slots, mub, muc);
+            }
+            // highest score among the holder and the offers before this lane's
+            float before = bs;
+            for (int x = 0; x < lanes; ++x) {
+                const float sx = __shfl(s, lead + x, 64);
+                if (x < lane) before = fmaxf(before, sx);
+            }
+            const bool record = valid && s > before;         // this offer would replace the holder when its turn comes
+            const unsigned long long rec = __ballot(record) >> lead & ((1ull << lanes) - 1ull);
+            if (rec) {
+                const int last = 63 - __builtin_clzll(rec);  // the last replacement of the round holds the slot after it
+                ref = __shfl(rk, lead + last, 64);
+                bs = __shfl(s, lead + last, 64);
+                sw += __builtin_popcountll(rec);
+            }
+        }
+        if (c >= 0 && lane == 0) {
+            winners[((size_t)bh * pl.N + c) * (qstride + 1) + 1 + j] = ref;
+            if (sw) atomicAdd(&wg_swaps[c], sw);
+        }
+    }
+    move = c >= 0 && ref < g.slots && ref != dst;   // a cache row that goes somewhere else (chunk tokens are read by scatter_kernel)
+    if (move) {
+        const size_t srow = ((size_t)bh * g.slots + ref) * g.d, trow = ((size_t)bh * stage_rows + eg) * g.d;
+        float x[8];
+        Vec8<T>::load(Kc + srow + lane * 8, x);          Vec8<T>::store(stK + trow + lane * 8, x);
+        Vec8<T>::load(Kc + srow + half + lane * 8, x);   Vec8<T>::store(stK + trow + half + lane * 8, x);
+        Vec8<T>::load(Vc + srow + lane * 8, x);          Vec8<T>::store(stV + trow + lane * 8, x);
+        Vec8<T>::load(Vc + srow + half + lane * 8, x);   Vec8<T>::store(stV + trow + half + lane * 8, x);
+        if (lane == 0) {
+            stMu[(size_t)bh * stage_rows + eg] = mu[(size_t)bh * g.slots + ref];
+            stId[(size_t)bh * stage_rows + eg] = ids[(size_t)bh * g.slots + ref];
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < pl.N && wg_swaps[threadIdx.x]) atomicAdd(&swaps[bh * pl.N + threadIdx.x], wg_swaps[threadIdx.x]);
+}
+
 template <typename T>
 static void moves_two_phase(const Geom& g, const DevBuffers& b, const UpdatePlan& pl, const MoveList& ml, int max_chunk,
-                            const void* k, const void* v, int k_token_stride, int k_batch_stride, hipStream_t s)
+                            const void* k, const void* v, int k_token_stride, int k_batch_stride, bool direct, hipStream_t s)
 {
     const int lanes = g.d / 16, threads = 256, rows = threads / lanes;
     const dim3 grid((ml.total + rows - 1) / rows, g.B * g.Hkv), block(threads);
@@ -534,18 +653,41 @@ static void moves_two_phase(const Geom& g, const DevBuffers& b, const UpdatePlan
     T* stV = stK + BH * b.move_stage_rows * g.d;
     float* stMu = (float*)(stV + BH * b.move_stage_rows * g.d);
     int32_t* stId = (int32_t*)(stMu + BH * b.move_stage_rows);
-    hipLaunchKernelGGL(gather_kernel<T>, grid, block, 0, s, g, pl, ml, max_chunk, b.move_stage_rows, b.winners,
-                       (const T*)b.Kc, (const T*)b.Vc, b.mu, b.ids, stK, stV, stMu, stId);
+    if (direct) {
+        int n_entries = ml.total;        // entries before those of the first cascade and of the sinks
+        for (int i = 0; i < ml.n; ++i)
+            if (ml.c[i] <= 0) { n_entries = ml.first[i]; break; }
+        if (n_entries > 0)
+            hipLaunchKernelGGL(gather_direct_kernel<T>, dim3((n_entries + rows - 1) / rows, g.B * g.Hkv), block, 0, s, g, pl, ml, n_entries,
+                               max_chunk, b.move_stage_rows, b.winners, b.swaps, b.mu_chunk, (const T*)b.Kc, (const T*)b.Vc, b.mu, b.ids,
+                               stK, stV, stMu, stId);
+    } else
+        hipLaunchKernelGGL(gather_kernel<T>, grid, block, 0, s, g, pl, ml, max_chunk, b.move_stage_rows, b.winners,
+                           (const T*)b.Kc, (const T*)b.Vc, b.mu, b.ids, stK, stV, stMu, stId);
     hipLaunchKernelGGL(scatter_kernel<T>, grid, block, 0, s, g, pl, ml, max_chunk, b.move_stage_rows, b.rope, b.winners,
                        (const T*)stK, (const T*)stV, stMu, stId, b.mu_chunk, (const T*)k, (const T*)v,
-                       (long)k_token_stride, (long)k_batch_stride, (T*)b.Kc, (T*)b.Kr, (T*)b.Vc, b.mu, b.ids);
+                       (long)k_token_stride, (long)k_batch_stride, (T*)b.Kc, (T*)b.Kr, (T*)b.Vc, b.mu, b.ids, direct);
 }
 
 // Head dimensions that are not a multiple of 16 take one launch per cascade: destinations of
 // cascade c take sources from earlier cascades or from the chunk only (items never move
 // backwards), so writing the last cascade first keeps every source intact until it has been read.
+bool update_is_direct(const Geom& g, const DevBuffers& b, const UpdatePlan& pl)
+{
+    if (!(g.d % 16 == 0 && b.move_stage) || b.opt_update_staged || !plan_is_direct(pl)) return false;
+    int total = pl.n_to_sink;
+    for (int c = 0; c < pl.N; ++c) {
+        if (pl.c[c].M == 0) continue;
+        int extra;
+        total += final_entries(pl.c[c], &extra);
+        total += extra;
+    }
+    return total <= b.move_stage_rows;
+}
+
+// `direct`: no plan_kernel has run; the gather launch decides the segments itself (update_is_direct)
 void launch_moves(const Geom& g, int dtype, const DevBuffers& b, const UpdatePlan& pl, int max_chunk,
-                  const void* k, const void* v, int k_token_stride, int k_batch_stride, hipStream_t s)
+                  const void* k, const void* v, int k_token_stride, int k_batch_stride, bool direct, hipStream_t s)
 {
     if (g.d % 16 == 0 && b.move_stage) {
         MoveList ml;
@@ -567,8 +709,8 @@ void launch_moves(const Geom& g, int dtype, const DevBuffers& b, const UpdatePla
         ml.first[ml.n] = ml.total;
         if (ml.total == 0) return;
         if (ml.total <= b.move_stage_rows) {
-            if (dtype == CASCADE_F32) moves_two_phase<float>(g, b, pl, ml, max_chunk, k, v, k_token_stride, k_batch_stride, s);
-            else moves_two_phase<bf16_t>(g, b, pl, ml, max_chunk, k, v, k_token_stride, k_batch_stride, s);
+            if (dtype == CASCADE_F32) moves_two_phase<float>(g, b, pl, ml, max_chunk, k, v, k_token_stride, k_batch_stride, direct, s);
+            else moves_two_phase<bf16_t>(g, b, pl, ml, max_chunk, k, v, k_token_stride, k_batch_stride, direct, s);
             return;
         }
     }

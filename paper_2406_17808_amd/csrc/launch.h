@@ -50,6 +50,7 @@ struct DevBuffers {
     int opt_score_narrow;      // CASCADE_KV_SCORE_NARROW: 0 / 1 force the 64- / 32-key form of the score kernel; -1 = automatic
     int opt_decode_qk_direct;  // CASCADE_KV_DECODE_QK_DIRECT: bf16 decode logits by the register-load kernel
     int opt_decode_pv_valu;    // CASCADE_KV_DECODE_PV_VALU: bf16 decode outputs by the VALU kernel
+    int opt_update_staged;     // CASCADE_KV_UPDATE_STAGED: always plan the update cascade by cascade (plan_kernel)
 };
 
 // tables
@@ -66,8 +67,11 @@ void launch_prep(const Geom& g, int dtype, const DevBuffers& b, const SegList& s
 // homogeneous heads: the scores of the cached rows (and of n_new new tokens) reduced over the KV heads and shared
 void launch_share_scores(const Geom& g, const DevBuffers& b, int n_new, int max_chunk, hipStream_t s);
 void launch_plan(const Geom& g, const DevBuffers& b, const UpdatePlan& pl, int max_chunk, hipStream_t s);
+// update_is_direct: the update needs no launch_plan (every segment can be decided on its own, by the
+// first launch of launch_moves); pass its result as `direct`
+bool update_is_direct(const Geom& g, const DevBuffers& b, const UpdatePlan& pl);
 void launch_moves(const Geom& g, int dtype, const DevBuffers& b, const UpdatePlan& pl, int max_chunk,
-                  const void* k, const void* v, int k_token_stride, int k_batch_stride, hipStream_t s);
+                  const void* k, const void* v, int k_token_stride, int k_batch_stride, bool direct, hipStream_t s);
 
 // attention, generic (any dtype / head_dim): scalar arithmetic
 void launch_attn_simple(const Geom& g, int dtype, const DevBuffers& b, const SegList& sl, int Q,

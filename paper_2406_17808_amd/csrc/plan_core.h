@@ -23,11 +23,34 @@ __host__ __device__ inline int offer_ref(int c, int k, int slots, int n_to_sink,
     return c == 0 ? slots + n_to_sink + k : off_in[k];
 }
 
+// When no cascade has a slot written twice in one update (J < cap for every cascade: the usual
+// case, a chunk shorter than every ring), the item a push evicts is simply what its ring position
+// held before the update, so the offers of cascade c can be named without knowing any winner of
+// cascade c - 1, and the segments of ALL cascades can be decided at the same time.
+__host__ __device__ inline bool plan_is_direct(const UpdatePlan& pl)
+{
+    for (int c = 0; c < pl.N; ++c) {
+        if (pl.c[c].M == 0) break;
+        if (pl.c[c].J >= pl.c[c].cap) return false;
+    }
+    return true;
+}
+
+// ref of offer k of cascade c under plan_is_direct: push k of cascade c - 1 evicts ring position wpos0 + A + k
+__host__ __device__ inline int offer_ref_direct(const UpdatePlan& pl, int c, int k, int slots)
+{
+    if (c == 0) return slots + pl.n_to_sink + k;
+    const CascStep& prev = pl.c[c - 1];
+    return prev.base + (prev.wpos0 + prev.A + k) % prev.cap;
+}
+
 // Winner of segment j of cascade c (j = -1: the item that was newest before the update and the
 // offers that compete with it before any slot opens).  *swaps receives the replacements.
+// off_in == nullptr: the offers are named directly (plan_is_direct), `pl` must be given.
 __host__ __device__ inline int segment_winner(const CascStep& cs, int c, int j, int slots, int n_to_sink,
                                               int token_selection, const int32_t* off_in,
-                                              const float* mu, const float* mu_chunk, int* swaps)
+                                              const float* mu, const float* mu_chunk, int* swaps,
+                                              const UpdatePlan* pl = nullptr)
 {
     int best, kb, ke;
     if (j < 0) {
@@ -36,7 +59,7 @@ __host__ __device__ inline int segment_winner(const CascStep& cs, int c, int j, 
         ke = cs.kp0 < cs.M ? cs.kp0 : cs.M;
     } else {
         const int kh = j < cs.A ? j : cs.kp0 + (j - cs.A) * cs.pstride;
-        best = offer_ref(c, kh, slots, n_to_sink, off_in);
+        best = off_in ? offer_ref(c, kh, slots, n_to_sink, off_in) : offer_ref_direct(*pl, c, kh, slots);
         kb = kh + 1;
         if (j + 1 < cs.A) ke = kb;                                   // the next offer is appended too
         else if (j + 1 == cs.A) ke = cs.kp0 < cs.M ? cs.kp0 : cs.M;  // last append: until the first push
@@ -46,7 +69,7 @@ __host__ __device__ inline int segment_winner(const CascStep& cs, int c, int j, 
     if (token_selection) {
         float bs = ref_score(best, slots, mu, mu_chunk);
         for (int k = kb; k < ke; ++k) {
-            const int r = offer_ref(c, k, slots, n_to_sink, off_in);
+            const int r = off_in ? offer_ref(c, k, slots, n_to_sink, off_in) : offer_ref_direct(*pl, c, k, slots);
             const float s = ref_score(r, slots, mu, mu_chunk);
             if (s > bs) { best = r; bs = s; ++n_swaps; }
         }

@@ -50,6 +50,7 @@ extern "C" int cascade_simulate_structure(const cascade_config* cfg, const int32
         std::vector<int32_t> off_a(Q + 1), off_b(Q + 1);
         std::vector<std::vector<int32_t>> W(g.N, std::vector<int32_t>(Q + 2, -1));
         int32_t *off_in = off_a.data(), *off_out = off_b.data();
+        const bool direct = plan_is_direct(pl);
         for (int c = 0; c < g.N; ++c) {
             const CascStep& cs = pl.c[c];
             if (cs.M == 0) break;
@@ -59,6 +60,15 @@ extern "C" int cascade_simulate_structure(const cascade_config* cfg, const int32
                 W[c][1 + j] = segment_winner(cs, c, j, g.slots, pl.n_to_sink, g.token_selection, off_in,
                                              mu.data(), muc, &sw);
                 swaps[c] += sw;
+                if (direct) {
+                    // the device takes this update without the cascade-by-cascade hand-over: the offers
+                    // named directly from the structure must be the ones handed over, segment by segment
+                    int sw2;
+                    const int w2 = segment_winner(cs, c, j, g.slots, pl.n_to_sink, g.token_selection, nullptr,
+                                                  mu.data(), muc, &sw2, &pl);
+                    if (w2 != W[c][1 + j] || sw2 != sw)
+                        return fail(CASCADE_E_INTERNAL, "cascade_simulate_structure: direct and staged plans disagree");
+                }
             }
             for (int i = 0; i < cs.P; ++i) off_out[i] = evicted_ref(cs, i, W[c].data());
             std::swap(off_in, off_out);

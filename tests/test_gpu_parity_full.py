@@ -333,7 +333,7 @@ def test_prefill_1m_sampled_rows_and_planted_key(oracle_mod):
     c_plant = p // wl.chunk
     compare = {40, c_plant, wl.n_chunks - 1}
     Q = wl.chunk
-    assert p % Q < Q - 300      # the sampled tail rows of its chunk all come after the planted key
+    assert Q // 2 + 4 <= p % Q      # the planted key comes after the sampled early rows of its chunk, inside or before the tail rows
     worst_out = worst_score = worst_planted = worst_model_out = worst_model_score = 0.0
     last = None
     for c in range(wl.n_chunks):

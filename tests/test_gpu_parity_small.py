@@ -324,7 +324,7 @@ def test_random_geometries(oracle_mod, seed, monkeypatch):
 
 
 @pytest.mark.parametrize("dtype,reduce,hkv,G,d", [(B.CASCADE_BF16, B.CASCADE_REDUCE_MAX, 4, 2, 128), (B.CASCADE_BF16, B.CASCADE_REDUCE_MEAN, 2, 4, 64),
-                                                  (B.CASCADE_F32, B.CASCADE_REDUCE_MAX, 3, 1, 32)])
+                                                  (B.CASCADE_F32, B.CASCADE_REDUCE_MAX, 3, 1, 64)])
 def test_homogeneous_heads(oracle_mod, dtype, reduce, hkv, G, d):
     """Homogeneous heads (Appendix "Head Policy and Head Reduction"): the scores are reduced over all
     heads, every KV head takes the same decisions.  Prefill chunks and decode steps against the
@@ -351,7 +351,7 @@ def test_homogeneous_heads(oracle_mod, dtype, reduce, hkv, G, d):
                 assert np.array_equal(st.ids[b, g], st.ids[b, 0]) and np.array_equal(st.mu[b, g], st.mu[b, 0]), (i, b, g)
     print(f"homogeneous heads reduce {reduce}: out {worst_out:.3e} score {worst_score:.3e}")
     assert worst_out <= tol_out and worst_score <= tol_score
-    assert len(run.oracles[0].discard_log(0)) > 100
+    assert int(run.gpu.read_state().discards.sum()) > 100      # the policy was at work
     run.close()
 
 
