@@ -34,6 +34,13 @@
  *       full at a non-accepting step, not when the whole cache is full).
  *   R6  RoPE pairs (x_i, x_{i+d/2}), theta_i = base^(-2i/d), angle = pos*theta_i.
  *   R7  token selection replaces the newest item in place, strict '>' only.
+ *   R8  (single-pass scores only, the *_single_pass entry points) Alg. 3 adds, while a program is
+ *       still sweeping the keys, col_sum(S^ / (l + l*rho/gamma) * C_EMA): S^ = exp(S - m) and l the
+ *       running normaliser after the current inner-loop step, gamma the steps completed including
+ *       it, rho the steps remaining.  S^/l does not depend on the running maximum, so the added
+ *       value is  C_EMA * (gamma / (gamma + rho)) * exp(S_ij) / sum of exp(S_ij') over the keys of
+ *       the steps done so far.  Which step visits which key, and how many steps a program has, is
+ *       the kernel's business (tile size, visiting order, rows per program): the caller passes both.
  *
  * Parity pins (tests/test_oracle_*.py): brute-force dense attention, the
  * sink + sliding-window special case (one cascade), the full causal attention
@@ -41,7 +48,9 @@
  * Section 3.1, a hand trace of Alg. 2, the acceptance rates and the span of
  * Eq. 4, the row-sum identity of the EMA increments, the comparison record of the
  * hand traces, and for homogeneous heads brute force over all query heads plus the
- * one-KV-head case where both policies coincide.  R1 (phase of the
+ * one-KV-head case where both policies coincide; for the single-pass scores (R8) a dense
+ * formula over a random schedule, the exactness of the last step and of a one-step schedule.
+ * R1 (phase of the
  * acceptance schedule) and the order of head reduction in R3 are fixed by these
  * readings only: parity unpinned by the paper for those two choices.
  *
@@ -277,8 +286,16 @@ static int64_t head_count(const oracle_config *cfg, const head_t *H)
  * out [Q][Hq][d]: only the evaluated rows and the heads of g are written.
  * delta [n + Q]: reduced increments in cache order, then chunk tokens.
  */
-static void eval_rows(const oracle_seq *S, int g, const float *q, const float *k, const float *v,
-                      int Q, int row_lo, int row_hi, double *out, double *delta)
+/*
+ * step_of_key (may be NULL: exact scores) [n + Q]: inner-loop step, counted from 1, at which the
+ * program visits each key (cache order, then the chunk's keys); steps_of_row [G][Q]: number of
+ * inner-loop steps of the program that holds query row (head of the group, chunk row).  With them
+ * the increments are Alg. 3's single-pass values (reading R8) instead of the exact probabilities;
+ * the outputs are the exact attention either way.
+ */
+static void eval_rows_scheduled(const oracle_seq *S, int g, const float *q, const float *k, const float *v,
+                                int Q, int row_lo, int row_hi, const int32_t *step_of_key, const int32_t *steps_of_row,
+                                double *out, double *delta)
 {
     const oracle_config *cfg = &S->cfg;
     head_t *H = &S->head[g];
@@ -336,6 +353,20 @@ static void eval_rows(const oracle_seq *S, int g, const float *q, const float *k
                 const double *vj = vv + j * d;
                 for (int e = 0; e < d; ++e) o[e] += p[j] * vj[e];
             }
+            if (step_of_key) {
+                /* Alg. 3: what the sweep adds for key j at its step gamma = step_of_key[j], with the
+                   normaliser as it stands after that step and rho = T - gamma steps to go */
+                const int T = steps_of_row[(size_t)hh * Q + i];
+                double *l_after = (double *)calloc((size_t)T + 1, sizeof(double));
+                for (int64_t j = 0; j < vis; ++j) l_after[step_of_key[j]] += p[j] * sum;   /* S^ = exp(S - m) again */
+                for (int t = 1; t <= T; ++t) l_after[t] += l_after[t - 1];
+                for (int64_t j = 0; j < vis; ++j) {
+                    const double gamma = (double)step_of_key[j], rho = (double)T - gamma;
+                    const double l = l_after[step_of_key[j]];
+                    p[j] = (p[j] * sum) / (l + l * rho / gamma);
+                }
+                free(l_after);
+            }
             /* one EMA time step per query row; keys this row cannot see receive 0 */
             for (int64_t j = 0; j < nk; ++j) delta_h[j] = beta * delta_h[j] + (1.0 - beta) * (j < vis ? p[j] : 0.0);
         }
@@ -349,13 +380,19 @@ static void eval_rows(const oracle_seq *S, int g, const float *q, const float *k
     free(order); free(kr); free(vv); free(tmp); free(delta_h); free(p); free(qr);
 }
 
+static void eval_rows(const oracle_seq *S, int g, const float *q, const float *k, const float *v,
+                      int Q, int row_lo, int row_hi, double *out, double *delta)
+{
+    eval_rows_scheduled(S, g, q, k, v, Q, row_lo, row_hi, NULL, NULL, out, delta);
+}
+
 /* The reduced increments of the whole chunk for KV head g (not applied yet). */
 static double *chunk_increments(oracle_seq *S, int g, const float *q, const float *k, const float *v,
-                                int Q, double *out)
+                                int Q, const int32_t *step_of_key, const int32_t *steps_of_row, double *out)
 {
     const int64_t n = head_count(&S->cfg, &S->head[g]);
     double *delta = (double *)malloc(sizeof(double) * (size_t)(n + Q));
-    eval_rows(S, g, q, k, v, Q, 0, Q, out, delta);
+    eval_rows_scheduled(S, g, q, k, v, Q, 0, Q, step_of_key, steps_of_row, out, delta);
     return delta;
 }
 
@@ -407,8 +444,8 @@ static void chunk_apply(oracle_seq *S, int g, const float *k, const float *v, in
  * the per-group means, the groups being equally large), every KV head then updates and inserts
  * with that one vector, so all KV heads hold the same tokens at all times.
  */
-int oracle_chunk(oracle_seq *S, const float *q, const float *k, const float *v, int Q,
-                 double *out, int kv_lo, int kv_hi)
+static int chunk_scheduled(oracle_seq *S, const float *q, const float *k, const float *v, int Q,
+                           double *out, int kv_lo, int kv_hi, const int32_t *step_of_key, const int32_t *steps_of_row)
 {
     if (!S || !q || !k || !v || !out || Q < 1) return -1;
     if (kv_lo < 0 || kv_hi > S->cfg.n_kv_heads || kv_lo >= kv_hi) return -1;
@@ -416,7 +453,7 @@ int oracle_chunk(oracle_seq *S, const float *q, const float *k, const float *v, 
     if (S->cfg.head_policy == 1 && (kv_lo != 0 || kv_hi != Hkv)) return -1;
     double **delta = (double **)calloc((size_t)Hkv, sizeof(double *));
 #pragma omp parallel for schedule(dynamic, 1)
-    for (int g = kv_lo; g < kv_hi; ++g) delta[g] = chunk_increments(S, g, q, k, v, Q, out);
+    for (int g = kv_lo; g < kv_hi; ++g) delta[g] = chunk_increments(S, g, q, k, v, Q, step_of_key, steps_of_row, out);
     if (S->cfg.head_policy == 1) {
         const int64_t nk = head_count(&S->cfg, &S->head[0]) + Q;   /* the same for every head */
         for (int64_t j = 0; j < nk; ++j) {
@@ -432,6 +469,35 @@ int oracle_chunk(oracle_seq *S, const float *q, const float *k, const float *v, 
 #pragma omp parallel for schedule(dynamic, 1)
     for (int g = kv_lo; g < kv_hi; ++g) chunk_apply(S, g, k, v, Q, delta[g]);
     free(delta);
+    return 0;
+}
+
+int oracle_chunk(oracle_seq *S, const float *q, const float *k, const float *v, int Q,
+                 double *out, int kv_lo, int kv_hi)
+{
+    return chunk_scheduled(S, q, k, v, Q, out, kv_lo, kv_hi, NULL, NULL);
+}
+
+/*
+ * The same chunk with Alg. 3's single-pass scores (reading R8) in place of the exact ones.  The
+ * schedule must be the same for all selected KV heads (they hold equally many items):
+ * step_of_key [count + Q], steps_of_row [G][Q]; steps are counted from 1 and never exceed the
+ * row's number of steps for a key the row can see.
+ */
+int oracle_chunk_single_pass(oracle_seq *S, const float *q, const float *k, const float *v, int Q,
+                             double *out, int kv_lo, int kv_hi, const int32_t *step_of_key, const int32_t *steps_of_row)
+{
+    if (!step_of_key || !steps_of_row) return -1;
+    return chunk_scheduled(S, q, k, v, Q, out, kv_lo, kv_hi, step_of_key, steps_of_row);
+}
+
+int oracle_eval_rows_single_pass(const oracle_seq *S, int g, const float *q, const float *k, const float *v, int Q,
+                                 int row_lo, int row_hi, const int32_t *step_of_key, const int32_t *steps_of_row,
+                                 double *out, double *delta)
+{
+    if (!S || !q || !k || !v || !out || !delta || !step_of_key || !steps_of_row) return -1;
+    if (g < 0 || g >= S->cfg.n_kv_heads || row_lo < 0 || row_hi > Q || row_lo >= row_hi) return -1;
+    eval_rows_scheduled(S, g, q, k, v, Q, row_lo, row_hi, step_of_key, steps_of_row, out, delta);
     return 0;
 }
 

@@ -54,6 +54,10 @@ def _lib():
         L.oracle_chunk.argtypes = [P, P, P, P, ctypes.c_int, P, ctypes.c_int, ctypes.c_int]
         L.oracle_eval_rows.restype = ctypes.c_int
         L.oracle_eval_rows.argtypes = [P, ctypes.c_int, P, P, P, ctypes.c_int, ctypes.c_int, ctypes.c_int, P, P]
+        L.oracle_chunk_single_pass.restype = ctypes.c_int
+        L.oracle_chunk_single_pass.argtypes = [P, P, P, P, ctypes.c_int, P, ctypes.c_int, ctypes.c_int, P, P]
+        L.oracle_eval_rows_single_pass.restype = ctypes.c_int
+        L.oracle_eval_rows_single_pass.argtypes = [P, ctypes.c_int, P, P, P, ctypes.c_int, ctypes.c_int, ctypes.c_int, P, P, P, P]
         L.oracle_insert_scored.restype = ctypes.c_int
         L.oracle_insert_scored.argtypes = [P, ctypes.c_int, ctypes.c_double]
         for name in ("oracle_count", "oracle_t", "oracle_n_seen"):
@@ -148,9 +152,19 @@ class OracleSeq:
             pass
 
     # -- the path ---------------------------------------------------------
+    def _schedule(self, schedule, n: int, Q: int):
+        """schedule = (step_of_key [n + Q], steps_of_row [G, Q]) of Alg. 3's single-pass scores."""
+        G = self.cfg.n_q_heads // self.cfg.n_kv_heads
+        step_of_key = np.ascontiguousarray(schedule[0], dtype=np.int32)
+        steps_of_row = np.ascontiguousarray(schedule[1], dtype=np.int32)
+        assert step_of_key.shape == (n + Q,) and steps_of_row.shape == (G, Q), (step_of_key.shape, steps_of_row.shape)
+        assert step_of_key.min() >= 1 and steps_of_row.min() >= 1
+        return step_of_key, steps_of_row
+
     def chunk(self, q: np.ndarray, k: np.ndarray, v: np.ndarray,
-              kv_heads: Optional[Tuple[int, int]] = None) -> np.ndarray:
-        """q [Q,Hq,d], k, v [Q,Hkv,d] -> out [Q,Hq,d] float64, then the chunk enters the cache."""
+              kv_heads: Optional[Tuple[int, int]] = None, schedule=None) -> np.ndarray:
+        """q [Q,Hq,d], k, v [Q,Hkv,d] -> out [Q,Hq,d] float64, then the chunk enters the cache.
+        schedule: None for exact scores, else the visiting schedule of Alg. 3's single-pass scores."""
         cfg = self.cfg
         q = np.ascontiguousarray(q, dtype=np.float32)
         k = np.ascontiguousarray(k, dtype=np.float32)
@@ -160,12 +174,16 @@ class OracleSeq:
         assert k.shape == (Q, cfg.n_kv_heads, cfg.head_dim) and v.shape == k.shape
         lo, hi = kv_heads if kv_heads is not None else (0, cfg.n_kv_heads)
         out = np.zeros((Q, cfg.n_q_heads, cfg.head_dim), dtype=np.float64)
-        rc = _lib().oracle_chunk(self._h, _ptr(q), _ptr(k), _ptr(v), Q, _ptr(out), lo, hi)
+        if schedule is None:
+            rc = _lib().oracle_chunk(self._h, _ptr(q), _ptr(k), _ptr(v), Q, _ptr(out), lo, hi)
+        else:
+            sk, sr = self._schedule(schedule, self.count(lo), Q)
+            rc = _lib().oracle_chunk_single_pass(self._h, _ptr(q), _ptr(k), _ptr(v), Q, _ptr(out), lo, hi, _ptr(sk), _ptr(sr))
         if rc != 0:
             raise RuntimeError("oracle_chunk failed")
         return out
 
-    def eval_rows(self, kv_head: int, q: np.ndarray, k: np.ndarray, v: np.ndarray, row_lo: int, row_hi: int):
+    def eval_rows(self, kv_head: int, q: np.ndarray, k: np.ndarray, v: np.ndarray, row_lo: int, row_hi: int, schedule=None):
         """Rows [row_lo, row_hi) of the chunk (q, k, v) for one KV head, cache untouched.
         Returns (out [Q,Hq,d] with only those rows and that head group written,
         delta [count + Q]: the EMA increments those rows alone produce)."""
@@ -177,7 +195,12 @@ class OracleSeq:
         assert q.shape == (Q, cfg.n_q_heads, cfg.head_dim) and k.shape == (Q, cfg.n_kv_heads, cfg.head_dim)
         out = np.zeros((Q, cfg.n_q_heads, cfg.head_dim), dtype=np.float64)
         delta = np.zeros(self.count(kv_head) + Q, dtype=np.float64)
-        rc = _lib().oracle_eval_rows(self._h, kv_head, _ptr(q), _ptr(k), _ptr(v), Q, row_lo, row_hi, _ptr(out), _ptr(delta))
+        if schedule is None:
+            rc = _lib().oracle_eval_rows(self._h, kv_head, _ptr(q), _ptr(k), _ptr(v), Q, row_lo, row_hi, _ptr(out), _ptr(delta))
+        else:
+            sk, sr = self._schedule(schedule, self.count(kv_head), Q)
+            rc = _lib().oracle_eval_rows_single_pass(self._h, kv_head, _ptr(q), _ptr(k), _ptr(v), Q, row_lo, row_hi,
+                                                     _ptr(sk), _ptr(sr), _ptr(out), _ptr(delta))
         if rc != 0:
             raise RuntimeError("oracle_eval_rows failed")
         return out, delta

@@ -180,6 +180,81 @@ def test_homogeneous_equals_independent_for_one_kv_head(oracle_mod):
     assert states[0][1].ids.tolist() == states[1][1].ids.tolist() and states[0][1].mu.tolist() == states[1][1].mu.tolist()
 
 
+def _single_pass_dense(q, qpos, keys, kpos, vis, base, scale, step_of_key, T):
+    """Alg. 3 written densely: while the sweep stands at step t the normaliser holds the keys of the
+    steps 1..t, and what is added for a key of step t is exp(S) / (l_t + l_t * (T - t) / t)."""
+    s = rope_complex(q, qpos, base) @ rope_complex(keys, kpos, base).T * scale
+    e = np.where(vis, np.exp(s - np.where(vis, s, -np.inf).max(axis=1, keepdims=True)), 0.0)
+    out = np.zeros_like(e)
+    for t in range(1, T + 1):
+        done = step_of_key <= t
+        l_t = e[:, done].sum(axis=1)
+        now = step_of_key == t
+        out[:, now] = e[:, now] / (l_t + l_t * (T - t) / t)[:, None]
+    return out
+
+
+def test_single_pass_scores_brute_force(oracle_mod):
+    """Alg. 3's single-pass scores (the running normaliser extrapolated by the steps still to go)
+    against a dense formula, for a random assignment of keys to inner-loop steps; the outputs stay the
+    exact attention.  Keys of the last step get their exact probability, a single step gives the exact
+    scores throughout, and every single-pass value is at least (step / steps) times the exact one."""
+    rng = np.random.default_rng(21)
+    Hq, Hkv, d, Q, beta, base = 4, 2, 8, 6, 0.8, 50.0
+    G = Hq // Hkv
+    cfg = OracleConfig(n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, n_sink=2, cascade_sizes=[5, 5],
+                       ema_beta=beta, rope_base=base)
+    o = OracleSeq(cfg)
+    q0, k0, v0 = _rand(rng, 30, Hq, d), _rand(rng, 30, Hkv, d), _rand(rng, 30, Hkv, d)
+    for s in range(0, 30, Q):
+        o.chunk(q0[s:s + Q], k0[s:s + Q], v0[s:s + Q])
+    q, k, v = _rand(rng, Q, Hq, d), _rand(rng, Q, Hkv, d), _rand(rng, Q, Hkv, d)
+    w = beta ** (Q - 1 - np.arange(Q)) * (1 - beta)
+    for g in range(Hkv):
+        st = o.state(g, with_kv=True)
+        n = len(st.ids)
+        T = 5
+        # any schedule: the steps of the cached keys in random order, the chunk's keys in the last two steps
+        step_of_key = np.concatenate([rng.integers(1, 4, size=n), np.where(np.arange(Q) < 3, 4, 5)]).astype(np.int32)
+        steps_of_row = np.full((G, Q), T, dtype=np.int32)
+        exact_out, exact_delta = o.eval_rows(g, q, k, v, 0, Q)
+        out, delta = o.eval_rows(g, q, k, v, 0, Q, schedule=(step_of_key, steps_of_row))
+        assert np.array_equal(out, exact_out)                    # the attention itself is not approximated
+        keys = np.concatenate([st.k, k[:, g].astype(np.float64)])
+        vis = np.concatenate([np.ones((Q, n), bool), np.tril(np.ones((Q, Q), bool))], axis=1)
+        per_head, per_head_exact = [], []
+        for hh in range(G):
+            qq = q[:, g * G + hh].astype(np.float64)
+            ph = _single_pass_dense(qq, n + np.arange(Q), keys, np.arange(n + Q), vis, base, d ** -0.5, step_of_key, T)
+            _, P = dense_attention(qq, n + np.arange(Q), keys, np.arange(n + Q), np.concatenate([st.v, v[:, g].astype(np.float64)]),
+                                   vis, base, d ** -0.5)
+            last = step_of_key == T
+            np.testing.assert_allclose(ph[:, last], P[:, last], rtol=1e-12, atol=1e-300)   # rho = 0: exact
+            assert (ph >= P * (step_of_key / T)[None, :] * (1 - 1e-12)).all()
+            per_head.append(w @ ph)
+            per_head_exact.append(w @ P)
+        np.testing.assert_allclose(delta, np.max(per_head, axis=0), rtol=1e-10, atol=1e-300)
+        np.testing.assert_allclose(exact_delta, np.max(per_head_exact, axis=0), rtol=1e-10, atol=1e-300)
+        assert np.abs(delta - exact_delta).max() > 1e-3           # and it is a different quantity
+        # one step: nothing is extrapolated
+        one = (np.ones(n + Q, dtype=np.int32), np.ones((G, Q), dtype=np.int32))
+        _, delta_one = o.eval_rows(g, q, k, v, 0, Q, schedule=one)
+        np.testing.assert_allclose(delta_one, exact_delta, rtol=1e-12, atol=1e-300)
+    # the whole chunk with a schedule: the cached scores are updated with the single-pass increments
+    g = 0
+    before = o.state(g)
+    n = len(before.ids)
+    sched = (np.concatenate([np.full(n, 1), np.full(Q, 2)]).astype(np.int32), np.full((G, Q), 2, dtype=np.int32))
+    _, d_sp = o.eval_rows(g, q, k, v, 0, Q, schedule=sched)
+    o.chunk(q, k, v, kv_heads=(g, g + 1), schedule=sched)
+    np.testing.assert_array_equal(o.last_delta(g), d_sp)
+    after = o.state(g)
+    expect = {int(i): beta ** Q * m + dl for i, m, dl in zip(before.ids, before.mu, d_sp[:n])}
+    for i, m in zip(after.ids, after.mu):
+        if int(i) in expect:
+            assert abs(m - expect[int(i)]) <= 1e-12 * max(1.0, abs(m))
+
+
 def test_mean_head_reduction(oracle_mod):
     """The mean reduction over the query heads of a group (Appendix "Head Policy")."""
     rng = np.random.default_rng(13)
