@@ -83,8 +83,17 @@ typedef struct cascade_config {
                                  scores) or CASCADE_HEADS_HOMOGENEOUS (Appendix "Head Policy and Head Reduction":
                                  the scores are reduced over ALL heads, by head_reduce, and every KV head takes
                                  the same decisions, so all of them hold the same tokens) */
-    int32_t score_mode;       /* CASCADE_SCORES_EXACT: the scores use the final softmax probabilities (Section 3.1);
-                                 CASCADE_SCORES_SINGLE_PASS: reserved */
+    int32_t score_mode;       /* CASCADE_SCORES_EXACT: the scores use the final softmax probabilities (Section 3.1).
+                                 CASCADE_SCORES_SINGLE_PASS (bf16 only): Alg. 3's scores, accumulated while the attention
+                                 kernel sweeps the keys, with the running normaliser extrapolated by the tiles still to
+                                 come: a row block of 256 tokens of one head adds, for the keys of its tile number
+                                 gamma of T,  C_EMA * exp(S - m) / (l + l * (T - gamma) / gamma)  with m, l as they stand
+                                 after that tile.  Tiles are 64 keys in the physical order of the cache (sinks, last
+                                 cascade, ..., first cascade, every ring from its slot 0, pieces cut where a ring head
+                                 sits), then the chunk's keys.  No second pass over the keys; the scores depend on that
+                                 order and are an approximation of the exact ones.  A chunk whose length is not a
+                                 multiple of 256, or whose launch is split over the keys (fewer than 129 row blocks in
+                                 all), takes the exact pass: cascade_state_view.last_single_pass says which it was. */
 } cascade_config;
 
 typedef struct cascade_ctx cascade_ctx;
@@ -138,6 +147,7 @@ typedef struct cascade_state_view {
     int32_t pre_count;        /* items cached before the last call */
     int32_t last_tokens;      /* tokens of the last call (0 before any call) */
     int32_t n_kv_pairs;       /* input: entries of host_kv_pairs */
+    int32_t last_single_pass; /* 1 if the last prefill call took the single-pass scores (score_mode) */
 } cascade_state_view;
 
 /* Device bytes cascade_init needs for this configuration; 0 if the configuration is invalid. */

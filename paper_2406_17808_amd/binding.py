@@ -86,6 +86,7 @@ class cascade_state_view(ctypes.Structure):
         ("discards", ctypes.c_int64 * CASCADE_MAX_CASCADES),
         ("t", ctypes.c_int64), ("n_seen", ctypes.c_int64),
         ("pre_count", ctypes.c_int32), ("last_tokens", ctypes.c_int32), ("n_kv_pairs", ctypes.c_int32),
+        ("last_single_pass", ctypes.c_int32),
     ]
 
 
@@ -266,6 +267,7 @@ class StateArrays:
         self.count = int(self.counts.sum())
         self.ids, self.mu, self.slot, self.k, self.v, self.swaps = ids, mu, slot, k, v, swaps
         self.pre_count, self.last_tokens = int(view.pre_count), int(view.last_tokens)
+        self.last_single_pass = bool(view.last_single_pass)
         self.pre_mu = self.chunk_mu = None
 
 

@@ -38,6 +38,7 @@ struct cascade_ctx {
     uint32_t prof_mask = ~0u;   // kernel families that get events while profiling
     bool is_static = false;   // one of the per-device contexts of cascade_init_static: never deleted
     bool poisoned = false;    // a launch of an earlier call failed: the device state is undefined
+    bool last_single_pass = false;   // the last prefill call took the single-pass scores
     std::vector<std::pair<hipEvent_t, hipEvent_t>> prof[CASCADE_K_FAMILIES];
     std::string err;
 };
@@ -124,6 +125,9 @@ static WorkspaceBytes carve(const cascade_config* c, const Geom& g, char* state_
     b.mu_chunk = (float*)take(BH * mc * 4);
     b.negt = (float*)take(mfma ? BHq * (mc + 64) * 4 : 0);
     b.attn_part = (float*)take(mfma ? (size_t)kAttnPartRows * (g.d + 2) * 4 : 0);
+    const bool single_pass = mfma && c->score_mode == CASCADE_SCORES_SINGLE_PASS;
+    b.sp_part = (float*)take(single_pass ? BH * (size_t)g.G * ((mc + 255) / 256) * (size_t)vt_tiles * 64 * 4 : 0);
+    if (!single_pass) b.sp_part = nullptr;
     b.offers = (int32_t*)take(BH * 2 * mc * 4);
     b.winners = (int32_t*)take(BH * g.N * (mc + 1) * 4);
     const int move_stage_rows = (g.N + 1) * ((int)mc + 1);    // every cascade and the sinks: at most max_chunk + 1 entries each
@@ -464,10 +468,13 @@ extern "C" int cascade_prefill_chunk(cascade_ctx* ctx, const void* dev_q, const 
     // the MFMA kernels take logits directly as base-2 exponents
     const float qscale = ctx->mfma ? g.scale * 1.4426950408889634f : 1.f;
     const int tail = Q < ctx->tail_k ? Q : ctx->tail_k;    // rows that carry weight in the score sums
+    const bool single_pass = ctx->mfma && attn_single_pass_ok(g, ctx->buf, Q);
+    ctx->last_single_pass = single_pass;
     {
         Timed t(ctx, CASCADE_K_PREP, s);
         // bf16: the attention kernel rotates its queries itself; only the score kernel reads rotated copies
-        launch_prep(g, ctx->dtype, ctx->buf, sl, Q, qscale, ctx->mfma ? Q - tail : 0, dev_q, dev_k, dev_v, s);
+        // (single-pass scores: nobody reads rotated query copies)
+        launch_prep(g, ctx->dtype, ctx->buf, sl, Q, qscale, ctx->mfma ? (single_pass ? Q : Q - tail) : 0, dev_q, dev_k, dev_v, s);
         if (ctx->mfma) {
             // The tiles of a full cache keep their place while the ring heads keep their offsets
             // inside a tile: then only the tiles the last update wrote, and the chunk's own, are
@@ -495,13 +502,14 @@ extern "C" int cascade_prefill_chunk(cascade_ctx* ctx, const void* dev_q, const 
     }
     {
         Timed t(ctx, CASCADE_K_ATTENTION, s);
-        if (ctx->mfma) launch_attn_stream(g, ctx->buf, sl, Q, dev_q, qscale, tail, ctx->max_chunk, dev_out, s);
+        if (ctx->mfma) launch_attn_stream(g, ctx->buf, sl, Q, dev_q, qscale, tail, ctx->max_chunk, dev_out, single_pass, s);
         else launch_attn_simple(g, ctx->dtype, ctx->buf, sl, Q, ctx->max_chunk, dev_out, s);
     }
     const float decay = (float)pow((double)g.beta, (double)Q);
     {
         Timed t(ctx, CASCADE_K_SCORES, s);
-        if (ctx->mfma) launch_score_mfma(g, ctx->buf, sl, Q, ctx->max_chunk, tail, decay, s);
+        if (single_pass) launch_single_pass_merge(g, ctx->buf, sl, Q, ctx->max_chunk, tail, decay, s);
+        else if (ctx->mfma) launch_score_mfma(g, ctx->buf, sl, Q, ctx->max_chunk, tail, decay, s);
         else launch_score_simple(g, ctx->dtype, ctx->buf, sl, Q, ctx->max_chunk, tail, decay, s);
         if (g.head_policy == CASCADE_HEADS_HOMOGENEOUS && g.Hkv > 1) launch_share_scores(g, ctx->buf, Q, ctx->max_chunk, s);
     }
@@ -546,6 +554,7 @@ extern "C" int cascade_decode_step(cascade_ctx* ctx, const void* dev_q, const vo
     SegList sl;
     build_segments(g, ctx->st, false, 1, sl);
     ctx->packed_valid = false;   // the step writes cache rows the packed copies of the prefill path do not follow
+    ctx->last_single_pass = false;
     {
         Timed t0(ctx, CASCADE_K_DECODE_QK, s);
         launch_decode_qk(g, ctx->dtype, ctx->buf, sl, dev_q, dev_k, s);
@@ -604,6 +613,7 @@ extern "C" int cascade_read_state(cascade_ctx* ctx, cascade_state_view* view, vo
     view->n_seen = st.n_seen;
     view->pre_count = ctx->st_prev.n_cached(g);
     view->last_tokens = ctx->last_tokens;
+    view->last_single_pass = ctx->last_single_pass ? 1 : 0;
 
     if (ctx->cfg.keep_update_scores && view->host_pre_mu && ctx->last_tokens > 0) {
         std::vector<float> snap(BH * g.slots);

@@ -139,6 +139,17 @@ struct ScoreOffsets {
     int tail, qpad;
 };
 
+// Single-pass scores (Alg. 3): while a row block sweeps the keys it adds, per tile, the column sums
+// over its queries of  C_EMA * S^ / (l + l * rho / gamma)  (S^ and l relative to the same running
+// maximum, gamma tiles done including this one, rho tiles to go).  A workgroup owns a slice of
+// `part`: [row block][tile][64 keys], written tile by tile with plain stores (no atomics: the sums
+// are the same from run to run); single_pass_merge_kernel adds the row blocks up.
+struct SinglePass {
+    float* part;         // [B*Hkv][G][rb_count][tiles_per_bh][64]
+    int rb_first;        // first row block (of a head's Q / 256) with a row that carries EMA weight
+    int rb_count;        // row blocks from there to the end of the chunk
+};
+
 __device__ inline void write_score_offset(const ScoreOffsets& so, size_t head, int Q, int i, float lse2)
 {
     float* row = so.negt + head * so.qpad;
@@ -149,13 +160,15 @@ __device__ inline void write_score_offset(const ScoreOffsets& so, size_t head, i
 // SPLIT: the tiles a row block visits are divided over n_split workgroups (for launches too small
 // to fill the chip otherwise); each writes its unnormalised output, running maximum and row sum
 // to part_o / part_ml, and attn_merge_kernel combines them.
-template <int D, bool DBG, bool SPLIT>
+// SP: single-pass scores (needs Q % 256 == 0 and no SPLIT: a row block is one head's 256 tokens).
+template <int D, bool DBG, bool SPLIT, bool SP = false>
 __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     Geom g, SegList sl, int Q, int tiles_per_bh, const bf16_t* __restrict__ q, const float2* __restrict__ rope, float qscale,
     const bf16_t* __restrict__ Kt, const bf16_t* __restrict__ Vt, bf16_t* __restrict__ out, float* __restrict__ lse,
     long long* dbg, int n_split, float* __restrict__ part_o, float* __restrict__ part_ml, const float* __restrict__ Knorm2,
-    ScoreOffsets so)
+    ScoreOffsets so, SinglePass sp)
 {
+    static_assert(!(SP && SPLIT), "single-pass scores are taken by unsplit launches only");
     constexpr int BM = kSWaves * 32;       // query rows per workgroup
     constexpr int KS = D / 16;             // k-steps of S^T = K Q^T
     constexpr int DB = D / 32;             // 32-wide blocks of the head dimension in O^T
@@ -165,6 +178,7 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     __shared__ __attribute__((aligned(1024))) bf16_t Ks[kSStages * TILE];
     __shared__ __attribute__((aligned(1024))) bf16_t Vs[kSStages * TILE];
     __shared__ float kn_wave[kSWaves];
+    __shared__ float sp_sum[SP ? 2 : 1][SP ? kSWaves : 1][SP ? kBN : 1];   // per-wave column sums of the last two tiles
 
     const int BH = g.B * g.Hkv;
     // consecutive workgroups: different KV heads; row blocks that see more of the chunk (longer loops) start first
@@ -288,7 +302,70 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     // when that exceeds kRescaleLog2 (the probabilities then stay below 2^kRescaleLog2, and most
     // tiles skip the rescaling of O), and turn S^T into probabilities.  FIRST: S^T is absolute
     // and m_run not set yet (the first tile of a workgroup).
-    auto softmax_tile = [&](const TileIter& it, bool first, auto interior) {
+    // Single-pass scores: a row block is 256 tokens of one head (Q % 256 == 0); it takes part if one
+    // of its rows carries EMA weight.  cw: the weight of this lane's row (Alg. 3's C_EMA).
+    const int rbs_per_head = SP ? Q / BM : 1;
+    const bool sp_on = SP && (tile % rbs_per_head) >= sp.rb_first;     // uniform for the workgroup
+    const float cw = (SP && qvalid && qi >= Q - so.tail) ? so.wrow[Q - 1 - qi] : 0.f;
+    float inv_steps = 0.f;               // 1 / tiles this row block visits, set once they are counted
+    float* sp_part = SP ? sp.part + ((((size_t)bh * g.G + tile / rbs_per_head) * sp.rb_count + (tile % rbs_per_head - sp.rb_first)) *
+                                     (size_t)tiles_per_bh) * kBN
+                        : nullptr;
+    // after the reduction below lane l holds the column sum of key 4*half + 32*(l32 >> 4) + 8*((l32 & 15) >> 2) + (l32 & 3)
+    const int sp_key = 4 * half + 32 * (l32 >> 4) + 8 * ((l32 & 15) >> 2) + (l32 & 3);
+    // Column sums over the 32 queries of this wave of  p * w  (w per query), for the 64 keys of a
+    // tile: s[][] holds p (fp32) on entry.  A reduce-scatter over the five lane bits of the query
+    // index: at every level the lanes of a pair each keep half of the values and add the partner's
+    // (lanes l and l^16 by v_permlane16_swap, with the weights folded into that first level, the
+    // rest by DPP), so that after five levels every lane holds the sum of one key (sp_key).
+    auto dpp = [](float x, auto ctrl) {
+        return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), decltype(ctrl)::value, 0xf, 0xf, true));
+    };
+    auto column_sums = [&](int step) {
+        const float lt = lsum + __shfl_xor(lsum, 32, 64);
+        // gamma / (gamma + rho) = step / NT; a row always sees a key of its first tile, so lt > 0
+        const float w = cw * (float)step * inv_steps * __builtin_amdgcn_rcpf(lt);
+        const auto wp = __builtin_amdgcn_permlane16_swap(__float_as_uint(w), __float_as_uint(w), false, false);
+        const float wa = __uint_as_float(wp[0]), wb = __uint_as_float(wp[1]);   // weights of the even-row and odd-row lane of a pair
+        float v[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            // even rows (bit 4 of the lane clear) end up with key block 0, odd rows with key block 1
+            const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(s[0][j]), __float_as_uint(s[1][j]), false, false);
+            v[j] = __builtin_fmaf(__uint_as_float(r[1]), wb, __uint_as_float(r[0]) * wa);
+        }
+        const bool b3 = l & 8, b2 = l & 4, b1 = l & 2, b0 = l & 1;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float t1 = v[j] + dpp(v[j], std::integral_constant<int, 0x128>());            // row_ror:8 = lane ^ 8
+            const float t2 = v[j + 8] + dpp(v[j + 8], std::integral_constant<int, 0x128>());
+            v[j] = b3 ? t2 : t1;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float t1 = v[j] + dpp(v[j], std::integral_constant<int, 0x104>());            // row_shl:4: from lane + 4
+            const float t2 = v[j + 4] + dpp(v[j + 4], std::integral_constant<int, 0x114>());    // row_shr:4: from lane - 4
+            v[j] = b2 ? t2 : t1;
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const float t1 = v[j] + dpp(v[j], std::integral_constant<int, 0x4E>());             // quad_perm [2,3,0,1]
+            const float t2 = v[j + 2] + dpp(v[j + 2], std::integral_constant<int, 0x4E>());
+            v[j] = b1 ? t2 : t1;
+        }
+        const float t1 = v[0] + dpp(v[0], std::integral_constant<int, 0xB1>());                 // quad_perm [1,0,3,2]
+        const float t2 = v[1] + dpp(v[1], std::integral_constant<int, 0xB1>());
+        sp_sum[step & 1][wave][sp_key] = b0 ? t2 : t1;
+    };
+    // One wave adds the eight waves' sums of tile t and stores the 64 values (every wave wrote them
+    // before the barrier the caller has passed; the slot is rewritten two tiles later).
+    auto flush_column_sums = [&](int t) {
+        float acc = 0.f;
+#pragma unroll
+        for (int w = 0; w < kSWaves; ++w) acc += sp_sum[(t + 1) & 1][w][l];
+        counted_store_f32(sp_part, (uint32_t)((t * kBN + l) * 4), acc);
+    };
+    auto softmax_tile = [&](const TileIter& it, bool first, auto interior, int step) {
         if (!decltype(interior)::value && ((it.t0 + kBN > it.sg.len) || (it.sg.chunk && it.t0 + kBN - 1 > wave_imin))) {
             const int lim = it.sg.chunk ? min(it.sg.len - 1, qi) : it.sg.len - 1;   // last visible key
             const int rel = lim - it.t0 - half * 4;   // accumulator j of block kb is key t0 + 4*half + (32 kb + 8 (j/4) + j%4)
@@ -340,8 +417,10 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
                 const float p1 = __builtin_amdgcn_exp2f(s[kb][hf * 8 + 2 * x2 + 1]);
                 pf[qt].u[x2] = cvt_pk_bf16(p0, p1);
                 lsum += p0 + p1;   // plain adds: the dot-product instructions queue behind the MFMAs of the SIMD
+                if (SP) { s[kb][hf * 8 + 2 * x2] = p0; s[kb][hf * 8 + 2 * x2 + 1] = p1; }
             }
         }
+        if (SP && sp_on) column_sums(step);
     };
     auto wave_active = [&](const TileIter& it) { return !(it.sg.chunk && it.t0 > wave_imax); };
 
@@ -349,6 +428,7 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     // and of K of tile t+3 are issued.  Only the softmax needs to know which segment a tile is from.
     int NT = 0;   // tiles this workgroup visits: chunk keys after its last row are never visible
     for (int i = 0; i < sl.n; ++i) NT += ((sl.s[i].chunk ? min(sl.s[i].len, wg_imax + 1) : sl.s[i].len) + kBN - 1) / kBN;
+    if (SP) inv_steps = 1.f / (float)NT;
     int tile_first = 0;                  // SPLIT: first tile of this workgroup's range
     TileIter it1;
     it1.first(sl, wg_imax);
@@ -425,7 +505,7 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     for (int w = 0; w < kSWaves; ++w) kn2 = fmaxf(kn2, kn_wave[w]);
     qk_tile(Ks);
     if (!SPLIT || wave_active(it1)) {
-        softmax_tile(it1, true, std::false_type());    // not SPLIT: every wave sees the first tile
+        softmax_tile(it1, true, std::false_type(), 1);    // not SPLIT: every wave sees the first tile
     } else {
 #pragma unroll
         for (int qt = 0; qt < 4; ++qt)
@@ -489,7 +569,8 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
                 lap(2);
                 // measured orders of the three parts: exponentials, fragments, copies (this one) 3.329 ms;
                 // fragments first 3.35; copies before the fragments 3.41
-                softmax_tile(it1, false, std::true_type());
+                softmax_tile(it1, false, std::true_type(), n0 + 2);
+                if (SP && sp_on && wave == (n0 & 3)) flush_column_sums(n0);
 #pragma unroll
                 for (int i = 0; i < kAhead; ++i) fr[i] = read_frag(Vs + ((n0 + 1) & 3) * TILE, Ks, i);
                 copy_tile(kt_bh, lds_k, n0 + 4, n0 & 3);
@@ -521,13 +602,15 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
         const int in_flight = issue(n0);   // here: a copy instruction can hold a wave up, and this block has time to spare
         // ---- vector block
         if (act_next) {
-            softmax_tile(it1, false, std::false_type());
+            softmax_tile(it1, false, std::false_type(), n0 + 2);
         } else {
 #pragma unroll
             for (int qt = 0; qt < 4; ++qt)
 #pragma unroll
                 for (int x = 0; x < 4; ++x) pf[qt].u[x] = 0u;
+            if (SP && sp_on) sp_sum[n0 & 1][wave][l] = 0.f;      // this wave sees nothing of tile n0 + 1 (step n0 + 2)
         }
+        if (SP && sp_on && wave == (n0 & 3)) flush_column_sums(n0);
         lap(3);
         publish(in_flight);
         wg_barrier();     // barrier 2t+2 (early group), 2t+3 (late group)
@@ -536,6 +619,7 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
         ++n0;
     }
     if (!late) wg_barrier();   // the late group passed one barrier more
+    if (SP && sp_on && wave == 0) flush_column_sums(n0);   // the last tile: every wave has left its vector block
     if (DBG && blockIdx.x == 100 && l == 0 && (wave == 0 || wave == 4)) {
 #pragma unroll
         for (int i = 0; i < 5; ++i) dbg[(wave / 4) * 8 + i] = tc[i];
@@ -633,6 +717,41 @@ __global__ __launch_bounds__(D) void attn_merge_kernel(Geom g, int Q, int n_tile
     }
 }
 
+// Single-pass scores, second half: per key, the row blocks' column sums added up in a fixed order,
+// the query heads of the group reduced (max or mean), and the EMA step of Section 3.1 taken:
+// cached rows mu <- decay * mu + increment, chunk tokens start at their increment.  One thread per
+// key of a packed tile; a chunk tile was only visited by the row blocks that see it.
+__global__ __launch_bounds__(kBN) void single_pass_merge_kernel(Geom g, SegList sl, int Q, int qstride, int tiles_per_bh, SinglePass sp,
+                                                                float decay, float* __restrict__ mu, float* __restrict__ mu_chunk)
+{
+    const int n = blockIdx.x, bh = blockIdx.y, x = threadIdx.x;
+    int si = 0, first = 0;
+    for (; si < sl.n; ++si) {
+        const int nt = (sl.s[si].len + kBN - 1) / kBN;
+        if (n < first + nt) break;
+        first += nt;
+    }
+    if (si >= sl.n) return;
+    const Seg sg = sl.s[si];
+    const int t0 = (n - first) * kBN, key = t0 + x;
+    if (key >= sg.len) return;
+    // row block r of a head covers tokens 256 r .. 256 r + 255 and visits the chunk's tiles up to its last token
+    const int r_lo = sg.chunk ? max(0, t0 / 256 - sp.rb_first) : 0;
+    float red = 0.f;
+    for (int hh = 0; hh < g.G; ++hh) {
+        const float* p = sp.part + ((((size_t)bh * g.G + hh) * sp.rb_count) * (size_t)tiles_per_bh + n) * kBN + x;
+        float v = 0.f;
+        for (int r = r_lo; r < sp.rb_count; ++r) v += p[(size_t)r * tiles_per_bh * kBN];
+        red = g.head_reduce == CASCADE_REDUCE_MAX ? (hh == 0 ? v : fmaxf(red, v)) : red + v;
+    }
+    if (g.head_reduce == CASCADE_REDUCE_MEAN) red /= (float)g.G;
+    if (sg.chunk) mu_chunk[(size_t)bh * qstride + key] = red;
+    else {
+        float* m = mu + (size_t)bh * g.slots + sg.start + key;
+        *m = decay * *m + red;
+    }
+}
+
 // Workgroups per (row block, KV head) so that a small launch still fills the chip: none for 256
 // workgroups or more.
 int attn_splits(const Geom& g, int Q, int forced)
@@ -645,10 +764,28 @@ int attn_splits(const Geom& g, int Q, int forced)
     return n < 1 ? 1 : n;
 }
 
+// A chunk takes the single-pass scores when its launch is not split over the keys and its row blocks
+// are whole heads' pieces (Q a multiple of 256); other chunks of such a context take the exact pass.
+bool attn_single_pass_ok(const Geom& g, const DevBuffers& b, int Q)
+{
+    return b.sp_part != nullptr && Q % (kSWaves * 32) == 0 && attn_splits(g, Q, b.opt_attn_splits) == 1;
+}
+
+void launch_single_pass_merge(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, int max_chunk, int tail_rows, float decay,
+                              hipStream_t s)
+{
+    const int rb_first = (Q - tail_rows) / (kSWaves * 32);
+    const SinglePass sp = {b.sp_part, rb_first, Q / (kSWaves * 32) - rb_first};
+    hipLaunchKernelGGL(single_pass_merge_kernel, dim3(packed_tiles(sl), g.B * g.Hkv), dim3(kBN), 0, s, g, sl, Q, max_chunk, b.vt_tiles, sp,
+                       decay, b.mu, b.mu_chunk);
+}
+
 void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, const void* q, float qscale,
-                        int tail_rows, int max_chunk, void* out, hipStream_t s)
+                        int tail_rows, int max_chunk, void* out, bool single_pass, hipStream_t s)
 {
     const ScoreOffsets so = {b.wrow, b.negt, tail_rows, max_chunk + kScorePadRows};
+    const int sp_rb_first = (Q - tail_rows) / (kSWaves * 32);
+    const SinglePass sp = {b.sp_part, sp_rb_first, Q / (kSWaves * 32) - sp_rb_first};
     const int tiles_per_bh = b.vt_tiles;   // stride between the packed streams of two (batch, KV head)
     constexpr int BM = kSWaves * 32;
     const int tiles = (g.G * Q + BM - 1) / BM;
@@ -659,12 +796,12 @@ void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, i
         float* part_ml = b.attn_part + (size_t)kAttnPartRows * g.d;
         if (g.d == 128) {
             hipLaunchKernelGGL((attn_stream_kernel<128, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
-                               (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, n_split, part_o, part_ml, b.knorm2, so);
+                               (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, n_split, part_o, part_ml, b.knorm2, so, sp);
             hipLaunchKernelGGL(attn_merge_kernel<128>, dim3(g.G * Q, g.B * g.Hkv), dim3(128), 0, s, g, Q, tiles, n_split, BM,
                                part_o, part_ml, (bf16_t*)out, b.lse, so);
         } else {
             hipLaunchKernelGGL((attn_stream_kernel<64, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
-                               (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, n_split, part_o, part_ml, b.knorm2, so);
+                               (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, n_split, part_o, part_ml, b.knorm2, so, sp);
             hipLaunchKernelGGL(attn_merge_kernel<64>, dim3(g.G * Q, g.B * g.Hkv), dim3(64), 0, s, g, Q, tiles, n_split, BM,
                                part_o, part_ml, (bf16_t*)out, b.lse, so);
         }
@@ -674,7 +811,7 @@ void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, i
     if (g.d == 128) {
         long long* dbg = (long long*)b.logits;
         hipLaunchKernelGGL((attn_stream_kernel<128, true, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
-                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, dbg, 1, (float*)nullptr, (float*)nullptr, b.knorm2, so);
+                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, dbg, 1, (float*)nullptr, (float*)nullptr, b.knorm2, so, sp);
         long long h[16];
         (void)hipStreamSynchronize(s);
         (void)hipMemcpy(h, dbg, sizeof(h), hipMemcpyDeviceToHost);
@@ -685,12 +822,21 @@ void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, i
         return;
     }
 #endif
+    if (single_pass) {      // (the caller has checked attn_single_pass_ok)
+        if (g.d == 128)
+            hipLaunchKernelGGL((attn_stream_kernel<128, false, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
+                               (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, 1, (float*)nullptr, (float*)nullptr, b.knorm2, so, sp);
+        else
+            hipLaunchKernelGGL((attn_stream_kernel<64, false, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
+                               (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, 1, (float*)nullptr, (float*)nullptr, b.knorm2, so, sp);
+        return;
+    }
     if (g.d == 128)
         hipLaunchKernelGGL((attn_stream_kernel<128, false, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
-                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, 1, (float*)nullptr, (float*)nullptr, b.knorm2, so);
+                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, 1, (float*)nullptr, (float*)nullptr, b.knorm2, so, sp);
     else
         hipLaunchKernelGGL((attn_stream_kernel<64, false, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
-                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, 1, (float*)nullptr, (float*)nullptr, b.knorm2, so);
+                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, 1, (float*)nullptr, (float*)nullptr, b.knorm2, so, sp);
 }
 
 }  // namespace ckv

@@ -33,6 +33,7 @@ struct DevBuffers {
     float* mu_chunk; // [B,Hkv,max_chunk] scores of the chunk's tokens
     float* attn_part;// [kAttnPartRows, d + 2] bf16 MFMA path: partial outputs, maxima and row sums of a split attention launch
     float* negt;     // [B,Hq,max_chunk+64] bf16 MFMA path: exponent offsets of the score sums (-inf: row does not contribute)
+    float* sp_part;  // [B,Hkv,G,max_chunk/256,vt_tiles,64] single-pass scores only (else null): column sums per row block
     int32_t* offers; // [B,Hkv,2,max_chunk]
     int32_t* winners;// [B,Hkv,N,max_chunk+1]
     void* move_stage;// [B,Hkv,move_stage_rows] x (K row, V row, score, id): sources of the update's moves, gathered before any is overwritten
@@ -86,8 +87,13 @@ void launch_score_simple(const Geom& g, int dtype, const DevBuffers& b, const Se
 int packed_tiles_of(const SegList& sl);
 bool launch_kv_pack(const Geom& g, const DevBuffers& b, const SegList& sl, const TileRuns& runs, int Q, hipStream_t s);
 // It also leaves the exponent offsets of the last tail_rows rows in b.negt for launch_score_mfma.
+// single_pass (only if attn_single_pass_ok): the kernel also leaves the column sums of Alg. 3's single-pass
+// scores in b.sp_part, which launch_single_pass_merge turns into the scores (instead of launch_score_mfma).
+bool attn_single_pass_ok(const Geom& g, const DevBuffers& b, int Q);
 void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, const void* q, float qscale,
-                        int tail_rows, int max_chunk, void* out, hipStream_t s);
+                        int tail_rows, int max_chunk, void* out, bool single_pass, hipStream_t s);
+void launch_single_pass_merge(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, int max_chunk, int tail_rows, float decay,
+                              hipStream_t s);
 void launch_score_mfma(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, int max_chunk,
                        int tail_rows, float decay, hipStream_t s);
 

@@ -104,6 +104,7 @@ extern "C" int cascade_simulate_structure(const cascade_config* cfg, const int32
     view->n_seen = st.n_seen;
     view->pre_count = 0;
     view->last_tokens = 0;
+    view->last_single_pass = 0;
     const int n = st.n_cached(g);
     for (int r = 0; r < g.slots; ++r) {
         const int sl = r < n ? slot_of_rank(g, st, r) : -1;

@@ -41,7 +41,7 @@ int check_config(const cascade_config* c, std::string& why)
     if (c->token_selection != 0 && c->token_selection != 1) { why = "token_selection must be 0 or 1"; return CASCADE_E_INVALID_CONFIG; }
     if (c->head_policy != CASCADE_HEADS_INDEPENDENT && c->head_policy != CASCADE_HEADS_HOMOGENEOUS) { why = "unknown head_policy"; return CASCADE_E_INVALID_CONFIG; }
     if (c->score_mode != CASCADE_SCORES_EXACT && c->score_mode != CASCADE_SCORES_SINGLE_PASS) { why = "unknown score_mode"; return CASCADE_E_INVALID_CONFIG; }
-    if (c->score_mode == CASCADE_SCORES_SINGLE_PASS) { why = "score_mode CASCADE_SCORES_SINGLE_PASS is not available"; return CASCADE_E_UNSUPPORTED; }
+    if (c->score_mode == CASCADE_SCORES_SINGLE_PASS && c->dtype != CASCADE_BF16) { why = "single-pass scores need dtype CASCADE_BF16"; return CASCADE_E_UNSUPPORTED; }
     long slots = c->n_sink;
     for (int i = 0; i < c->n_cascades; ++i) slots += c->cascade_sizes[i];
     if (slots > (1L << 28)) { why = "cache too large"; return CASCADE_E_INVALID_CONFIG; }

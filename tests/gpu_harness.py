@@ -129,6 +129,44 @@ def classify_flips(ref_log, gpu_log, token_selection: int, tau: float):
     return noise, mismatch, downstream
 
 
+def visiting_schedule(cfg: B.cascade_config, st, Q: int):
+    """The order in which the library's chunk attention visits the keys, as the single-pass scores
+    of Alg. 3 need it (an input of the oracle's *_single_pass calls), written from the documented
+    layout: the cache is swept in PHYSICAL order (sinks, then the last cascade ... the first cascade,
+    every ring from its slot 0; a full ring is cut at xi mod 64 and at its head xi), every piece in
+    tiles of 64 keys, then the chunk's own keys; a row block is 256 tokens of one head and visits
+    the chunk's tiles up to its last token.  st: the library's state before the chunk.
+    Returns step_of_key [n + Q] (cache order, then chunk; counted from 1) and steps_of_row [G, Q]."""
+    N = cfg.n_cascades
+    sizes = [cfg.cascade_sizes[i] for i in range(N)]
+    bases, base = [0] * N, cfg.n_sink
+    for c in range(N - 1, -1, -1):
+        bases[c] = base
+        base += sizes[c]
+    pieces = [(0, int(st.counts[0]))]
+    for c in range(N - 1, -1, -1):
+        cnt, cap, xi = int(st.counts[1 + c]), sizes[c], int(st.xi[c])
+        if cnt < cap:
+            pieces.append((bases[c], cnt))
+        else:
+            o = xi % 64
+            pieces += [(bases[c], o), (bases[c] + o, xi - o), (bases[c] + xi, cap - xi)]
+    step_of_slot = np.zeros(cfg.n_sink + sum(sizes), dtype=np.int32)
+    tiles = 0
+    for start, length in pieces:
+        if length <= 0:
+            continue
+        step_of_slot[start:start + length] = tiles + np.arange(length) // 64 + 1
+        tiles += (length + 63) // 64
+    n = st.count
+    step_of_key = np.concatenate([step_of_slot[st.slot[0, 0, :n]], tiles + np.arange(Q) // 64 + 1]).astype(np.int32)
+    assert step_of_key.min() >= 1
+    G = cfg.n_q_heads // cfg.n_kv_heads
+    last_token = (np.arange(Q) // 256 + 1) * 256
+    steps_of_row = np.broadcast_to(tiles + (np.minimum(Q, last_token) + 63) // 64, (G, Q)).astype(np.int32)
+    return step_of_key, steps_of_row
+
+
 def periods_of(cfg: B.cascade_config):
     N = cfg.n_cascades
     p = [cfg.accept_period[i] for i in range(N)]
@@ -168,6 +206,8 @@ class StepReport:
     flips_downstream: int = 0     # comparisons with other participants than the oracle's (after an earlier flip)
     model_out_err: float = 0.0    # bf16 only, on request: outputs / scores against the numpy model that rounds
     model_score_err: float = 0.0  # where the bf16 contract rounds (bf16_model.py)
+    single_pass: bool = False     # the call took Alg. 3's single-pass scores (and the oracle was given the schedule)
+    diverged_from_exact: int = 0  # single pass, on request: cache positions that differ from the EXACT-score oracle's
 
 
 def gpu_decision_scores(st, b, g, npre, n_tok) -> np.ndarray:
@@ -290,10 +330,13 @@ class ParityRun:
 
     # -- one compared step -----------------------------------------------------
     def step(self, q: np.ndarray, k: np.ndarray, v: np.ndarray, decode: bool = False, threaded: bool = False,
-             with_model: bool = False) -> StepReport:
+             with_model: bool = False, exact_twin: bool = False) -> StepReport:
         """q [B,n,Hq,d], k, v [B,n,Hkv,d] float32 (bf16-valued for a bf16 context); decode: n == 1.
         threaded: the oracle evaluates only the compared KV heads, each on a thread of its own.
-        with_model (prefill, bf16, one step ahead): also compare with the bf16 rounding model."""
+        with_model (prefill, bf16, one step ahead): also compare with the bf16 rounding model.
+        exact_twin (single-pass scores, one step ahead): a second oracle takes the same step from the
+        same state with the EXACT scores; the positions where the library's cache then differs from
+        its cache are counted (how far the approximation moves the membership)."""
         cfg = self.cfg
         n_tok = q.shape[1]
         dq, dk, dv = to_device(q, cfg, self.device), to_device(k, cfg, self.device), to_device(v, cfg, self.device)
@@ -308,21 +351,34 @@ class ParityRun:
         out = out.float().cpu().numpy()
         rep = StepReport()
         beta = float(np.float32(cfg.ema_beta))
+        rep.single_pass = bool(st.last_single_pass)
+        schedule = visiting_schedule(cfg, self.prev, n_tok) if rep.single_pass else None
         for b, o in self.oracles.items():
             pre = {g: o.state(g) for g in self.heads}
             for g in range(cfg.n_kv_heads):
                 o.clear_logs(g)
+            twin = None
+            if exact_twin and rep.single_pass:
+                assert self.one_step
+                twin = OracleSeq(self.ocfg)
+                for g in self.heads:
+                    full = o.state(g, with_kv=True)
+                    twin.set_state(g, full.ids, full.mu, full.counts, full.k, full.v, full.t, full.n_seen)
             refs = {}
             if threaded and self.ocfg.head_policy == 0:
                 def work(g, o=o, b=b):
-                    refs[g] = o.chunk(q[b], k[b], v[b], kv_heads=(g, g + 1))
+                    refs[g] = o.chunk(q[b], k[b], v[b], kv_heads=(g, g + 1), schedule=schedule)
+                    if twin is not None:
+                        twin.chunk(q[b], k[b], v[b], kv_heads=(g, g + 1))
                 threads = [threading.Thread(target=work, args=(g,)) for g in self.heads]
                 [t.start() for t in threads]
                 [t.join() for t in threads]
             else:
                 hs = (0, cfg.n_kv_heads) if self.ocfg.head_policy == 1 else (min(self.heads), max(self.heads) + 1)
-                ref = o.chunk(q[b], k[b], v[b], kv_heads=hs)
+                ref = o.chunk(q[b], k[b], v[b], kv_heads=hs, schedule=schedule)
                 refs = {g: ref for g in self.heads}
+                if twin is not None:
+                    twin.chunk(q[b], k[b], v[b], kv_heads=hs)
             for g in self.heads:
                 hq = slice(g * self.G, (g + 1) * self.G)
                 rep.out_err = max(rep.out_err, row_errors(out[b], refs[g], hq))
@@ -338,6 +394,8 @@ class ParityRun:
                 # oracle on its own scores
                 same_start = pre[g].ids.tolist() == self.prev.ids[b, g, :npre].tolist()
                 compare_decisions(cfg, rep, o, g, self.prev, st, b, mu_gpu, same_start, self.tau)
+                if twin is not None:
+                    rep.diverged_from_exact += int((twin.state(g).ids != st.ids[b, g, :st.count]).sum())
                 if with_model:
                     from bf16_model import chunk_reference
                     assert self.one_step and not decode and cfg.dtype == B.CASCADE_BF16 and cfg.head_reduce == 0
@@ -351,6 +409,8 @@ class ParityRun:
                     mu_model = np.concatenate([pre[g].mu * beta ** n_tok, np.zeros(n_tok)]) + md.max(axis=0)
                     relm = np.abs(mu_gpu - mu_model) / np.maximum(np.abs(mu_model), 1e-12)
                     rep.model_score_err = max(rep.model_score_err, float(relm[mu_model > 1e-30].max()))
+            if twin is not None:
+                twin.close()
         if self.one_step:
             self.sync_oracle_from_gpu(st)
         else:

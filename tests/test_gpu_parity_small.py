@@ -355,6 +355,58 @@ def test_homogeneous_heads(oracle_mod, dtype, reduce, hkv, G, d):
     run.close()
 
 
+@pytest.mark.parametrize("case", [
+    # every row of a chunk carries weight; rings of whole and of ragged tiles, two row blocks per head
+    dict(name="sp_all_rows_d128", d=128, Hq=8, Hkv=2, n_sink=64, sizes=[256, 256, 192], beta=0.999, chunks=[512] * 7),
+    # beta = 0.5: only the last 40 rows of a chunk carry weight, so only the last row block of a head adds column sums
+    dict(name="sp_short_tail_d64", d=64, Hq=4, Hkv=2, n_sink=5, sizes=[300, 200], beta=0.5, chunks=[768] * 5),
+    # chunks that do not qualify (not a multiple of 256) take the exact pass in between; mean reduction
+    dict(name="sp_mixed_chunks_mean", d=128, Hq=4, Hkv=1, n_sink=4, sizes=[128, 128, 128], beta=0.99,
+         chunks=[256, 256, 100, 256, 37, 512, 256], head_reduce=B.CASCADE_REDUCE_MEAN),
+], ids=lambda c: c["name"])
+def test_single_pass_scores(oracle_mod, case, monkeypatch):
+    """score_mode = CASCADE_SCORES_SINGLE_PASS: the scores of Alg. 3, added up while the attention
+    kernel sweeps the keys, against the oracle's single-pass scores on the kernel's visiting
+    schedule (gpu_harness.visiting_schedule); outputs, decisions and cached rows as in every other
+    case.  How far the approximation moves the cache is counted against an exact-score twin."""
+    from gpu_harness import ParityRun
+    monkeypatch.setenv("CASCADE_KV_ATTN_SPLITS", "1")     # small launches are otherwise split over the keys (exact pass)
+    cfg = B.make_config(batch=1, n_q_heads=case["Hq"], n_kv_heads=case["Hkv"], head_dim=case["d"], dtype=B.CASCADE_BF16,
+                        n_sink=case["n_sink"], cascade_sizes=case["sizes"], ema_beta=case["beta"], rope_base=10000.0,
+                        max_chunk=max(case["chunks"]), head_reduce=case.get("head_reduce", 0), keep_update_scores=1,
+                        score_mode=B.CASCADE_SCORES_SINGLE_PASS)
+    tol_out, tol_score = _tolerances(cfg)
+    rng = np.random.default_rng(41)
+    run = ParityRun(cfg, one_step_ahead=True)
+    worst_out = worst_score = 0.0
+    diverged = compared = taken = 0
+    for i, n in enumerate(case["chunks"]):
+        q, k, v = _inputs(rng, cfg, n)
+        rep = run.step(q, k, v, exact_twin=True)
+        assert rep.single_pass == (n % 256 == 0), (i, n)
+        assert rep.replay_exact, (case["name"], i)
+        assert rep.flips_mismatch == 0, (case["name"], i, rep)
+        worst_out, worst_score = max(worst_out, rep.out_err), max(worst_score, rep.score_err)
+        if rep.single_pass:
+            taken += 1
+            diverged += rep.diverged_from_exact
+            compared += rep.compared
+    print(f"{case['name']}: out {worst_out:.3e} score {worst_score:.3e}; {taken} single-pass chunks, cache positions that "
+          f"differ from the exact-score oracle's: {diverged}/{compared}")
+    assert worst_out <= tol_out and worst_score <= tol_score
+    assert taken >= 4
+    run.close()
+
+
+def test_single_pass_needs_bf16():
+    cfg = B.make_config(batch=1, n_q_heads=2, n_kv_heads=1, head_dim=64, dtype=B.CASCADE_F32, n_sink=1, cascade_sizes=[4],
+                        ema_beta=0.9, rope_base=10000.0, max_chunk=8, score_mode=B.CASCADE_SCORES_SINGLE_PASS)
+    assert B.cascade_workspace_bytes(cfg) == 0
+    with pytest.raises(B.CascadeError) as e:
+        B.cascade_init(cfg, 256, 1 << 20)
+    assert e.value.code == B.CASCADE_E_UNSUPPORTED
+
+
 def test_layers_share_scratch_without_interfering(oracle_mod):
     """Three layers over one workspace (the layer loop of Alg. 1), fed different inputs in turn,
     prefill and decode: the middle layer is compared with the oracle at every step, the outer

@@ -40,7 +40,7 @@ def test_struct_layouts_match_header(lib):
     # sizes follow from the field lists of include/cascade_kv.h
     assert ctypes.sizeof(B.cascade_config) == 7 * 4 + 16 * 4 * 2 + 3 * 4 + 3 * 4 + 4 + 4 + 2 * 4
     assert ctypes.sizeof(B.cascade_init_state) == 4 * 8 + 17 * 4 + 4 + 2 * 8
-    assert ctypes.sizeof(B.cascade_state_view) == 9 * 8 + 17 * 4 + 16 * 4 + 4 + 2 * 16 * 8 + 2 * 8 + 3 * 4 + 4
+    assert ctypes.sizeof(B.cascade_state_view) == 9 * 8 + 17 * 4 + 16 * 4 + 4 + 2 * 16 * 8 + 2 * 8 + 4 * 4
 
 
 @pytest.mark.parametrize("kw,code", [

@@ -99,3 +99,32 @@ def test_flip_classification():
     other = (np.array([[5, 4], [7, 5], [9, 8], [11, 10]]), ref[1])                       # after 5 replaced 4
     assert classify_flips(ref, other, 1, 2.0 ** -6) == (0, 0, 1)
     assert classify_flips(ref, wide, 0, 2.0 ** -6) == (0, 0, 0)                          # nothing is ever replaced
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_visiting_schedule_covers_every_key_once(seed):
+    """The visiting schedule handed to the single-pass oracle, built from the documented layout on the
+    structure the library's host replay reports: tiles of at most 64 keys, numbered without gaps,
+    the keys of one tile contiguous in physical order, the chunk's tiles after the cache's."""
+    from gpu_harness import visiting_schedule
+    from paper_2406_17808_amd import binding as B
+    rng = np.random.default_rng(300 + seed)
+    N = int(rng.integers(1, 5))
+    sizes = [int(rng.integers(1, 6)) * 50 for _ in range(N)]
+    cfg = B.make_config(batch=1, n_q_heads=4, n_kv_heads=2, head_dim=64, dtype=B.CASCADE_BF16, n_sink=int(rng.integers(0, 70)),
+                        cascade_sizes=sizes, ema_beta=0.9, rope_base=10000.0, max_chunk=512)
+    chunks = [int(x) for x in rng.integers(1, 400, size=int(rng.integers(1, 12)))]
+    st = B.cascade_simulate_structure(cfg, chunks)
+    st.slot = st.slot[None, None]
+    Q = 512
+    step_of_key, steps_of_row = visiting_schedule(cfg, st, Q)
+    n = st.count
+    assert step_of_key.shape == (n + Q,) and steps_of_row.shape == (2, Q)
+    cache_tiles = int(step_of_key[:n].max()) if n else 0
+    assert sorted(set(step_of_key[:n].tolist())) == list(range(1, cache_tiles + 1))
+    slot = st.slot[0, 0, :n]
+    for t in range(1, cache_tiles + 1):
+        members = np.sort(slot[step_of_key[:n] == t])
+        assert 1 <= len(members) <= 64 and members[-1] - members[0] == len(members) - 1      # one run of physical slots
+    assert step_of_key[n:].tolist() == [cache_tiles + j // 64 + 1 for j in range(Q)]
+    assert steps_of_row[0, 0] == cache_tiles + 4 and steps_of_row[1, 511] == cache_tiles + 8
