@@ -65,7 +65,7 @@ def prefill_bench(args, torch, B, wl):
     from paper_2406_17808_amd.workloads import chunk_inputs_torch
     dev = "cuda:0"
     W, K = args.warmup, args.steps
-    cfg = config_of(wl)
+    cfg = config_of(wl, score_mode=B.CASCADE_SCORES_SINGLE_PASS if args.score_mode == "single_pass" else B.CASCADE_SCORES_EXACT)
     # cached rows before every chunk (host arithmetic; the fill does not depend on the scores)
     n_before = [B.cascade_simulate_structure(cfg, [wl.chunk] * c).count if c else 0 for c in range(wl.n_chunks + 1)]
     # setup chunks: the stream from its start until every slot is occupied
@@ -256,6 +256,9 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--cpu-sample-tokens", type=int, default=640)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--score-mode", choices=["exact", "single_pass"], default="exact",
+                    help="exact: the EMA scores use the final softmax probabilities (default, the mode parity is stated for); "
+                         "single_pass: the scores of Alg. 3, accumulated inside the attention kernel")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the untimed leg that measures read / copy / MFMA ceilings")
     ap.add_argument("--only-decode", action="store_true")
@@ -286,7 +289,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "seq_len": wl.seq_len, "chunk": wl.chunk, "n_sink": wl.n_sink,
                    "cascades": list(wl.cascade_sizes), "n_q_heads": wl.n_q_heads, "n_kv_heads": wl.n_kv_heads,
-                   "head_dim": wl.head_dim, "ema_beta": wl.ema_beta, "n_slots": wl.n_slots, "setup_chunks": res["setup_chunks"],
+                   "head_dim": wl.head_dim, "ema_beta": wl.ema_beta, "score_mode": args.score_mode, "n_slots": wl.n_slots, "setup_chunks": res["setup_chunks"],
                    "timed_chunks": res["timed_chunks"], "cache_rows_first_timed": res["cache_rows_first_timed"],
                    "cache_rows_last_timed": res["cache_rows_last_timed"]},
         "roofline": res["roofline"], "kernel_ms_per_step": res["kernel_ms_per_step"],

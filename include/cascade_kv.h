@@ -91,9 +91,11 @@ typedef struct cascade_config {
                                  after that tile.  Tiles are 64 keys in the physical order of the cache (sinks, last
                                  cascade, ..., first cascade, every ring from its slot 0, pieces cut where a ring head
                                  sits), then the chunk's keys.  No second pass over the keys; the scores depend on that
-                                 order and are an approximation of the exact ones.  A chunk whose length is not a
-                                 multiple of 256, or whose launch is split over the keys (fewer than 129 row blocks in
-                                 all), takes the exact pass: cascade_state_view.last_single_pass says which it was. */
+                                 order and are an approximation of the exact ones.  Taken by the chunks all of whose
+                                 rows carry EMA weight (see score_tail_eps: an EMA parameter close to 1, the paper's
+                                 0.9999), whose length is a multiple of 256 and whose launch is not split over the keys
+                                 (more than 128 row blocks in all); other chunks take the exact pass, which is short
+                                 when few rows carry weight: cascade_state_view.last_single_pass says which it was. */
 } cascade_config;
 
 typedef struct cascade_ctx cascade_ctx;

@@ -468,7 +468,7 @@ extern "C" int cascade_prefill_chunk(cascade_ctx* ctx, const void* dev_q, const 
     // the MFMA kernels take logits directly as base-2 exponents
     const float qscale = ctx->mfma ? g.scale * 1.4426950408889634f : 1.f;
     const int tail = Q < ctx->tail_k ? Q : ctx->tail_k;    // rows that carry weight in the score sums
-    const bool single_pass = ctx->mfma && attn_single_pass_ok(g, ctx->buf, Q);
+    const bool single_pass = ctx->mfma && attn_single_pass_ok(g, ctx->buf, Q, tail);
     ctx->last_single_pass = single_pass;
     {
         Timed t(ctx, CASCADE_K_PREP, s);
@@ -508,7 +508,7 @@ extern "C" int cascade_prefill_chunk(cascade_ctx* ctx, const void* dev_q, const 
     const float decay = (float)pow((double)g.beta, (double)Q);
     {
         Timed t(ctx, CASCADE_K_SCORES, s);
-        if (single_pass) launch_single_pass_merge(g, ctx->buf, sl, Q, ctx->max_chunk, tail, decay, s);
+        if (single_pass) launch_single_pass_merge(g, ctx->buf, sl, Q, ctx->max_chunk, decay, s);
         else if (ctx->mfma) launch_score_mfma(g, ctx->buf, sl, Q, ctx->max_chunk, tail, decay, s);
         else launch_score_simple(g, ctx->dtype, ctx->buf, sl, Q, ctx->max_chunk, tail, decay, s);
         if (g.head_policy == CASCADE_HEADS_HOMOGENEOUS && g.Hkv > 1) launch_share_scores(g, ctx->buf, Q, ctx->max_chunk, s);

@@ -145,9 +145,7 @@ struct ScoreOffsets {
 // `part`: [row block][tile][64 keys], written tile by tile with plain stores (no atomics: the sums
 // are the same from run to run); single_pass_merge_kernel adds the row blocks up.
 struct SinglePass {
-    float* part;         // [B*Hkv][G][rb_count][tiles_per_bh][64]
-    int rb_first;        // first row block (of a head's Q / 256) with a row that carries EMA weight
-    int rb_count;        // row blocks from there to the end of the chunk
+    float* part;         // [B*Hkv][G][Q / 256][tiles_per_bh][64]
 };
 
 __device__ inline void write_score_offset(const ScoreOffsets& so, size_t head, int Q, int i, float lse2)
@@ -160,7 +158,8 @@ __device__ inline void write_score_offset(const ScoreOffsets& so, size_t head, i
 // SPLIT: the tiles a row block visits are divided over n_split workgroups (for launches too small
 // to fill the chip otherwise); each writes its unnormalised output, running maximum and row sum
 // to part_o / part_ml, and attn_merge_kernel combines them.
-// SP: single-pass scores (needs Q % 256 == 0 and no SPLIT: a row block is one head's 256 tokens).
+// SP: single-pass scores (needs Q % 256 == 0 and no SPLIT: a row block is one head's 256 tokens; and
+// every row of the chunk carrying EMA weight, so that every row block takes part).
 template <int D, bool DBG, bool SPLIT, bool SP = false>
 __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     Geom g, SegList sl, int Q, int tiles_per_bh, const bf16_t* __restrict__ q, const float2* __restrict__ rope, float qscale,
@@ -297,22 +296,14 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
                 s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[ks].v, s[kb], 0, 0, 0);
             }
     };
-    // The vector block of one tile: mask the keys a query may not see (past the end of the
-    // segment; later chunk tokens), take the row maximum of S^T (relative to m_run), raise m_run only
-    // when that exceeds kRescaleLog2 (the probabilities then stay below 2^kRescaleLog2, and most
-    // tiles skip the rescaling of O), and turn S^T into probabilities.  FIRST: S^T is absolute
-    // and m_run not set yet (the first tile of a workgroup).
-    // Single-pass scores: a row block is 256 tokens of one head (Q % 256 == 0); it takes part if one
-    // of its rows carries EMA weight.  cw: the weight of this lane's row (Alg. 3's C_EMA).
+    // Single-pass scores: a row block is 256 tokens of one head (Q % 256 == 0).  cw: the weight of this
+    // lane's row (Alg. 3's C_EMA).
     const int rbs_per_head = SP ? Q / BM : 1;
-    const bool sp_on = SP && (tile % rbs_per_head) >= sp.rb_first;     // uniform for the workgroup
-    const float cw = (SP && qvalid && qi >= Q - so.tail) ? so.wrow[Q - 1 - qi] : 0.f;
-    float inv_steps = 0.f;               // 1 / tiles this row block visits, set once they are counted
-    float* sp_part = SP ? sp.part + ((((size_t)bh * g.G + tile / rbs_per_head) * sp.rb_count + (tile % rbs_per_head - sp.rb_first)) *
-                                     (size_t)tiles_per_bh) * kBN
-                        : nullptr;
+    const float cw = (SP && qvalid) ? so.wrow[Q - 1 - qi] : 0.f;
+    float* sp_part = SP ? sp.part + ((size_t)bh * g.G * rbs_per_head + tile) * (size_t)tiles_per_bh * kBN : nullptr;
     // after the reduction below lane l holds the column sum of key 4*half + 32*(l32 >> 4) + 8*((l32 & 15) >> 2) + (l32 & 3)
     const int sp_key = 4 * half + 32 * (l32 >> 4) + 8 * ((l32 & 15) >> 2) + (l32 & 3);
+    float inv_steps = 0.f;               // 1 / tiles this row block visits, set once they are counted
     // Column sums over the 32 queries of this wave of  p * w  (w per query), for the 64 keys of a
     // tile: s[][] holds p (fp32) on entry.  A reduce-scatter over the five lane bits of the query
     // index: at every level the lanes of a pair each keep half of the values and add the partner's
@@ -322,7 +313,8 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
         return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), decltype(ctrl)::value, 0xf, 0xf, true));
     };
     auto column_sums = [&](int step) {
-        const float lt = lsum + __shfl_xor(lsum, 32, 64);
+        const auto lp = __builtin_amdgcn_permlane32_swap(__float_as_uint(lsum), __float_as_uint(lsum), false, false);
+        const float lt = __uint_as_float(lp[0]) + __uint_as_float(lp[1]);    // both halves of the row's keys
         // gamma / (gamma + rho) = step / NT; a row always sees a key of its first tile, so lt > 0
         const float w = cw * (float)step * inv_steps * __builtin_amdgcn_rcpf(lt);
         const auto wp = __builtin_amdgcn_permlane16_swap(__float_as_uint(w), __float_as_uint(w), false, false);
@@ -365,6 +357,11 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
         for (int w = 0; w < kSWaves; ++w) acc += sp_sum[(t + 1) & 1][w][l];
         counted_store_f32(sp_part, (uint32_t)((t * kBN + l) * 4), acc);
     };
+    // The vector block of one tile: mask the keys a query may not see (past the end of the
+    // segment; later chunk tokens), take the row maximum of S^T (relative to m_run), raise m_run only
+    // when that exceeds kRescaleLog2 (the probabilities then stay below 2^kRescaleLog2, and most
+    // tiles skip the rescaling of O), and turn S^T into probabilities.  FIRST: S^T is absolute
+    // and m_run not set yet (the first tile of a workgroup).
     auto softmax_tile = [&](const TileIter& it, bool first, auto interior, int step) {
         if (!decltype(interior)::value && ((it.t0 + kBN > it.sg.len) || (it.sg.chunk && it.t0 + kBN - 1 > wave_imin))) {
             const int lim = it.sg.chunk ? min(it.sg.len - 1, qi) : it.sg.len - 1;   // last visible key
@@ -420,7 +417,7 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
                 if (SP) { s[kb][hf * 8 + 2 * x2] = p0; s[kb][hf * 8 + 2 * x2 + 1] = p1; }
             }
         }
-        if (SP && sp_on) column_sums(step);
+        if (SP) column_sums(step);
     };
     auto wave_active = [&](const TileIter& it) { return !(it.sg.chunk && it.t0 > wave_imax); };
 
@@ -570,7 +567,7 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
                 // measured orders of the three parts: exponentials, fragments, copies (this one) 3.329 ms;
                 // fragments first 3.35; copies before the fragments 3.41
                 softmax_tile(it1, false, std::true_type(), n0 + 2);
-                if (SP && sp_on && wave == (n0 & 3)) flush_column_sums(n0);
+                if (SP && wave == (n0 & 3)) flush_column_sums(n0);
 #pragma unroll
                 for (int i = 0; i < kAhead; ++i) fr[i] = read_frag(Vs + ((n0 + 1) & 3) * TILE, Ks, i);
                 copy_tile(kt_bh, lds_k, n0 + 4, n0 & 3);
@@ -608,9 +605,9 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
             for (int qt = 0; qt < 4; ++qt)
 #pragma unroll
                 for (int x = 0; x < 4; ++x) pf[qt].u[x] = 0u;
-            if (SP && sp_on) sp_sum[n0 & 1][wave][l] = 0.f;      // this wave sees nothing of tile n0 + 1 (step n0 + 2)
+            if (SP) sp_sum[n0 & 1][wave][l] = 0.f;      // this wave sees nothing of tile n0 + 1 (step n0 + 2)
         }
-        if (SP && sp_on && wave == (n0 & 3)) flush_column_sums(n0);
+        if (SP && wave == (n0 & 3)) flush_column_sums(n0);
         lap(3);
         publish(in_flight);
         wg_barrier();     // barrier 2t+2 (early group), 2t+3 (late group)
@@ -619,7 +616,7 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
         ++n0;
     }
     if (!late) wg_barrier();   // the late group passed one barrier more
-    if (SP && sp_on && wave == 0) flush_column_sums(n0);   // the last tile: every wave has left its vector block
+    if (SP && wave == 0) flush_column_sums(n0);   // the last tile: every wave has left its vector block
     if (DBG && blockIdx.x == 100 && l == 0 && (wave == 0 || wave == 4)) {
 #pragma unroll
         for (int i = 0; i < 5; ++i) dbg[(wave / 4) * 8 + i] = tc[i];
@@ -736,12 +733,12 @@ __global__ __launch_bounds__(kBN) void single_pass_merge_kernel(Geom g, SegList 
     const int t0 = (n - first) * kBN, key = t0 + x;
     if (key >= sg.len) return;
     // row block r of a head covers tokens 256 r .. 256 r + 255 and visits the chunk's tiles up to its last token
-    const int r_lo = sg.chunk ? max(0, t0 / 256 - sp.rb_first) : 0;
+    const int rbs = Q / 256, r_lo = sg.chunk ? t0 / 256 : 0;
     float red = 0.f;
     for (int hh = 0; hh < g.G; ++hh) {
-        const float* p = sp.part + ((((size_t)bh * g.G + hh) * sp.rb_count) * (size_t)tiles_per_bh + n) * kBN + x;
+        const float* p = sp.part + ((((size_t)bh * g.G + hh) * rbs) * (size_t)tiles_per_bh + n) * kBN + x;
         float v = 0.f;
-        for (int r = r_lo; r < sp.rb_count; ++r) v += p[(size_t)r * tiles_per_bh * kBN];
+        for (int r = r_lo; r < rbs; ++r) v += p[(size_t)r * tiles_per_bh * kBN];
         red = g.head_reduce == CASCADE_REDUCE_MAX ? (hh == 0 ? v : fmaxf(red, v)) : red + v;
     }
     if (g.head_reduce == CASCADE_REDUCE_MEAN) red /= (float)g.G;
@@ -764,18 +761,18 @@ int attn_splits(const Geom& g, int Q, int forced)
     return n < 1 ? 1 : n;
 }
 
-// A chunk takes the single-pass scores when its launch is not split over the keys and its row blocks
-// are whole heads' pieces (Q a multiple of 256); other chunks of such a context take the exact pass.
-bool attn_single_pass_ok(const Geom& g, const DevBuffers& b, int Q)
+// A chunk takes the single-pass scores when every one of its rows carries EMA weight (an EMA
+// parameter close to 1, the paper's setting: otherwise the exact pass is short, and cheaper than
+// column sums in every row block), its launch is not split over the keys, and its row blocks are
+// whole heads' pieces (Q a multiple of 256); other chunks of such a context take the exact pass.
+bool attn_single_pass_ok(const Geom& g, const DevBuffers& b, int Q, int tail_rows)
 {
-    return b.sp_part != nullptr && Q % (kSWaves * 32) == 0 && attn_splits(g, Q, b.opt_attn_splits) == 1;
+    return b.sp_part != nullptr && tail_rows >= Q && Q % (kSWaves * 32) == 0 && attn_splits(g, Q, b.opt_attn_splits) == 1;
 }
 
-void launch_single_pass_merge(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, int max_chunk, int tail_rows, float decay,
-                              hipStream_t s)
+void launch_single_pass_merge(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, int max_chunk, float decay, hipStream_t s)
 {
-    const int rb_first = (Q - tail_rows) / (kSWaves * 32);
-    const SinglePass sp = {b.sp_part, rb_first, Q / (kSWaves * 32) - rb_first};
+    const SinglePass sp = {b.sp_part};
     hipLaunchKernelGGL(single_pass_merge_kernel, dim3(packed_tiles(sl), g.B * g.Hkv), dim3(kBN), 0, s, g, sl, Q, max_chunk, b.vt_tiles, sp,
                        decay, b.mu, b.mu_chunk);
 }
@@ -784,8 +781,7 @@ void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, i
                         int tail_rows, int max_chunk, void* out, bool single_pass, hipStream_t s)
 {
     const ScoreOffsets so = {b.wrow, b.negt, tail_rows, max_chunk + kScorePadRows};
-    const int sp_rb_first = (Q - tail_rows) / (kSWaves * 32);
-    const SinglePass sp = {b.sp_part, sp_rb_first, Q / (kSWaves * 32) - sp_rb_first};
+    const SinglePass sp = {b.sp_part};
     const int tiles_per_bh = b.vt_tiles;   // stride between the packed streams of two (batch, KV head)
     constexpr int BM = kSWaves * 32;
     const int tiles = (g.G * Q + BM - 1) / BM;

@@ -442,7 +442,7 @@ __device__ inline bool move_entry(const Geom& g, const UpdatePlan& pl, const Mov
         *ref = g.slots + e;
         return true;
     }
-    if (direct && c == 0) {              // J < cap: entry e is slot j = e; no offer competes in the first cascade
+    if (direct && c == 0) {              // J <= cap: entry e is slot j = e; no offer competes in the first cascade
         const CascStep& cs = pl.c[0];
         *dst = cs.base + (cs.wpos0 + e) % cs.cap;
         *ref = offer_ref_direct(pl, 0, e < cs.A ? e : cs.kp0 + (e - cs.A) * cs.pstride, g.slots);
@@ -559,7 +559,7 @@ __global__ void gather_direct_kernel(Geom g, UpdatePlan pl, MoveList ml, int n_e
         c = ml.c[i];
         {
             const CascStep& cs = pl.c[c];
-            // entry e < E is slot j = e of the J < cap slots opened (final_entry); entry E is the segment of
+            // entry e < E is slot j = e of the J <= cap slots opened (final_entry); entry E is the segment of
             // the item that was newest before the update
             const int e = eg - ml.first[i];
             j = e < ml.E[i] ? e : -1;

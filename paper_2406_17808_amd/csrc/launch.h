@@ -89,11 +89,10 @@ bool launch_kv_pack(const Geom& g, const DevBuffers& b, const SegList& sl, const
 // It also leaves the exponent offsets of the last tail_rows rows in b.negt for launch_score_mfma.
 // single_pass (only if attn_single_pass_ok): the kernel also leaves the column sums of Alg. 3's single-pass
 // scores in b.sp_part, which launch_single_pass_merge turns into the scores (instead of launch_score_mfma).
-bool attn_single_pass_ok(const Geom& g, const DevBuffers& b, int Q);
+bool attn_single_pass_ok(const Geom& g, const DevBuffers& b, int Q, int tail_rows);
 void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, const void* q, float qscale,
                         int tail_rows, int max_chunk, void* out, bool single_pass, hipStream_t s);
-void launch_single_pass_merge(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, int max_chunk, int tail_rows, float decay,
-                              hipStream_t s);
+void launch_single_pass_merge(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, int max_chunk, float decay, hipStream_t s);
 void launch_score_mfma(const Geom& g, const DevBuffers& b, const SegList& sl, int Q, int max_chunk,
                        int tail_rows, float decay, hipStream_t s);
 

@@ -23,15 +23,16 @@ __host__ __device__ inline int offer_ref(int c, int k, int slots, int n_to_sink,
     return c == 0 ? slots + n_to_sink + k : off_in[k];
 }
 
-// When no cascade has a slot written twice in one update (J < cap for every cascade: the usual
-// case, a chunk shorter than every ring), the item a push evicts is simply what its ring position
-// held before the update, so the offers of cascade c can be named without knowing any winner of
-// cascade c - 1, and the segments of ALL cascades can be decided at the same time.
+// When no cascade has a slot written twice in one update (J <= cap for every cascade: the usual
+// case, a chunk no longer than any ring), and none overwrites the slot whose holder the first
+// offers compete for, the item a push evicts is simply what its ring position held before the
+// update: the offers of cascade c can be named without knowing any winner of cascade c - 1, and the
+// segments of ALL cascades can be decided at the same time.
 __host__ __device__ inline bool plan_is_direct(const UpdatePlan& pl)
 {
     for (int c = 0; c < pl.N; ++c) {
         if (pl.c[c].M == 0) break;
-        if (pl.c[c].J >= pl.c[c].cap) return false;
+        if (pl.c[c].J > pl.c[c].cap || (pl.c[c].J == pl.c[c].cap && pl.c[c].pre)) return false;
     }
     return true;
 }

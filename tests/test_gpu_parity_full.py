@@ -95,26 +95,33 @@ def test_prefill_131k_sampled_heads(oracle_mod):
     run.close()
 
 
-def test_prefill_paper_16k_all_rows_in_scores(oracle_mod):
+@pytest.mark.parametrize("mode", ["exact", "single_pass"])
+def test_prefill_paper_16k_all_rows_in_scores(oracle_mod, mode):
     """The geometry of the paper's latency figure: 64 sinks + 4 x 4096 slots, stride 4096, EMA decay
     0.9999, so every one of the 4096 query rows of a chunk enters the score sums (sixteen passes of
-    the score kernel).  Eight chunks; the seventh (three cascades full, discards under way) compared whole
-    on two KV heads."""
+    the score kernel; or, with score_mode single_pass, the column sums of Alg. 3 inside the attention
+    kernel, compared with the oracle's single-pass scores on the kernel's visiting schedule).  Eight
+    chunks; the seventh (three cascades full, discards under way) compared whole on two KV heads.
+    For the single-pass scores the cache positions that end up different from those of an oracle
+    that takes the same chunk with the exact scores are counted and reported."""
     from gpu_harness import ParityRun
     from paper_2406_17808_amd.cache import config_of
     wl = WORKLOADS["prefill_paper_16k"]
-    cfg = config_of(wl, keep_update_scores=1)
+    sp = mode == "single_pass"
+    cfg = config_of(wl, keep_update_scores=1, score_mode=B.CASCADE_SCORES_SINGLE_PASS if sp else B.CASCADE_SCORES_EXACT)
     run = ParityRun(cfg, one_step_ahead=True, kv_heads=[0, 5])
     rep = None
     for c in range(8):
         dq, dk, dv = chunk_inputs_torch(wl, 0, c, "cuda:0")
         if c == 6:
             run.sync_oracle_from_gpu()
-            print("prefill_paper_16k: comparing chunk 6", flush=True)
-            rep = run.step(_host(dq), _host(dk), _host(dv), threaded=True)
+            print(f"prefill_paper_16k ({mode}): comparing chunk 6", flush=True)
+            rep = run.step(_host(dq), _host(dk), _host(dv), threaded=True, exact_twin=sp)
         else:
             run.advance_gpu_only(dq, dk, dv)
-    print(f"prefill_paper_16k: out {rep.out_err:.3e} score {rep.score_err:.3e} drift {rep.drift}/{rep.compared}")
+    print(f"prefill_paper_16k ({mode}): out {rep.out_err:.3e} score {rep.score_err:.3e} drift {rep.drift}/{rep.compared}"
+          + (f"; cache positions that differ from the exact-score oracle's: {rep.diverged_from_exact}/{rep.compared}" if sp else ""))
+    assert rep.single_pass == sp
     assert rep.replay_exact and rep.flips_mismatch == 0, rep
     assert rep.out_err <= TOL_OUT and rep.score_err <= TOL_SCORE
     st = run.gpu.read_state()
