@@ -71,8 +71,9 @@ def prefill_bench(args, torch, B, wl):
     # setup chunks: the stream from its start until every slot is occupied
     F = next((c for c in range(wl.n_chunks + 1) if n_before[c] == wl.n_slots), None)
     if F is None and wl.name != HEADLINE:
-        # a stream too short to fill its cache (Eq. 4: the span of the cascades exceeds it): time its last chunks
-        F = max(wl.n_chunks - W - K, 0)
+        # a stream too short to fill its cache (Eq. 4: the span of the cascades exceeds it): time its last
+        # chunks but sixteen, which the per-family breakdown takes
+        F = max(wl.n_chunks - W - K - 16, 0)
     if F is None or F + W + K > wl.n_chunks:
         print(f"bench.py: {wl.name} has {wl.n_chunks} chunks; {F} fill the cache, so --warmup + --steps "
               f"must not exceed {wl.n_chunks - (F or 0)}", file=sys.stderr)

@@ -176,30 +176,18 @@ __global__ void prep_kernel(Geom g, SegList sl, int Q, float qscale, int q_first
                             T* __restrict__ Qr, T* __restrict__ Krc, T* __restrict__ Vch)
 {
     const int half = g.d / 2, groups = half / 8;
-    const int rows_per_tok = g.Hq + 2 * g.Hkv;          // per (b, i): query heads, K heads, V heads
+    // threads [0, n_kv): one per (sequence, token, K or V head, group); then one per (sequence, query row
+    // that needs rotated copies, query head, group)
     const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    const long total = (long)g.B * Q * rows_per_tok * groups;
-    if (idx >= total) return;
-    const int e = (int)(idx % groups) * 8;
-    long r = idx / groups;
-    const int row = (int)(r % rows_per_tok);
-    r /= rows_per_tok;
-    const int i = (int)(r % Q), b = (int)(r / Q);
+    const long n_kv = (long)g.B * Q * 2 * g.Hkv * groups;
+    const int q_rows = Q - q_first_row;
     float x0[8], x1[8];
-    if (row < g.Hq) {
-        if (i < q_first_row) return;     // the attention kernel rotates its queries itself
-        const int h = row;
-        const size_t src = (((size_t)b * Q + i) * g.Hq + h) * g.d;
-        Vec8<T>::load(q + src + e, x0);
-        Vec8<T>::load(q + src + e + half, x1);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) { x0[j] *= qscale; x1[j] *= qscale; }
-        for (int vq = 0; vq < sl.n_qvar; ++vq) {
-            const size_t dst = ((((size_t)vq * g.B + b) * g.Hq + h) * Q + i) * g.d;
-            rotate8<T>(x0, x1, rope + (size_t)(sl.qrot0[vq] + i) * half + e, Qr + dst + e, Qr + dst + e + half);
-        }
-    } else {
-        const int rr = row - g.Hq;
+    if (idx < n_kv) {
+        const int e = (int)(idx % groups) * 8;
+        long r = idx / groups;
+        const int rr = (int)(r % (2 * g.Hkv));
+        r /= 2 * g.Hkv;
+        const int i = (int)(r % Q), b = (int)(r / Q);
         const int h = rr % g.Hkv;
         const size_t src = (((size_t)b * Q + i) * g.Hkv + h) * g.d;
         const size_t dst = (((size_t)b * g.Hkv + h) * Q + i) * g.d;
@@ -213,6 +201,23 @@ __global__ void prep_kernel(Geom g, SegList sl, int Q, float qscale, int q_first
             Vec8<T>::store(Vch + dst + e, x0);
             Vec8<T>::store(Vch + dst + e + half, x1);
         }
+        return;
+    }
+    const long qidx = idx - n_kv;
+    if (qidx >= (long)g.B * q_rows * g.Hq * groups) return;
+    const int e = (int)(qidx % groups) * 8;
+    long r = qidx / groups;
+    const int h = (int)(r % g.Hq);
+    r /= g.Hq;
+    const int i = q_first_row + (int)(r % q_rows), b = (int)(r / q_rows);
+    const size_t src = (((size_t)b * Q + i) * g.Hq + h) * g.d;
+    Vec8<T>::load(q + src + e, x0);
+    Vec8<T>::load(q + src + e + half, x1);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { x0[j] *= qscale; x1[j] *= qscale; }
+    for (int vq = 0; vq < sl.n_qvar; ++vq) {
+        const size_t dst = ((((size_t)vq * g.B + b) * g.Hq + h) * Q + i) * g.d;
+        rotate8<T>(x0, x1, rope + (size_t)(sl.qrot0[vq] + i) * half + e, Qr + dst + e, Qr + dst + e + half);
     }
 }
 
@@ -263,7 +268,7 @@ void launch_prep(const Geom& g, int dtype, const DevBuffers& b, const SegList& s
 {
     const dim3 block(256);
     if (g.d % 16 == 0) {
-        const long n = (long)g.B * Q * (g.Hq + 2 * g.Hkv) * (g.d / 16);
+        const long n = (long)g.B * (Q * 2 * g.Hkv + (Q - q_first_row) * g.Hq) * (g.d / 16);
         const dim3 grid((unsigned)((n + 255) / 256));
         if (dtype == CASCADE_F32)
             hipLaunchKernelGGL(prep_kernel<float>, grid, block, 0, s, g, sl, Q, qscale, q_first_row, b.rope, (const float*)q, (const float*)k,
