@@ -178,6 +178,7 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     __shared__ __attribute__((aligned(1024))) bf16_t Vs[kSStages * TILE];
     __shared__ float kn_wave[kSWaves];
     __shared__ float sp_sum[SP ? 2 : 1][SP ? kSWaves : 1][SP ? kBN : 1];   // per-wave column sums of the last two tiles
+    __shared__ __attribute__((aligned(16))) float sp_w[SP ? kSWaves : 1][SP ? 32 : 4];   // the weights of a wave's 32 queries
 
     const int BH = g.B * g.Hkv;
     // consecutive workgroups: different KV heads; row blocks that see more of the chunk (longer loops) start first
@@ -301,53 +302,60 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     const int rbs_per_head = SP ? Q / BM : 1;
     const float cw = (SP && qvalid) ? so.wrow[Q - 1 - qi] : 0.f;
     float* sp_part = SP ? sp.part + ((size_t)bh * g.G * rbs_per_head + tile) * (size_t)tiles_per_bh * kBN : nullptr;
-    // after the reduction below lane l holds the column sum of key 4*half + 32*(l32 >> 4) + 8*((l32 & 15) >> 2) + (l32 & 3)
-    const int sp_key = 4 * half + 32 * (l32 >> 4) + 8 * ((l32 & 15) >> 2) + (l32 & 3);
     float inv_steps = 0.f;               // 1 / tiles this row block visits, set once they are counted
-    // Column sums over the 32 queries of this wave of  p * w  (w per query), for the 64 keys of a
-    // tile: s[][] holds p (fp32) on entry.  A reduce-scatter over the five lane bits of the query
-    // index: at every level the lanes of a pair each keep half of the values and add the partner's
-    // (lanes l and l^16 by v_permlane16_swap, with the weights folded into that first level, the
-    // rest by DPP), so that after five levels every lane holds the sum of one key (sp_key).
-    auto dpp = [](float x, auto ctrl) {
-        return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), decltype(ctrl)::value, 0xf, 0xf, true));
-    };
+    // Column sums over the 32 queries of this wave of  p * w  (w per query), for the 64 keys of a tile.
+    // A lane owns a query, so the sum runs across lanes; the matrix pipe does the transposition: the
+    // probabilities are already packed as an MFMA operand (pf, for O^T = V^T P^T); taken as the A operand
+    // (rows: queries, contraction: 16 keys) against a 0/1 matrix that sends contraction index k to the
+    // column of its key, two MFMAs per 32-key block leave P with the KEYS across the lanes and the
+    // queries in the 16 accumulator registers (S^T is dead by now: its registers take the result).
+    // What is left is an in-lane weighted sum (the weights of the wave's 32 queries go through LDS, 16 of
+    // them per lane) and one exchange between the two lane halves, after which lane l holds the sum of
+    // key l of the tile.  The probabilities enter rounded to bf16, as they do for the outputs.
+    Frag bid[2];       // bid[hf][k][n] = 1 where column n is the key of contraction index k of pf[2 kb + hf]
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+        // element i of lane half h of pf[2 kb + hf] is key 16 hf + 8 (i / 4) + 4 h + i % 4 of the block
+        const int np = l32 - 16 * hf;
+        int i = -1;
+        if (SP && np >= 0 && np < 16 && ((np >> 2) & 1) == half) i = 4 * (np >> 3) + (np & 3);
+#pragma unroll
+        for (int x = 0; x < 4; ++x) bid[hf].u[x] = (i >= 0 && (i >> 1) == x) ? ((i & 1) ? 0x3F800000u : 0x00003F80u) : 0u;
+    }
+    // (measured: taking the weighted sums only after the fragment reads and the copies of the vector block
+    // have been issued, to give the four MFMAs time, is slower: 1.30 against 1.28 ms on a 16K cache)
     auto column_sums = [&](int step) {
         const auto lp = __builtin_amdgcn_permlane32_swap(__float_as_uint(lsum), __float_as_uint(lsum), false, false);
         const float lt = __uint_as_float(lp[0]) + __uint_as_float(lp[1]);    // both halves of the row's keys
         // gamma / (gamma + rho) = step / NT; a row always sees a key of its first tile, so lt > 0
         const float w = cw * (float)step * inv_steps * __builtin_amdgcn_rcpf(lt);
-        const auto wp = __builtin_amdgcn_permlane16_swap(__float_as_uint(w), __float_as_uint(w), false, false);
-        const float wa = __uint_as_float(wp[0]), wb = __uint_as_float(wp[1]);   // weights of the even-row and odd-row lane of a pair
-        float v[16];
+        if (half == 0) sp_w[wave][l32] = w;
+        const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        // above the priority of the other group's matrix block: these four must not queue behind its MFMAs
+        __builtin_amdgcn_s_setprio(3);
+        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[0].v, bid[0].v, zero, 0, 0, 0);
+        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[2].v, bid[0].v, zero, 0, 0, 0);
+        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[1].v, bid[1].v, s[0], 0, 0, 0);
+        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[3].v, bid[1].v, s[1], 0, 0, 0);
+        __builtin_amdgcn_s_setprio(0);
+        __builtin_amdgcn_wave_barrier();      // LDS accesses of one wave are executed in order
+        asm volatile("" ::: "memory");
+        // accumulator j of this lane is query row 8 (j / 4) + 4 half + j % 4
+        float acc[2] = {0.f, 0.f};
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            // even rows (bit 4 of the lane clear) end up with key block 0, odd rows with key block 1
-            const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(s[0][j]), __float_as_uint(s[1][j]), false, false);
-            v[j] = __builtin_fmaf(__uint_as_float(r[1]), wb, __uint_as_float(r[0]) * wa);
-        }
-        const bool b3 = l & 8, b2 = l & 4, b1 = l & 2, b0 = l & 1;
+        for (int jq = 0; jq < 4; ++jq) {
+            const float4 w4 = *reinterpret_cast<const float4*>(&sp_w[wave][8 * jq + 4 * half]);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const float t1 = v[j] + dpp(v[j], std::integral_constant<int, 0x128>());            // row_ror:8 = lane ^ 8
-            const float t2 = v[j + 8] + dpp(v[j + 8], std::integral_constant<int, 0x128>());
-            v[j] = b3 ? t2 : t1;
+            for (int kb = 0; kb < 2; ++kb) {
+                acc[kb] = __builtin_fmaf(s[kb][4 * jq + 0], w4.x, acc[kb]);
+                acc[kb] = __builtin_fmaf(s[kb][4 * jq + 1], w4.y, acc[kb]);
+                acc[kb] = __builtin_fmaf(s[kb][4 * jq + 2], w4.z, acc[kb]);
+                acc[kb] = __builtin_fmaf(s[kb][4 * jq + 3], w4.w, acc[kb]);
+            }
         }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const float t1 = v[j] + dpp(v[j], std::integral_constant<int, 0x104>());            // row_shl:4: from lane + 4
-            const float t2 = v[j + 4] + dpp(v[j + 4], std::integral_constant<int, 0x114>());    // row_shr:4: from lane - 4
-            v[j] = b2 ? t2 : t1;
-        }
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const float t1 = v[j] + dpp(v[j], std::integral_constant<int, 0x4E>());             // quad_perm [2,3,0,1]
-            const float t2 = v[j + 2] + dpp(v[j + 2], std::integral_constant<int, 0x4E>());
-            v[j] = b1 ? t2 : t1;
-        }
-        const float t1 = v[0] + dpp(v[0], std::integral_constant<int, 0xB1>());                 // quad_perm [1,0,3,2]
-        const float t2 = v[1] + dpp(v[1], std::integral_constant<int, 0xB1>());
-        sp_sum[step & 1][wave][sp_key] = b0 ? t2 : t1;
+        // lower lanes keep key block 0, upper lanes key block 1, each adding the other half's queries
+        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[0]), __float_as_uint(acc[1]), false, false);
+        sp_sum[step & 1][wave][l] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
     };
     // One wave adds the eight waves' sums of tile t and stores the 64 values (every wave wrote them
     // before the barrier the caller has passed; the slot is rewritten two tiles later).
@@ -414,7 +422,6 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
                 const float p1 = __builtin_amdgcn_exp2f(s[kb][hf * 8 + 2 * x2 + 1]);
                 pf[qt].u[x2] = cvt_pk_bf16(p0, p1);
                 lsum += p0 + p1;   // plain adds: the dot-product instructions queue behind the MFMAs of the SIMD
-                if (SP) { s[kb][hf * 8 + 2 * x2] = p0; s[kb][hf * 8 + 2 * x2 + 1] = p1; }
             }
         }
         if (SP) column_sums(step);
