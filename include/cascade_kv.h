@@ -285,10 +285,13 @@ int cascade_profile_end(cascade_ctx* ctx, cascade_profile* out);
  * Diagnostics: what the device this process runs on sustains, measured now, next to which the
  * roofline fractions of the library's kernels can be read (Section 4.1 reports latencies of one
  * GPU; the published peaks of another say little about it): number of compute units and clocks
- * from the device properties, a streaming read of dev_buffer (GB/s), a copy of its first half
- * onto its second (GB/s of bytes read plus bytes written), and a loop of nothing but
+ * from the device properties, a streaming read of dev_buffer (GB/s; all workgroups sweeping one
+ * front), the same with a contiguous region per workgroup (the pattern of the decode kernels),
+ * that again while one byte is written for every sixteen read (the logits of the decode step's
+ * first pass against the keys it reads; GB/s of the bytes READ), a copy of its first half onto
+ * its second (GB/s of bytes read plus bytes written), and a loop of nothing but
  * v_mfma_f32_32x32x16_bf16 on register operands, two waves per SIMD (TFLOP/s).  dev_buffer: at least
- * 64 MiB of device memory, 16-byte aligned; its contents are overwritten.  Blocks until done.
+ * 256 MiB of device memory, 16-byte aligned; its contents are overwritten.  Blocks until done.
  * Errors: NULL_ARG, BAD_ARG, HIP.
  */
 typedef struct cascade_ceilings {
@@ -299,6 +302,8 @@ typedef struct cascade_ceilings {
     double read_gb_s;
     double copy_gb_s;
     double mfma_bf16_tflops;
+    double read_regions_gb_s;
+    double read_with_stores_gb_s;
 } cascade_ceilings;
 int cascade_measure_ceilings(void* dev_buffer, size_t bytes, void* stream, cascade_ceilings* out);
 

@@ -30,6 +30,30 @@ __global__ __launch_bounds__(256) void ceiling_read_kernel(const cu32x4_t* __res
     if (acc == 0x9E3779B9u) *sink = acc;   // (practically never: keeps the loads alive)
 }
 
+// Every workgroup streams a contiguous region of its own, sixteen 4 KB loads in flight (the access
+// pattern of the decode kernels, one region per split).  STORES: after every 64 KB read the workgroup
+// writes 4 KB elsewhere, the ratio of logits written to keys read in the decode step's first pass.
+template <bool STORES>
+__global__ __launch_bounds__(256) void ceiling_regions_kernel(const cu32x4_t* __restrict__ src, size_t per_wg16, cu32x4_t* __restrict__ dst,
+                                                              uint32_t* __restrict__ sink)
+{
+    constexpr int U = 16;
+    uint32_t acc = 0;
+    const cu32x4_t* p = src + (size_t)blockIdx.x * per_wg16;
+    cu32x4_t* o = dst + (size_t)blockIdx.x * (per_wg16 / U);
+    for (size_t i = threadIdx.x; i + (U - 1) * 256 < per_wg16; i += U * 256) {
+        cu32x4_t v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load(p + i + u * 256);
+        cu32x4_t x = v[0];
+#pragma unroll
+        for (int u = 1; u < U; ++u) x ^= v[u];
+        if (STORES) o[(i / (U * 256)) * 256 + threadIdx.x] = x;     // 256 * iteration + thread: below per_wg16 / U
+        else acc ^= x[0] ^ x[1] ^ x[2] ^ x[3];
+    }
+    if (!STORES && acc == 0x9E3779B9u) *sink = acc;
+}
+
 __global__ __launch_bounds__(256) void ceiling_copy_kernel(const cu32x4_t* __restrict__ src, cu32x4_t* __restrict__ dst, size_t n16)
 {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -98,7 +122,7 @@ template <typename F> static int best_of(int reps, hipStream_t s, F launch, doub
 extern "C" int cascade_measure_ceilings(void* dev_buffer, size_t bytes, void* stream, cascade_ceilings* out)
 {
     if (!dev_buffer || !out) return ceil_fail(CASCADE_E_NULL_ARG, "cascade_measure_ceilings: NULL argument");
-    if (bytes < ((size_t)64 << 20) || ((uintptr_t)dev_buffer & 15)) return ceil_fail(CASCADE_E_BAD_ARG, "cascade_measure_ceilings: needs a 16-byte aligned buffer of at least 64 MiB");
+    if (bytes < ((size_t)256 << 20) || ((uintptr_t)dev_buffer & 15)) return ceil_fail(CASCADE_E_BAD_ARG, "cascade_measure_ceilings: needs a 16-byte aligned buffer of at least 256 MiB");
     memset(out, 0, sizeof(*out));
     int dev = 0;
     hipDeviceProp_t prop;
@@ -119,6 +143,23 @@ extern "C" int cascade_measure_ceilings(void* dev_buffer, size_t bytes, void* st
     }, &ms);
     if (rc) return ceil_fail(rc, "cascade_measure_ceilings: streaming read");
     out->read_gb_s = (double)n_read * 16 / (ms * 1e-3) / 1e9;
+    {
+        // regions: the first 15/16 of the buffer is read by 8 workgroups per compute unit, the rest takes the stores
+        const int wgs_r = prop.multiProcessorCount * 8;
+        const size_t per_wg16 = (((bytes / 16) * 15 / 16) / wgs_r) & ~(size_t)4095;     // whole iterations of 16 x 256 loads
+        if (per_wg16 == 0) return ceil_fail(CASCADE_E_BAD_ARG, "cascade_measure_ceilings: buffer too small for this device");
+        cu32x4_t* dst = (cu32x4_t*)dev_buffer + per_wg16 * wgs_r;                         // per_wg16 / 16 stores per workgroup fit behind
+        rc = best_of(5, s, [&] {
+            hipLaunchKernelGGL(ceiling_regions_kernel<false>, dim3(wgs_r), dim3(256), 0, s, (const cu32x4_t*)dev_buffer, per_wg16, dst, sink);
+        }, &ms);
+        if (rc) return ceil_fail(rc, "cascade_measure_ceilings: streaming read of regions");
+        out->read_regions_gb_s = (double)per_wg16 * wgs_r * 16 / (ms * 1e-3) / 1e9;
+        rc = best_of(5, s, [&] {
+            hipLaunchKernelGGL(ceiling_regions_kernel<true>, dim3(wgs_r), dim3(256), 0, s, (const cu32x4_t*)dev_buffer, per_wg16, dst, sink);
+        }, &ms);
+        if (rc) return ceil_fail(rc, "cascade_measure_ceilings: streaming read with stores");
+        out->read_with_stores_gb_s = (double)per_wg16 * wgs_r * 16 / (ms * 1e-3) / 1e9;   // bytes read only
+    }
     rc = best_of(5, s, [&] {
         hipLaunchKernelGGL(ceiling_copy_kernel, dim3(blocks), dim3(256), 0, s, (const cu32x4_t*)dev_buffer,
                            (cu32x4_t*)((char*)dev_buffer + half), n_copy);
