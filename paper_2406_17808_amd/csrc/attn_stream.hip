@@ -322,43 +322,21 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
 #pragma unroll
         for (int x = 0; x < 4; ++x) bid[hf].u[x] = (i >= 0 && (i >> 1) == x) ? ((i & 1) ? 0x3F800000u : 0x00003F80u) : 0u;
     }
-    // (measured: taking the weighted sums only after the fragment reads and the copies of the vector block
-    // have been issued, to give the four MFMAs time, is slower: 1.30 against 1.28 ms on a 16K cache)
-    auto column_sums = [&](int step) {
+    // The weights are set in the vector block that makes the probabilities of a tile (column_weights);
+    // the four MFMAs and the weighted sums are part of the matrix block that multiplies those
+    // probabilities with V (there the wave owns the matrix pipe, and the vector instructions fall into the
+    // shadow of its MFMAs; in the vector block, which is as long as the matrix block without them, they cost
+    // 1.28 against 1.04 ms on a 16K cache, with the four MFMAs queuing behind the other group's).
+    auto column_weights = [&](int step) {
         const auto lp = __builtin_amdgcn_permlane32_swap(__float_as_uint(lsum), __float_as_uint(lsum), false, false);
         const float lt = __uint_as_float(lp[0]) + __uint_as_float(lp[1]);    // both halves of the row's keys
         // gamma / (gamma + rho) = step / NT; a row always sees a key of its first tile, so lt > 0
         const float w = cw * (float)step * inv_steps * __builtin_amdgcn_rcpf(lt);
         if (half == 0) sp_w[wave][l32] = w;
-        const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        // above the priority of the other group's matrix block: these four must not queue behind its MFMAs
-        __builtin_amdgcn_s_setprio(3);
-        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[0].v, bid[0].v, zero, 0, 0, 0);
-        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[2].v, bid[0].v, zero, 0, 0, 0);
-        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[1].v, bid[1].v, s[0], 0, 0, 0);
-        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[3].v, bid[1].v, s[1], 0, 0, 0);
-        __builtin_amdgcn_s_setprio(0);
-        __builtin_amdgcn_wave_barrier();      // LDS accesses of one wave are executed in order
-        asm volatile("" ::: "memory");
-        // accumulator j of this lane is query row 8 (j / 4) + 4 half + j % 4
-        float acc[2] = {0.f, 0.f};
-#pragma unroll
-        for (int jq = 0; jq < 4; ++jq) {
-            const float4 w4 = *reinterpret_cast<const float4*>(&sp_w[wave][8 * jq + 4 * half]);
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                acc[kb] = __builtin_fmaf(s[kb][4 * jq + 0], w4.x, acc[kb]);
-                acc[kb] = __builtin_fmaf(s[kb][4 * jq + 1], w4.y, acc[kb]);
-                acc[kb] = __builtin_fmaf(s[kb][4 * jq + 2], w4.z, acc[kb]);
-                acc[kb] = __builtin_fmaf(s[kb][4 * jq + 3], w4.w, acc[kb]);
-            }
-        }
-        // lower lanes keep key block 0, upper lanes key block 1, each adding the other half's queries
-        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[0]), __float_as_uint(acc[1]), false, false);
-        sp_sum[step & 1][wave][l] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
     };
-    // One wave adds the eight waves' sums of tile t and stores the 64 values (every wave wrote them
-    // before the barrier the caller has passed; the slot is rewritten two tiles later).
+    // One wave adds the eight waves' sums of tile t and stores the 64 values.  Called by a wave of the
+    // late group in its vector block t: both groups have left their matrix block t (the barrier the caller
+    // has passed), and the slot is written again in matrix block t + 2, two barriers later.
     auto flush_column_sums = [&](int t) {
         float acc = 0.f;
 #pragma unroll
@@ -424,7 +402,7 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
                 lsum += p0 + p1;   // plain adds: the dot-product instructions queue behind the MFMAs of the SIMD
             }
         }
-        if (SP) column_sums(step);
+        if (SP) column_weights(step);
     };
     auto wave_active = [&](const TileIter& it) { return !(it.sg.chunk && it.t0 > wave_imax); };
 
@@ -542,11 +520,44 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
         {
             const bf16_t* Vtile = Vs + (t & 3) * TILE;
             const bf16_t* Ktile = Ks + ((t + 1) & 3) * TILE;
+            float4 w4[SP ? 4 : 1];
+            float csum[2] = {0.f, 0.f};
+            if (SP) {
+                // S^T of tile t has become probabilities: its registers take P with the keys across the lanes
+                // (accumulator j of this lane: query row 8 (j / 4) + 4 half + j % 4 of the wave)
+                w4[0] = *reinterpret_cast<const float4*>(&sp_w[wave][4 * half]);    // the others follow two MFMAs ahead of their use
+                const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[0].v, bid[0].v, zero, 0, 0, 0);
+                s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[2].v, bid[0].v, zero, 0, 0, 0);
+                s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[1].v, bid[1].v, s[0], 0, 0, 0);
+                s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[3].v, bid[1].v, s[1], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
 #pragma unroll
             for (int i = 0; i < NF; ++i) {
                 if (i < NV) o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kAhead].v, pf[i / DB].v, o[i % DB], 0, 0, 0);
                 else s[(i - NV) % 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kAhead].v, qf[(i - NV) / 2].v, i - NV < 2 ? negm : s[(i - NV) % 2], 0, 0, 0);
                 if (i + kAhead < NF) fr[i % kAhead] = read_frag(Vtile, Ktile, i + kAhead);
+                // the weighted sums, in eight groups of four terms behind the first MFMAs (S^T is rewritten from MFMA NV on)
+                constexpr int GPS = NV >= 16 ? 1 : 2, FIRST = NV >= 16 ? 4 : 3, LAST = FIRST + 8 / GPS;
+                static_assert(LAST < NV, "the sums read S^T's registers before the next QK^T writes them");
+                if (SP && i >= FIRST - 2 && i < LAST - 2 && (i - FIRST + 2) * GPS % 2 == 0 && ((i - FIRST + 2) * GPS) / 2 + 1 < 4)
+                    w4[((i - FIRST + 2) * GPS) / 2 + 1] = *reinterpret_cast<const float4*>(&sp_w[wave][8 * (((i - FIRST + 2) * GPS) / 2 + 1) + 4 * half]);
+                if (SP && i >= FIRST && i < LAST) {
+#pragma unroll
+                    for (int gq = (i - FIRST) * GPS; gq < (i - FIRST + 1) * GPS; ++gq) {
+                        const int jq = gq >> 1, kb = gq & 1;
+                        csum[kb] = __builtin_fmaf(s[kb][4 * jq + 0], w4[jq].x, csum[kb]);
+                        csum[kb] = __builtin_fmaf(s[kb][4 * jq + 1], w4[jq].y, csum[kb]);
+                        csum[kb] = __builtin_fmaf(s[kb][4 * jq + 2], w4[jq].z, csum[kb]);
+                        csum[kb] = __builtin_fmaf(s[kb][4 * jq + 3], w4[jq].w, csum[kb]);
+                    }
+                }
+                if (SP && i == LAST) {
+                    // lower lanes keep key block 0, upper lanes key block 1, each adding the other half's queries
+                    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(csum[0]), __float_as_uint(csum[1]), false, false);
+                    sp_sum[(t + 1) & 1][wave][l] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -574,7 +585,7 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
                 // measured orders of the three parts: exponentials, fragments, copies (this one) 3.329 ms;
                 // fragments first 3.35; copies before the fragments 3.41
                 softmax_tile(it1, false, std::true_type(), n0 + 2);
-                if (SP && wave == (n0 & 3)) flush_column_sums(n0);
+                if (SP && wave == 4 + (n0 & 3)) flush_column_sums(n0);
 #pragma unroll
                 for (int i = 0; i < kAhead; ++i) fr[i] = read_frag(Vs + ((n0 + 1) & 3) * TILE, Ks, i);
                 copy_tile(kt_bh, lds_k, n0 + 4, n0 & 3);
@@ -612,9 +623,8 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
             for (int qt = 0; qt < 4; ++qt)
 #pragma unroll
                 for (int x = 0; x < 4; ++x) pf[qt].u[x] = 0u;
-            if (SP) sp_sum[n0 & 1][wave][l] = 0.f;      // this wave sees nothing of tile n0 + 1 (step n0 + 2)
         }
-        if (SP && wave == (n0 & 3)) flush_column_sums(n0);
+        if (SP && wave == 4 + (n0 & 3)) flush_column_sums(n0);
         lap(3);
         publish(in_flight);
         wg_barrier();     // barrier 2t+2 (early group), 2t+3 (late group)
@@ -623,7 +633,10 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
         ++n0;
     }
     if (!late) wg_barrier();   // the late group passed one barrier more
-    if (SP && wave == 0) flush_column_sums(n0);   // the last tile: every wave has left its vector block
+    if (SP) {
+        wg_barrier();                            // every wave has left its last matrix block
+        if (wave == 0) flush_column_sums(n0);    // the last tile
+    }
     if (DBG && blockIdx.x == 100 && l == 0 && (wave == 0 || wave == 4)) {
 #pragma unroll
         for (int i = 0; i < 5; ++i) dbg[(wave / 4) * 8 + i] = tc[i];
