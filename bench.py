@@ -117,7 +117,9 @@ def prefill_bench(args, torch, B, wl):
         acc0 = cache.read_state().accepted.copy()
         B.cascade_profile_begin(cache.ctx)
         for c in range(W + K, W + K + K2):
-            cache.prefill_chunk(*chunk_inputs_torch(wl, args.seed, c, dev), out=out)
+            qkv = chunk_inputs_torch(wl, args.seed, c, dev)
+            # (the last chunk of a stream may be ragged)
+            cache.prefill_chunk(*qkv, out=out if qkv[0].shape == out.shape else torch.empty_like(qkv[0]))
         torch.cuda.synchronize()
         prof2 = B.cascade_profile_end(cache.ctx)
         breakdown = {k: v[0] / max(v[1], 1) for k, v in prof2.items() if v[1]}

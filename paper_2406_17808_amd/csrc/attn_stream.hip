@@ -826,8 +826,12 @@ void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, i
 #ifdef CASCADE_KV_ATTN_PHASE_TIMING   // development builds only: per-phase cycle counts of one workgroup
     if (g.d == 128) {
         long long* dbg = (long long*)b.logits;
-        hipLaunchKernelGGL((attn_stream_kernel<128, true, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
-                           (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, dbg, 1, (float*)nullptr, (float*)nullptr, b.knorm2, so, sp);
+        if (single_pass)
+            hipLaunchKernelGGL((attn_stream_kernel<128, true, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
+                               (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, dbg, 1, (float*)nullptr, (float*)nullptr, b.knorm2, so, sp);
+        else
+            hipLaunchKernelGGL((attn_stream_kernel<128, true, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
+                               (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, dbg, 1, (float*)nullptr, (float*)nullptr, b.knorm2, so, sp);
         long long h[16];
         (void)hipStreamSynchronize(s);
         (void)hipMemcpy(h, dbg, sizeof(h), hipMemcpyDeviceToHost);
