@@ -124,6 +124,8 @@ static WorkspaceBytes carve(const cascade_config* c, const Geom& g, char* state_
     b.lse = (float*)take(BHq * mc * 4);
     b.mu_chunk = (float*)take(BH * mc * 4);
     b.negt = (float*)take(mfma ? BHq * (mc + 64) * 4 : 0);
+    b.rope_t = (float2*)take(mfma ? (size_t)rope_rows * (g.d / 2) * 8 : 0);
+    if (!mfma) b.rope_t = nullptr;
     b.attn_part = (float*)take(mfma ? (size_t)kAttnPartRows * (g.d + 2) * 4 : 0);
     const bool single_pass = mfma && c->score_mode == CASCADE_SCORES_SINGLE_PASS;
     b.sp_part = (float*)take(single_pass ? BH * (size_t)g.G * ((mc + 255) / 256) * (size_t)vt_tiles * 64 * 4 : 0);
@@ -246,7 +248,7 @@ static int init_context(const char* who, const cascade_config* cfg, const Geom& 
     const size_t BH = (size_t)g.B * g.Hkv;
     launch_fill_i32(b.ids, BH * g.slots, -1, s);
     if (tables) {
-        launch_rope_table(g, cfg->rope_base, b.rope, b.rope_rows, s);
+        launch_rope_table(g, cfg->rope_base, b.rope, b.rope_t, b.rope_rows, s);
         launch_wrow_table(cfg->ema_beta, b.wrow, cfg->max_chunk, s);
     }
     if (init_state && total > 0)

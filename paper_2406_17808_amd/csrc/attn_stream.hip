@@ -162,7 +162,7 @@ __device__ inline void write_score_offset(const ScoreOffsets& so, size_t head, i
 // every row of the chunk carrying EMA weight, so that every row block takes part).
 template <int D, bool DBG, bool SPLIT, bool SP = false>
 __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
-    Geom g, SegList sl, int Q, int tiles_per_bh, const bf16_t* __restrict__ q, const float2* __restrict__ rope, float qscale,
+    Geom g, SegList sl, int Q, int tiles_per_bh, const bf16_t* __restrict__ q, const float4* __restrict__ rope_t, int rope_rows, float qscale,
     const bf16_t* __restrict__ Kt, const bf16_t* __restrict__ Vt, bf16_t* __restrict__ out, float* __restrict__ lse,
     long long* dbg, int n_split, float* __restrict__ part_o, float* __restrict__ part_ml, const float* __restrict__ Knorm2,
     ScoreOffsets so, SinglePass sp)
@@ -257,20 +257,33 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     auto load_q = [&](const Seg& sg) {
         qn2 = 0.f;
         const bf16_t* qsrc = q + (((size_t)b * Q + qi) * g.Hq + qh) * D + half * 8;
-        const float2* cs = rope + (size_t)(sl.qrot0[sg.qvar] + qi) * (D / 2) + half * 8;
+        // (cos, sin) of this lane's 8 rotary pairs per step from the index-minor table: group ks * 8 + half * 4 + x
+        const float4* cs = rope_t + ((size_t)half * 4 * rope_rows + (size_t)(sl.qrot0[sg.qvar] + qi));
+        // All loads first (24 at D = 128), then the arithmetic: scheduled freely, the loads come in four or
+        // five groups, each waiting for the one before.  (Measured: no difference; what a reload costs is
+        // neither those round trips nor, much, the cache lines its loads touch: the index-minor table
+        // below, 8 lines per load instead of 32, gains 2 % on a 16K cache and 0.7 % on a 64K cache.)
+        u32x4_t lo[KS / 2], hi[KS / 2];
+        float4 c4[KS / 2][4];      // (cos, sin) of 8 rotary pairs
 #pragma unroll
         for (int ks = 0; ks < KS / 2; ++ks) {
-            const u32x4_t lo = *reinterpret_cast<const u32x4_t*>(qsrc + ks * 16);
-            const u32x4_t hi = *reinterpret_cast<const u32x4_t*>(qsrc + ks * 16 + D / 2);
+            lo[ks] = *reinterpret_cast<const u32x4_t*>(qsrc + ks * 16);
+            hi[ks] = *reinterpret_cast<const u32x4_t*>(qsrc + ks * 16 + D / 2);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) c4[ks][x] = cs[(size_t)(ks * 8 + x) * rope_rows];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ks = 0; ks < KS / 2; ++ks) {
             float y0[8], y1[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const uint32_t wl = lo[j >> 1], wh = hi[j >> 1];
+                const uint32_t wl = lo[ks][j >> 1], wh = hi[ks][j >> 1];
                 const float x0 = __uint_as_float((j & 1) ? (wl & 0xFFFF0000u) : (wl << 16)) * qscale;
                 const float x1 = __uint_as_float((j & 1) ? (wh & 0xFFFF0000u) : (wh << 16)) * qscale;
-                const float2 c = cs[ks * 16 + j];
-                y0[j] = rot_lo(x0, x1, c.x, c.y);
-                y1[j] = rot_hi(x0, x1, c.x, c.y);
+                const float cx = (j & 1) ? c4[ks][j >> 1].z : c4[ks][j >> 1].x, cy = (j & 1) ? c4[ks][j >> 1].w : c4[ks][j >> 1].y;
+                y0[j] = rot_lo(x0, x1, cx, cy);
+                y1[j] = rot_hi(x0, x1, cx, cy);
                 qn2 += x0 * x0 + x1 * x1;
             }
 #pragma unroll
@@ -604,6 +617,13 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
             load_q(it1.sg);
             q_var = it1.sg.qvar;
             wait_vm<0>();   // here, so that no wait for these loads is placed among the MFMAs (it would also wait for the copies)
+            // load_q holds all its loads in registers at once.  What can be had again for nothing is written after
+            // it, and so is dead while it runs: the copies of -m_run (16 registers) and the fragments read ahead for
+            // the coming matrix block (32; still in LDS).  Without this the reload spills.
+#pragma unroll
+            for (int j = 0; j < 16; ++j) negm[j] = -m_run;
+#pragma unroll
+            for (int i = 0; i < kAhead; ++i) fr[i] = read_frag(Vs + (n0 & 3) * TILE, Ks, i);
         }
         lap(0);
         matrix_block(n0);
@@ -811,12 +831,12 @@ void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, i
         float* part_o = b.attn_part;
         float* part_ml = b.attn_part + (size_t)kAttnPartRows * g.d;
         if (g.d == 128) {
-            hipLaunchKernelGGL((attn_stream_kernel<128, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
+            hipLaunchKernelGGL((attn_stream_kernel<128, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, (const float4*)b.rope_t, b.rope_rows, qscale,
                                (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, n_split, part_o, part_ml, b.knorm2, so, sp);
             hipLaunchKernelGGL(attn_merge_kernel<128>, dim3(g.G * Q, g.B * g.Hkv), dim3(128), 0, s, g, Q, tiles, n_split, BM,
                                part_o, part_ml, (bf16_t*)out, b.lse, so);
         } else {
-            hipLaunchKernelGGL((attn_stream_kernel<64, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
+            hipLaunchKernelGGL((attn_stream_kernel<64, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, (const float4*)b.rope_t, b.rope_rows, qscale,
                                (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, n_split, part_o, part_ml, b.knorm2, so, sp);
             hipLaunchKernelGGL(attn_merge_kernel<64>, dim3(g.G * Q, g.B * g.Hkv), dim3(64), 0, s, g, Q, tiles, n_split, BM,
                                part_o, part_ml, (bf16_t*)out, b.lse, so);
@@ -827,10 +847,10 @@ void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, i
     if (g.d == 128) {
         long long* dbg = (long long*)b.logits;
         if (single_pass)
-            hipLaunchKernelGGL((attn_stream_kernel<128, true, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
+            hipLaunchKernelGGL((attn_stream_kernel<128, true, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, (const float4*)b.rope_t, b.rope_rows, qscale,
                                (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, dbg, 1, (float*)nullptr, (float*)nullptr, b.knorm2, so, sp);
         else
-            hipLaunchKernelGGL((attn_stream_kernel<128, true, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
+            hipLaunchKernelGGL((attn_stream_kernel<128, true, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, (const float4*)b.rope_t, b.rope_rows, qscale,
                                (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, dbg, 1, (float*)nullptr, (float*)nullptr, b.knorm2, so, sp);
         long long h[16];
         (void)hipStreamSynchronize(s);
@@ -844,18 +864,18 @@ void launch_attn_stream(const Geom& g, const DevBuffers& b, const SegList& sl, i
 #endif
     if (single_pass) {      // (the caller has checked attn_single_pass_ok)
         if (g.d == 128)
-            hipLaunchKernelGGL((attn_stream_kernel<128, false, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
+            hipLaunchKernelGGL((attn_stream_kernel<128, false, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, (const float4*)b.rope_t, b.rope_rows, qscale,
                                (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, 1, (float*)nullptr, (float*)nullptr, b.knorm2, so, sp);
         else
-            hipLaunchKernelGGL((attn_stream_kernel<64, false, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
+            hipLaunchKernelGGL((attn_stream_kernel<64, false, false, true>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, (const float4*)b.rope_t, b.rope_rows, qscale,
                                (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, 1, (float*)nullptr, (float*)nullptr, b.knorm2, so, sp);
         return;
     }
     if (g.d == 128)
-        hipLaunchKernelGGL((attn_stream_kernel<128, false, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
+        hipLaunchKernelGGL((attn_stream_kernel<128, false, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, (const float4*)b.rope_t, b.rope_rows, qscale,
                            (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, 1, (float*)nullptr, (float*)nullptr, b.knorm2, so, sp);
     else
-        hipLaunchKernelGGL((attn_stream_kernel<64, false, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, b.rope, qscale,
+        hipLaunchKernelGGL((attn_stream_kernel<64, false, false>), grid, block, 0, s, g, sl, Q, tiles_per_bh, (const bf16_t*)q, (const float4*)b.rope_t, b.rope_rows, qscale,
                            (const bf16_t*)b.Kt, (const bf16_t*)b.Vt, (bf16_t*)out, b.lse, (long long*)nullptr, 1, (float*)nullptr, (float*)nullptr, b.knorm2, so, sp);
 }
 

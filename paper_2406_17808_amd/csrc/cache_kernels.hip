@@ -10,7 +10,10 @@ namespace ckv {
 
 // (cos, sin)(p * theta_i), theta_i = base^(-2i/d), evaluated in double so that large
 // indices keep full float accuracy.
-__global__ void rope_table_kernel(float2* __restrict__ rope, int rows, int half, int d, double base)
+// rope_t (optional): the same values index-minor, [d/4 groups of two rotary pairs][rows], for readers whose
+// lanes hold consecutive indices (the attention kernel's queries): their 16-byte loads then fall into
+// a few cache lines per instruction instead of one line per lane.
+__global__ void rope_table_kernel(float2* __restrict__ rope, float2* __restrict__ rope_t, int rows, int half, int d, double base)
 {
     const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (long)rows * half) return;
@@ -19,14 +22,15 @@ __global__ void rope_table_kernel(float2* __restrict__ rope, int rows, int half,
     double s, c;
     sincos((double)p * theta, &s, &c);
     rope[idx] = make_float2((float)c, (float)s);
+    if (rope_t) rope_t[((size_t)(i >> 1) * rows + p) * 2 + (i & 1)] = make_float2((float)c, (float)s);
 }
 
-void launch_rope_table(const Geom& g, float base, float2* rope, int rows, hipStream_t s)
+void launch_rope_table(const Geom& g, float base, float2* rope, float2* rope_t, int rows, hipStream_t s)
 {
     const int half = g.d / 2;
     const long n = (long)rows * half;
     hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
-                       rope, rows, half, g.d, (double)base);
+                       rope, rope_t, rows, half, g.d, (double)base);
 }
 
 // wrow[k] = beta^k (1 - beta): weight of the query row that has k rows after it in its chunk

@@ -21,6 +21,7 @@ struct DevBuffers {
     float* mu_snap;  // [B,Hkv,slots] diagnostics: scores when the last insertion decisions were taken
     // tables
     float2* rope;    // [rope_rows, d/2] (cos, sin) of index * theta_i
+    float2* rope_t;  // bf16 MFMA path: the same, [d/4, rope_rows, 2] (index-minor: see rope_table_kernel)
     float* wrow;     // [max_chunk] beta^k (1 - beta): EMA weight of the row that has k rows after it
     // per-call scratch
     void* Qr;        // [n_qvar_max, B, Hq, max_chunk, d] rotated query copies (bf16 MFMA path: times scale * log2 e)
@@ -55,7 +56,7 @@ struct DevBuffers {
 };
 
 // tables
-void launch_rope_table(const Geom& g, float base, float2* rope, int rows, hipStream_t s);
+void launch_rope_table(const Geom& g, float base, float2* rope, float2* rope_t, int rows, hipStream_t s);
 void launch_wrow_table(float beta, float* wrow, int n, hipStream_t s);
 
 // cache maintenance

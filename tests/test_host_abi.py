@@ -126,11 +126,12 @@ def test_workspace_grows_with_the_cache(lib):
     big = B.cascade_workspace_bytes(_cfg(cascade_sizes=[64, 64, 64]))
     assert big > small
     # five row arrays (K, rotated K, V, and the per-chunk packed copies of rotated K and V of the
-    # bf16 MFMA path) dominate a large cache
+    # bf16 MFMA path) dominate a large cache; the two layouts of the rotation table (2 x slots rows of
+    # d/2 (cos, sin) pairs each) come to one more
     huge = _cfg(dtype=B.CASCADE_BF16, head_dim=128, n_q_heads=32, n_kv_heads=8, n_sink=64,
                 cascade_sizes=[16384] * 4, max_chunk=1)
     rows = 8 * 65600 * 128 * 2
-    assert 5 * rows < B.cascade_workspace_bytes(huge) < 6 * rows
+    assert 5 * rows < B.cascade_workspace_bytes(huge) < 7 * rows
 
 
 @pytest.mark.parametrize("seed", range(6))
