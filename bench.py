@@ -127,8 +127,8 @@ def prefill_bench(args, torch, B, wl):
         moved = int((cache.read_state().accepted - acc0).sum()) * wl.n_kv_heads * wl.batch
     # cache update (Alg. 2 as row moves): rows that arrived at an accepting step of a cascade (the
     # host-visible count; a token that wins a selection moves one more row, so this is a lower
-    # bound).  Two bases: `roofline_update` counts what SURVEY-style accounting calls the algorithmic
-    # bytes, 520 B per row (K, V, score, id) read once and written once; `bytes_incl_rotated_copy`
+    # bound).  Two bases: `roofline_update` counts the algorithmic bytes of a move,
+    # 520 B per row (K, V, score, id) read once and written once; `bytes_incl_rotated_copy`
     # also counts the rotated key copy the library writes for its own use.
     esz = 2 if wl.dtype == "bf16" else 4
     row_bytes = 2 * d * esz + 8
