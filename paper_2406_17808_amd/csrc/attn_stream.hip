@@ -347,14 +347,19 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
         const float w = cw * (float)step * inv_steps * __builtin_amdgcn_rcpf(lt);
         if (half == 0) sp_w[wave][l32] = w;
     };
-    // One wave adds the eight waves' sums of tile t and stores the 64 values.  Called by a wave of the
-    // late group in its vector block t: both groups have left their matrix block t (the barrier the caller
-    // has passed), and the slot is written again in matrix block t + 2, two barriers later.
-    auto flush_column_sums = [&](int t) {
-        float acc = 0.f;
-#pragma unroll
-        for (int w = 0; w < kSWaves; ++w) acc += sp_sum[(t + 1) & 1][w][l];
-        counted_store_f32(sp_part, (uint32_t)((t * kBN + l) * 4), acc);
+    // The four waves of the late group add the eight waves' sums of tile t, 16 keys each, and store them.
+    // Called in their vector block t: both groups have left their matrix block t (the barrier the caller
+    // has passed), and the slot is written again in matrix block t + 2, two barriers later.  Lane l of wave
+    // 4 + kq takes key 16 kq + l % 16 and the sums of waves 2 (l / 16) and 2 (l / 16) + 1; two lane exchanges
+    // add the four pairs (in a fixed order: the result does not depend on timing).
+    auto flush_column_sums = [&](int t, int kq) {
+        const int key = 16 * kq + (l & 15), pair = l >> 4;
+        float a = sp_sum[(t + 1) & 1][2 * pair][key] + sp_sum[(t + 1) & 1][2 * pair + 1][key];
+        const auto r16 = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(a), false, false);
+        a = __uint_as_float(r16[0]) + __uint_as_float(r16[1]);       // rows 0+1 | 0+1 | 2+3 | 2+3
+        const auto r32 = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(a), false, false);
+        a = __uint_as_float(r32[0]) + __uint_as_float(r32[1]);
+        if (l < 16) counted_store_f32(sp_part, (uint32_t)((t * kBN + key) * 4), a);
     };
     // The vector block of one tile: mask the keys a query may not see (past the end of the
     // segment; later chunk tokens), take the row maximum of S^T (relative to m_run), raise m_run only
@@ -598,7 +603,7 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
                 // measured orders of the three parts: exponentials, fragments, copies (this one) 3.329 ms;
                 // fragments first 3.35; copies before the fragments 3.41
                 softmax_tile(it1, false, std::true_type(), n0 + 2);
-                if (SP && wave == 4 + (n0 & 3)) flush_column_sums(n0);
+                if (SP && late) flush_column_sums(n0, wave - 4);
 #pragma unroll
                 for (int i = 0; i < kAhead; ++i) fr[i] = read_frag(Vs + ((n0 + 1) & 3) * TILE, Ks, i);
                 copy_tile(kt_bh, lds_k, n0 + 4, n0 & 3);
@@ -644,7 +649,7 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
 #pragma unroll
                 for (int x = 0; x < 4; ++x) pf[qt].u[x] = 0u;
         }
-        if (SP && wave == 4 + (n0 & 3)) flush_column_sums(n0);
+        if (SP && late) flush_column_sums(n0, wave - 4);
         lap(3);
         publish(in_flight);
         wg_barrier();     // barrier 2t+2 (early group), 2t+3 (late group)
@@ -655,7 +660,7 @@ __global__ __launch_bounds__(kSWaves * 64, 1) void attn_stream_kernel(
     if (!late) wg_barrier();   // the late group passed one barrier more
     if (SP) {
         wg_barrier();                            // every wave has left its last matrix block
-        if (wave == 0) flush_column_sums(n0);    // the last tile
+        if (late) flush_column_sums(n0, wave - 4);    // the last tile
     }
     if (DBG && blockIdx.x == 100 && l == 0 && (wave == 0 || wave == 4)) {
 #pragma unroll
