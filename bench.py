@@ -48,7 +48,7 @@ def calibration_copy(torch, mib):
 
 def measured_ceilings(torch, B):
     """What this very device sustains, measured in this run (untimed leg): streaming read, copy, pure MFMA loop."""
-    nbytes = 4 << 30
+    nbytes = 9 << 30      # a half is the size of the decode workload's K (or V) cache; single-launch figures use the first half
     buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
     buf.fill_(1)
     torch.cuda.synchronize()
@@ -58,6 +58,7 @@ def measured_ceilings(torch, B):
     return {"compute_units": c["compute_units"], "core_clock_mhz": c["core_clock_mhz"], "memory_clock_mhz": c["memory_clock_mhz"],
             "memory_bus_bits": c["memory_bus_bits"], "hbm_read_gb_s": c["read_gb_s"], "hbm_copy_gb_s_read_plus_write": c["copy_gb_s"],
             "hbm_read_regions_gb_s": c["read_regions_gb_s"], "hbm_read_with_1_16_stores_gb_s": c["read_with_stores_gb_s"],
+            "hbm_two_pass_read_gb_s": c["two_pass_read_gb_s"],
             "mfma_bf16_tflops": c["mfma_bf16_tflops"], "buffer_bytes": nbytes}
 
 
@@ -318,6 +319,10 @@ def main():
             line["roofline_decode"]["frac_of_measured_read_with_stores"] = (line["roofline_decode"]["achieved"]
                                                                             / ceilings["hbm_read_with_1_16_stores_gb_s"])
             line["decode_frac_of_measured_read"] = line["decode_hbm_frac"] * HBM_PEAK / 1e9 / rd
+            # the whole step against its two passes as traffic alone (a read with stores, then a plain read,
+            # alternating): bytes of K and V read per second over the measured rate of that pair
+            kv_rate = 2 * line["roofline_decode"]["achieved"] * (line["decode_kernel_us"]["decode_qk"] / line["decode_step_us"])
+            line["decode_frac_of_measured_two_pass_read"] = kv_rate / ceilings["hbm_two_pass_read_gb_s"]
     print(json.dumps(line))
 
 

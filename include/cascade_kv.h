@@ -288,10 +288,12 @@ int cascade_profile_end(cascade_ctx* ctx, cascade_profile* out);
  * from the device properties, a streaming read of dev_buffer (GB/s; all workgroups sweeping one
  * front), the same with a contiguous region per workgroup (the pattern of the decode kernels),
  * that again while one byte is written for every sixteen read (the logits of the decode step's
- * first pass against the keys it reads; GB/s of the bytes READ), a copy of its first half onto
+ * first pass against the keys it reads; GB/s of the bytes READ), that launch and a plain read
+ * alternating (two_pass_read_gb_s), a copy of its first half onto
  * its second (GB/s of bytes read plus bytes written), and a loop of nothing but
  * v_mfma_f32_32x32x16_bf16 on register operands, two waves per SIMD (TFLOP/s).  dev_buffer: at least
- * 256 MiB of device memory, 16-byte aligned; its contents are overwritten.  Blocks until done.
+ * 1 GiB of device memory (every single-launch figure uses its first half, the alternating launches both halves:
+ * size a half like the array one pass of the workload streams), 16-byte aligned; its contents are overwritten.  Blocks until done.
  * Errors: NULL_ARG, BAD_ARG, HIP.
  */
 typedef struct cascade_ceilings {
@@ -304,6 +306,10 @@ typedef struct cascade_ceilings {
     double mfma_bf16_tflops;
     double read_regions_gb_s;
     double read_with_stores_gb_s;
+    double two_pass_read_gb_s;  /* a read with stores on one half of the buffer followed by a plain read of the other half
+                                   (the two passes of a decode step as traffic alone), pairs back to back: bytes read by both
+                                   per second.  Below the mean of the two rates measured alone: what the first launch wrote
+                                   is still on its way to memory while the second reads. */
 } cascade_ceilings;
 int cascade_measure_ceilings(void* dev_buffer, size_t bytes, void* stream, cascade_ceilings* out);
 

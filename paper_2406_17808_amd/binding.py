@@ -94,7 +94,8 @@ class cascade_ceilings(ctypes.Structure):
     _fields_ = [("compute_units", ctypes.c_int32), ("memory_bus_bits", ctypes.c_int32),
                 ("core_clock_mhz", ctypes.c_double), ("memory_clock_mhz", ctypes.c_double),
                 ("read_gb_s", ctypes.c_double), ("copy_gb_s", ctypes.c_double), ("mfma_bf16_tflops", ctypes.c_double),
-                ("read_regions_gb_s", ctypes.c_double), ("read_with_stores_gb_s", ctypes.c_double)]
+                ("read_regions_gb_s", ctypes.c_double), ("read_with_stores_gb_s", ctypes.c_double),
+                ("two_pass_read_gb_s", ctypes.c_double)]
 
 
 class cascade_profile(ctypes.Structure):

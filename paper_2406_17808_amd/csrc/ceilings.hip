@@ -122,7 +122,7 @@ template <typename F> static int best_of(int reps, hipStream_t s, F launch, doub
 extern "C" int cascade_measure_ceilings(void* dev_buffer, size_t bytes, void* stream, cascade_ceilings* out)
 {
     if (!dev_buffer || !out) return ceil_fail(CASCADE_E_NULL_ARG, "cascade_measure_ceilings: NULL argument");
-    if (bytes < ((size_t)256 << 20) || ((uintptr_t)dev_buffer & 15)) return ceil_fail(CASCADE_E_BAD_ARG, "cascade_measure_ceilings: needs a 16-byte aligned buffer of at least 256 MiB");
+    if (bytes < ((size_t)1 << 30) || ((uintptr_t)dev_buffer & 15)) return ceil_fail(CASCADE_E_BAD_ARG, "cascade_measure_ceilings: needs a 16-byte aligned buffer of at least 1 GiB");
     memset(out, 0, sizeof(*out));
     int dev = 0;
     hipDeviceProp_t prop;
@@ -133,6 +133,11 @@ extern "C" int cascade_measure_ceilings(void* dev_buffer, size_t bytes, void* st
     out->memory_clock_mhz = prop.memoryClockRate / 1000.0;
     out->memory_bus_bits = prop.memoryBusWidth;
     hipStream_t s = (hipStream_t)stream;
+    // Every single-launch figure is taken on the FIRST HALF of the buffer (the copy: its first quarter onto its
+    // second), the pairs of launches on both halves: sized for the workload at hand, half the buffer is the
+    // array one pass streams.
+    const size_t full = bytes;
+    bytes = (full / 2) & ~(size_t)4095;
     const size_t half = (bytes / 2) & ~(size_t)4095;
     const size_t n_read = (bytes & ~(size_t)4095) / 16, n_copy = half / 16;
     uint32_t* sink = (uint32_t*)dev_buffer;    // written only if a checksum takes one particular value
@@ -159,6 +164,25 @@ extern "C" int cascade_measure_ceilings(void* dev_buffer, size_t bytes, void* st
         }, &ms);
         if (rc) return ceil_fail(rc, "cascade_measure_ceilings: streaming read with stores");
         out->read_with_stores_gb_s = (double)per_wg16 * wgs_r * 16 / (ms * 1e-3) / 1e9;   // bytes read only
+        // The two passes of a decode step one after the other, as traffic alone: a read with stores (the keys,
+        // the logits written) on one half of the buffer, then a plain read (the values) on the other half,
+        // eight such pairs back to back.  What the first launch wrote is still on its way to memory while the
+        // second reads, so a pair takes longer than its two launches measured alone.
+        const size_t half16 = ((full / 2) / 16) & ~(size_t)255;
+        const size_t per_a16 = ((half16 * 15 / 16) / wgs_r) & ~(size_t)4095;
+        const size_t per_b16 = (half16 / wgs_r) & ~(size_t)4095;
+        if (per_a16 == 0 || per_b16 == 0) return ceil_fail(CASCADE_E_BAD_ARG, "cascade_measure_ceilings: buffer too small for this device");
+        const cu32x4_t* src_b = (const cu32x4_t*)dev_buffer + half16;
+        cu32x4_t* dst_a = (cu32x4_t*)dev_buffer + per_a16 * wgs_r;          // behind the part of the first half that is read
+        const int pairs = 8;
+        rc = best_of(2, s, [&] {
+            for (int i = 0; i < pairs; ++i) {
+                hipLaunchKernelGGL(ceiling_regions_kernel<true>, dim3(wgs_r), dim3(256), 0, s, (const cu32x4_t*)dev_buffer, per_a16, dst_a, sink);
+                hipLaunchKernelGGL(ceiling_regions_kernel<false>, dim3(wgs_r), dim3(256), 0, s, src_b, per_b16, dst_a, sink);
+            }
+        }, &ms);
+        if (rc) return ceil_fail(rc, "cascade_measure_ceilings: pairs of launches");
+        out->two_pass_read_gb_s = (double)(per_a16 + per_b16) * wgs_r * 16 * pairs / (ms * 1e-3) / 1e9;   // bytes read by both
     }
     rc = best_of(5, s, [&] {
         hipLaunchKernelGGL(ceiling_copy_kernel, dim3(blocks), dim3(256), 0, s, (const cu32x4_t*)dev_buffer,

@@ -41,7 +41,7 @@ def test_struct_layouts_match_header(lib):
     assert ctypes.sizeof(B.cascade_config) == 7 * 4 + 16 * 4 * 2 + 3 * 4 + 3 * 4 + 4 + 4 + 2 * 4
     assert ctypes.sizeof(B.cascade_init_state) == 4 * 8 + 17 * 4 + 4 + 2 * 8
     assert ctypes.sizeof(B.cascade_state_view) == 9 * 8 + 17 * 4 + 16 * 4 + 4 + 2 * 16 * 8 + 2 * 8 + 4 * 4
-    assert ctypes.sizeof(B.cascade_ceilings) == 2 * 4 + 7 * 8
+    assert ctypes.sizeof(B.cascade_ceilings) == 2 * 4 + 8 * 8
 
 
 @pytest.mark.parametrize("kw,code", [
