@@ -283,8 +283,10 @@ extern "C" int cascade_init(const cascade_config* cfg, void* dev_workspace, size
     if (rc != CASCADE_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
     // zero the cache (rows of empty slots are read, masked, by the attention tiles) and scratch
-    const hipError_t e = hipMemsetAsync(dev_workspace, 0, need.state + need.shared, s);
-    if (e != hipSuccess) return hip_check(nullptr, e, "cascade_init: memset");
+    // (by a fill kernel, not hipMemsetAsync: a caller may be capturing the stream into a graph)
+    launch_fill_i32((int32_t*)dev_workspace, (need.state + need.shared) / 4, 0, s);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_check(nullptr, e, "cascade_init: clearing the workspace");
     char* base = (char*)dev_workspace;
     return init_context("cascade_init", cfg, g, base, base + need.state, true, init_state, st, total, s, out_ctx);
 }
@@ -311,8 +313,9 @@ extern "C" int cascade_init_layers(const cascade_config* cfg, int32_t n_layers, 
         if (rc != CASCADE_OK) return rc;
     }
     hipStream_t s = (hipStream_t)stream;
-    const hipError_t e = hipMemsetAsync(dev_workspace, 0, total, s);
-    if (e != hipSuccess) return hip_check(nullptr, e, "cascade_init_layers: memset");
+    launch_fill_i32((int32_t*)dev_workspace, total / 4, 0, s);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_check(nullptr, e, "cascade_init_layers: clearing the workspace");
     char* base = (char*)dev_workspace;
     char* shared = base + need.state * (size_t)n_layers;
     for (int i = 0; i < n_layers; ++i) {
@@ -400,8 +403,9 @@ extern "C" int cascade_init_static(const cascade_config* cfg, const cascade_init
     ctx->is_static = true;
     hipStream_t s = (hipStream_t)stream;
     // the array keeps what the last context left: everything this one reads before writing starts from zero
-    e = hipMemsetAsync(base, 0, need.state + need.shared, s);
-    if (e != hipSuccess) return hip_check(nullptr, e, "cascade_init_static: memset");
+    launch_fill_i32((int32_t*)base, (need.state + need.shared) / 4, 0, s);      // (a fill kernel: safe under a stream capture)
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_check(nullptr, e, "cascade_init_static: clearing the workspace");
     return init_context("cascade_init_static", cfg, g, base, base + need.state, true, init_state, st, total, s, out_ctx, ctx);
 }
 
