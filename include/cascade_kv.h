@@ -308,8 +308,8 @@ typedef struct cascade_ceilings {
     double read_with_stores_gb_s;
     double two_pass_read_gb_s;  /* a read with stores on one half of the buffer followed by a plain read of the other half
                                    (the two passes of a decode step as traffic alone), pairs back to back: bytes read by both
-                                   per second.  Below the mean of the two rates measured alone: what the first launch wrote
-                                   is still on its way to memory while the second reads. */
+                                   per second (what the first launch wrote may still be on its way to memory while the
+                                   second reads). */
 } cascade_ceilings;
 int cascade_measure_ceilings(void* dev_buffer, size_t bytes, void* stream, cascade_ceilings* out);
 

@@ -166,8 +166,8 @@ extern "C" int cascade_measure_ceilings(void* dev_buffer, size_t bytes, void* st
         out->read_with_stores_gb_s = (double)per_wg16 * wgs_r * 16 / (ms * 1e-3) / 1e9;   // bytes read only
         // The two passes of a decode step one after the other, as traffic alone: a read with stores (the keys,
         // the logits written) on one half of the buffer, then a plain read (the values) on the other half,
-        // eight such pairs back to back.  What the first launch wrote is still on its way to memory while the
-        // second reads, so a pair takes longer than its two launches measured alone.
+        // eight such pairs back to back (what the first launch wrote may still be on its way to memory while the
+        // second reads).
         const size_t half16 = ((full / 2) / 16) & ~(size_t)255;
         const size_t per_a16 = ((half16 * 15 / 16) / wgs_r) & ~(size_t)4095;
         const size_t per_b16 = (half16 / wgs_r) & ~(size_t)4095;
