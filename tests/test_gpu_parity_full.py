@@ -130,30 +130,34 @@ def test_prefill_paper_16k_all_rows_in_scores(oracle_mod, mode):
     run.close()
 
 
-@pytest.mark.parametrize("name,n_chunks,compare,kv_heads", [
+@pytest.mark.parametrize("name,n_chunks,compare,kv_heads,mode", [
     # 8 cascades of 4096: at chunk 20 three cascades are full, the fourth is filling
-    ("prefill_passkey_32k", 21, (20,), [1, 6]),
+    ("prefill_passkey_32k", 21, (20,), [1, 6], "exact"),
+    # the same with the single-pass scores of Alg. 3 (many segments and query rotations in one sweep)
+    ("prefill_passkey_32k", 21, (20,), [1, 6], "single_pass"),
     # 8 cascades of 8192: at chunk 36 cascades 1-2 are full (many query rotations in one step)
-    ("prefill_passkey_65k", 37, (36,), [2, 7]),
+    ("prefill_passkey_65k", 37, (36,), [2, 7], "exact"),
     # stride 512 into an 8K cache: a chunk in steady state and the ragged last chunk (64 tokens)
-    ("prefill_longbench_8k", 79, (60, 78), [0, 4]),
+    ("prefill_longbench_8k", 79, (60, 78), [0, 4], "exact"),
 ])
-def test_other_experiment_geometries(oracle_mod, name, n_chunks, compare, kv_heads):
+def test_other_experiment_geometries(oracle_mod, name, n_chunks, compare, kv_heads, mode):
     """Cache geometries of the paper's passkey (Section 4.4) and long-context-understanding
     (Section 4.3) experiments with its EMA decay: the compared chunks whole on two KV heads,
     one step ahead of the GPU state."""
     from gpu_harness import ParityRun
     from paper_2406_17808_amd.cache import config_of
     wl = WORKLOADS[name]
-    cfg = config_of(wl, keep_update_scores=1)
+    sp = mode == "single_pass"
+    cfg = config_of(wl, keep_update_scores=1, score_mode=B.CASCADE_SCORES_SINGLE_PASS if sp else B.CASCADE_SCORES_EXACT)
     run = ParityRun(cfg, one_step_ahead=True, kv_heads=kv_heads)
     for c in range(n_chunks):
         dq, dk, dv = chunk_inputs_torch(wl, 0, c, "cuda:0")
         if c in compare:
             run.sync_oracle_from_gpu()
-            print(f"{name}: comparing chunk {c} ({dq.shape[1]} tokens)", flush=True)
+            print(f"{name} ({mode}): comparing chunk {c} ({dq.shape[1]} tokens)", flush=True)
             rep = run.step(_host(dq), _host(dk), _host(dv), threaded=True)
-            print(f"{name}: chunk {c}: out {rep.out_err:.3e} score {rep.score_err:.3e} drift {rep.drift}/{rep.compared}", flush=True)
+            print(f"{name} ({mode}): chunk {c}: out {rep.out_err:.3e} score {rep.score_err:.3e} drift {rep.drift}/{rep.compared}", flush=True)
+            assert rep.single_pass == sp
             assert rep.replay_exact and rep.flips_mismatch == 0, rep
             assert rep.out_err <= TOL_OUT and rep.score_err <= TOL_SCORE
         else:
