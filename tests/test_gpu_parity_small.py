@@ -400,6 +400,44 @@ def test_single_pass_scores(oracle_mod, case, monkeypatch):
     run.close()
 
 
+@pytest.mark.parametrize("seed", list(range(8)))
+def test_random_single_pass(oracle_mod, seed, monkeypatch):
+    """Seeded random geometries with score_mode single_pass: chunks of 256, 512 and 768 tokens take the
+    column sums inside the attention kernel (rings that are no multiples of a tile, several row blocks per
+    head, both head policies), ragged chunks and decode steps in between take the exact pass."""
+    from gpu_harness import ParityRun
+    monkeypatch.setenv("CASCADE_KV_ATTN_SPLITS", "1")
+    monkeypatch.setenv("CASCADE_KV_PACK_REUSE", str(seed % 2))
+    rng = np.random.default_rng(5000 + seed)
+    d = int(rng.choice([64, 128]))
+    hkv = int(rng.choice([1, 2]))
+    G = int(rng.choice([1, 2, 4]))
+    N = int(rng.integers(1, 5))
+    sizes = [int(rng.integers(40, 400)) for _ in range(N)]
+    max_chunk = int(rng.choice([256, 512, 768]))
+    cfg = B.make_config(batch=1, n_q_heads=hkv * G, n_kv_heads=hkv, head_dim=d,
+                        dtype=B.CASCADE_BF16, n_sink=int(rng.integers(0, 70)), cascade_sizes=sizes,
+                        ema_beta=float(rng.choice([0.999, 0.9999])), rope_base=10000.0, max_chunk=max_chunk,
+                        head_reduce=int(rng.integers(0, 2)), keep_update_scores=1,
+                        head_policy=int(rng.random() < 0.3), score_mode=B.CASCADE_SCORES_SINGLE_PASS)
+    tol_out, tol_score = _tolerances(cfg)
+    run = ParityRun(cfg, one_step_ahead=True)
+    worst_out = worst_score = 0.0
+    taken = 0
+    for step in range(6):
+        n = int(rng.choice([256, 512, 768, 100, 1]))
+        n = min(n, max_chunk)
+        q, k, v = _inputs(rng, cfg, n)
+        rep = run.step(q, k, v, decode=(n == 1 and rng.random() < 0.5))
+        assert rep.replay_exact, (seed, step)
+        assert rep.flips_mismatch == 0, (seed, step, rep)
+        taken += int(rep.single_pass)
+        worst_out, worst_score = max(worst_out, rep.out_err), max(worst_score, rep.score_err)
+    print(f"random single pass {seed}: d={d} heads {hkv * G}/{hkv} sizes {sizes} max_chunk {max_chunk}: out {worst_out:.3e} score {worst_score:.3e} taken {taken}")
+    assert worst_out <= tol_out and worst_score <= tol_score
+    run.close()
+
+
 def test_single_pass_needs_bf16():
     cfg = B.make_config(batch=1, n_q_heads=2, n_kv_heads=1, head_dim=64, dtype=B.CASCADE_F32, n_sink=1, cascade_sizes=[4],
                         ema_beta=0.9, rope_base=10000.0, max_chunk=8, score_mode=B.CASCADE_SCORES_SINGLE_PASS)
