@@ -278,6 +278,41 @@ def test_prefill_then_decode(oracle_mod, dtype, d, hq, hkv):
     run.close()
 
 
+@pytest.mark.parametrize("dtype,d,G,policy", [(B.CASCADE_BF16, 128, 4, 0), (B.CASCADE_BF16, 64, 2, 1)])
+def test_long_decode(oracle_mod, dtype, d, G, policy):
+    """Three hundred decode steps after one chunk, every step compared one step ahead: the rings of 37, 64
+    and 50 slots turn over several times, every acceptance phase of the three cascades comes up."""
+    from gpu_harness import ParityRun
+    cfg = B.make_config(batch=2, n_q_heads=2 * G, n_kv_heads=2, head_dim=d, dtype=dtype, n_sink=3,
+                        cascade_sizes=[37, 64, 50], ema_beta=0.97, rope_base=10000.0, max_chunk=64,
+                        keep_update_scores=1, head_policy=policy)
+    rng = np.random.default_rng(77)
+    run = ParityRun(cfg, one_step_ahead=True)
+    worst_out = worst_score = 0.0
+
+    def inputs(n):
+        sh_q = (cfg.batch, n, cfg.n_q_heads, d)
+        sh_k = (cfg.batch, n, cfg.n_kv_heads, d)
+        f = lambda sh: rng.standard_normal(sh).astype(np.float32)
+        q, k, v = f(sh_q), f(sh_k), f(sh_k)
+        if dtype == B.CASCADE_BF16:
+            from paper_2406_17808_amd.workloads import round_to_bf16
+            q, k, v = round_to_bf16(q), round_to_bf16(k), round_to_bf16(v)
+        return q, k, v
+
+    rep = run.step(*inputs(50))
+    for step in range(300):
+        rep = run.step(*inputs(1), decode=True)
+        assert rep.replay_exact, step
+        assert rep.flips_mismatch == 0, (step, rep)
+        worst_out, worst_score = max(worst_out, rep.out_err), max(worst_score, rep.score_err)
+    print(f"long decode dtype {dtype} d={d} G={G} head policy {policy}: out {worst_out:.3e} score {worst_score:.3e}")
+    tol_out, tol_score = _tolerances(cfg)
+    assert worst_out <= tol_out and worst_score <= tol_score
+    assert int(run.gpu.read_state().discards.sum()) > 100
+    run.close()
+
+
 @pytest.mark.parametrize("seed", list(range(12)))
 def test_random_geometries(oracle_mod, seed, monkeypatch):
     """Seeded random geometries (heads, head_dim, sinks, cascade count and sizes, periods, chunk
