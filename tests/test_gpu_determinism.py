@@ -31,15 +31,18 @@ def _one_run(wl, cfg, n_chunks, n_decode, outs):
     return st
 
 
-@pytest.mark.parametrize("name,n_chunks", [("prefill_32k", 32), ("prefill_paper_16k", 6)])
-def test_two_runs_give_the_same_bits(name, n_chunks):
+@pytest.mark.parametrize("name,n_chunks,mode", [("prefill_32k", 32, "exact"), ("prefill_paper_16k", 6, "exact"),
+                                                ("prefill_paper_16k", 6, "single_pass")])
+def test_two_runs_give_the_same_bits(name, n_chunks, mode):
     """prefill_32k whole (split attention launches, the narrow score kernel) and six chunks of the
-    paper's 16K geometry (unsplit attention, every row in the score sums), each followed by eight
-    decode steps, twice from fresh contexts: every output, score, id and cached row bit-equal."""
+    paper's 16K geometry (unsplit attention, every row in the score sums: by the exact pass, and by the
+    column sums inside the attention kernel, whose partial sums meet in LDS and in a per-row-block
+    array), each followed by eight decode steps, twice from fresh contexts: every output, score, id
+    and cached row bit-equal."""
     import torch
     from paper_2406_17808_amd.cache import config_of
     wl = WORKLOADS[name]
-    cfg = config_of(wl)
+    cfg = config_of(wl, score_mode=B.CASCADE_SCORES_SINGLE_PASS if mode == "single_pass" else B.CASCADE_SCORES_EXACT)
     outs_a, outs_b = [], []
     a = _one_run(wl, cfg, n_chunks, 8, outs_a)
     b = _one_run(wl, cfg, n_chunks, 8, outs_b)
